@@ -1,0 +1,352 @@
+/*
+ * sgns_oracle.c -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+ *
+ * A plain, slow, single-threaded CPU statement of what the skip-gram
+ * negative-sampling (SGNS) training path computes.  Only tests, the smoke
+ * check and the benchmark's cpu_baseline leg may build or call it; the GPU
+ * library shares no code, header, table or constant with this file.
+ *
+ * Source of each piece (FULL-W2V paper, by section):
+ *   - problem statement, sliding window of 2W words, N negatives drawn from
+ *     a weighted distribution ...................... Section 2.1
+ *   - the N negatives are drawn once per context window and shared by all of
+ *     its context words; the window pairs every context word with the N+1
+ *     "samples" (target + negatives) .............. Section 3.1, Figure 3,
+ *                                                    Figure 4 caption
+ *   - the update of a window is the sum over all pairings, order-free
+ *                                                    Section 3.1 (independence
+ *                                                    of negative samples)
+ *   - windows of one sentence are processed strictly in order
+ *                                                    Section 3.1 (last par.)
+ *   - traditional window width: random in [1, W]    Section 3.2
+ *   - the paper's own variant: fixed width ceil(W/2) Section 3.2
+ *   - sentences are independent units (Hogwild)     Section 2.2 / 2.3
+ *   - words with >= 5 occurrences, <= 1000 words per sentence: corpus
+ *     preparation, done by the caller ............... Table 3 caption
+ * Where the paper is silent (sampling distribution exponent, subsampling
+ * rule, learning-rate schedule, random numbers, weight initialisation) the
+ * conventions of the word2vec papers it cites are used; each such choice is
+ * spelled out next to the function that implements it.
+ *
+ * Build:  gcc -O2 -ffp-contract=off -fno-fast-math -shared -fPIC \
+ *             -DREAL=float  sgns_oracle.c -o liboracle_f32.so -lm
+ *         (and -DREAL=double for the gradient-check build)
+ *
+ * Parity pins (tests/test_oracle_*.py): published SplitMix64 outputs for the
+ * mixer, closed forms for table / thresholds / width, hand-computed windows,
+ * central finite differences of the window loss, brute-force enumeration on
+ * an 8-word vocabulary, untouched-row invariants.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifndef REAL
+#define REAL float
+#endif
+typedef REAL real_t;
+
+#define ORC_MAX_NEG 64
+#define ORC_MAX_CTX 64
+
+/* ------------------------------------------------------------------ */
+/* Random numbers: counter-based, keyed by (seed, epoch, position, j). */
+/* The mixer is the finaliser of the public-domain SplitMix64          */
+/* generator (Steele, Lea, Flood 2014): mix64(k*G), k=1,2,.. with      */
+/* seed 0 reproduces that generator's published output stream.         */
+/* ------------------------------------------------------------------ */
+static const uint64_t ORC_G = 0x9E3779B97F4A7C15ull;
+
+uint64_t orc_mix64(uint64_t z)
+{
+    z ^= z >> 30;
+    z *= 0xBF58476D1CE4E5B9ull;
+    z ^= z >> 27;
+    z *= 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    return z;
+}
+
+/* draw j of global (pre-subsampling) token position pos in epoch `epoch`:
+ *   j = 0  subsampling decision, j = 1 window width, j = 2+k negative k. */
+uint64_t orc_draw(uint64_t seed, uint32_t epoch, uint64_t pos, uint32_t j)
+{
+    uint64_t key  = orc_mix64(seed + ORC_G * ((uint64_t)epoch + 1u));
+    uint64_t base = orc_mix64(key ^ orc_mix64(pos));
+    return orc_mix64(base + ORC_G * ((uint64_t)j + 1u));
+}
+
+static uint32_t u32_of(uint64_t draw) { return (uint32_t)(draw >> 32); }
+static uint32_t mulhi32(uint32_t a, uint32_t n) { return (uint32_t)(((uint64_t)a * (uint64_t)n) >> 32); }
+
+/* ------------------------------------------------------------------ */
+/* Negative-sampling distribution ("weighted distribution", Sec. 2.1). */
+/* weight_i = count_i^0.75 (Mikolov et al.), written as                */
+/* sqrt(c)*sqrt(sqrt(c)) so that only correctly rounded IEEE           */
+/* operations are involved.  The distribution is quantised onto        */
+/* `tsz` equal slots: word i owns slots [end[i-1], end[i]).            */
+/* ------------------------------------------------------------------ */
+int orc_table_ends(const uint64_t *counts, uint32_t V, uint64_t tsz, uint64_t *end)
+{
+    double total = 0.0;
+    for (uint32_t i = 0; i < V; ++i) {
+        double c = (double)counts[i];
+        total += sqrt(c) * sqrt(sqrt(c));
+    }
+    if (!(total > 0.0)) return -1;
+    double cum = 0.0;
+    for (uint32_t i = 0; i < V; ++i) {
+        double c = (double)counts[i];
+        cum += sqrt(c) * sqrt(sqrt(c));
+        double e = floor((cum / total) * (double)tsz);
+        uint64_t ei = (uint64_t)e;
+        if (ei > tsz) ei = tsz;
+        end[i] = ei;
+    }
+    end[V - 1] = tsz;
+    return 0;
+}
+
+/* word that owns slot `slot`: the smallest i with end[i] > slot. */
+int32_t orc_word_of_slot(const uint64_t *end, uint32_t V, uint64_t slot)
+{
+    uint32_t lo = 0, hi = V - 1;
+    while (lo < hi) {
+        uint32_t mid = lo + (hi - lo) / 2;
+        if (end[mid] > slot) hi = mid; else lo = mid + 1;
+    }
+    return (int32_t)lo;
+}
+
+int32_t orc_negative(const uint64_t *end, uint32_t V, uint64_t tsz,
+                     uint64_t seed, uint32_t epoch, uint64_t pos, uint32_t k)
+{
+    uint32_t u = u32_of(orc_draw(seed, epoch, pos, 2u + k));
+    return orc_word_of_slot(end, V, (uint64_t)mulhi32(u, (uint32_t)tsz));
+}
+
+/* ------------------------------------------------------------------ */
+/* Frequent-word subsampling (Mikolov et al. 2013, the "conventional   */
+/* hyperparameters" the paper's evaluation refers to):                 */
+/*   P_keep(w) = min(1, sqrt(t / f_w)),  f_w = count_w / sum(counts).  */
+/* Quantised to 32 bits; 0xFFFFFFFF means "always keep".               */
+/* ------------------------------------------------------------------ */
+void orc_thresholds(const uint64_t *counts, uint32_t V, double t, uint32_t *thr)
+{
+    double total = 0.0;
+    for (uint32_t i = 0; i < V; ++i) total += (double)counts[i];
+    for (uint32_t i = 0; i < V; ++i) {
+        if (!(t > 0.0) || counts[i] == 0) { thr[i] = 0xFFFFFFFFu; continue; }
+        double f = (double)counts[i] / total;
+        double p = sqrt(t / f);
+        if (p >= 1.0) { thr[i] = 0xFFFFFFFFu; continue; }
+        double q = floor(p * 4294967296.0);
+        thr[i] = (q >= 4294967295.0) ? 0xFFFFFFFFu : (uint32_t)q;
+    }
+}
+
+int orc_keep(const uint32_t *thr, int32_t w, uint64_t seed, uint32_t epoch, uint64_t pos)
+{
+    uint32_t t = thr[w];
+    if (t == 0xFFFFFFFFu) return 1;
+    return u32_of(orc_draw(seed, epoch, pos, 0)) < t;
+}
+
+/* window width: uniform on {1..W} (mode 0, Sec. 3.2 "traditional") or
+ * the fixed ceil(W/2) of the paper's own variant (mode 1). */
+uint32_t orc_width(uint32_t W, uint32_t mode, uint64_t seed, uint32_t epoch, uint64_t pos)
+{
+    if (mode == 1) return (W + 1u) / 2u;
+    return 1u + mulhi32(u32_of(orc_draw(seed, epoch, pos, 1)), W);
+}
+
+/* ------------------------------------------------------------------ */
+/* Learning rate of a sentence: linear decay over all epochs, from the */
+/* global offset of the sentence's first token (schedule-independent). */
+/* ------------------------------------------------------------------ */
+float orc_lr(double lr0, double lr_min_frac, uint32_t epoch, uint32_t total_epochs,
+             uint64_t tokens_per_epoch, uint64_t sentence_start)
+{
+    double done = (double)((uint64_t)epoch * tokens_per_epoch + sentence_start);
+    double all  = (double)((uint64_t)total_epochs * tokens_per_epoch);
+    double frac = 1.0 - done / all;
+    if (frac < lr_min_frac) frac = lr_min_frac;
+    return (float)(lr0 * frac);
+}
+
+/* ------------------------------------------------------------------ */
+/* Initial weights: syn0 ~ U(-0.5/d, 0.5/d) from the seed, syn1neg = 0 */
+/* ------------------------------------------------------------------ */
+void orc_init_weights(uint64_t seed, uint32_t V, uint32_t d, real_t *syn0, real_t *syn1neg)
+{
+    uint64_t k = orc_mix64(seed ^ 0x696E6974ull);
+    for (uint64_t i = 0; i < (uint64_t)V; ++i)
+        for (uint64_t j = 0; j < d; ++j) {
+            uint32_t u = u32_of(orc_mix64(k + (i * d + j)));
+            double r = ((double)(u >> 8) * (1.0 / 16777216.0) - 0.5) / (double)d;
+            syn0[i * d + j] = (real_t)(float)r;
+        }
+    memset(syn1neg, 0, sizeof(real_t) * (size_t)V * d);
+}
+
+/* ------------------------------------------------------------------ */
+/* One context window = one minibatch SGD step on                      */
+/*   L_win = sum_c [ softplus(-<I_c,O_0>) + sum_{k>=1} m_k softplus(<I_c,O_k>) ] */
+/* I_c = syn0[ctx[c]] (context words), O_0 = syn1neg[target],          */
+/* O_k = syn1neg[negative k]; m_k = 0 when negative k is the target.   */
+/* All dot products use the values the rows had when the window began; */
+/* the summed update is applied at the end (Sec. 3.1).  A row that     */
+/* occurs several times receives the sum of its deltas.                */
+/* ------------------------------------------------------------------ */
+static real_t sigmoid_r(real_t x) { return (real_t)1 / ((real_t)1 + (real_t)exp(-(double)x)); }
+static double softplus_d(double x) { return (x > 0 ? x : 0) + log1p(exp(-fabs(x))); }
+
+void orc_window_step(real_t *syn0, real_t *syn1neg, uint32_t d,
+                     const int32_t *ctx, uint32_t nctx,
+                     const int32_t *out, uint32_t nout,   /* out[0] = target */
+                     real_t alpha, double *loss_sum)
+{
+    real_t g[ORC_MAX_CTX][ORC_MAX_NEG + 1];
+    real_t *dI = (real_t *)calloc((size_t)nctx * d, sizeof(real_t));
+    real_t *dO = (real_t *)calloc((size_t)nout * d, sizeof(real_t));
+    for (uint32_t c = 0; c < nctx; ++c) {
+        const real_t *I = syn0 + (size_t)ctx[c] * d;
+        for (uint32_t k = 0; k < nout; ++k) {
+            const real_t *O = syn1neg + (size_t)out[k] * d;
+            int masked = (k >= 1 && out[k] == out[0]);
+            real_t x = 0;
+            for (uint32_t j = 0; j < d; ++j) x += I[j] * O[j];
+            real_t label = (k == 0) ? (real_t)1 : (real_t)0;
+            g[c][k] = masked ? (real_t)0 : alpha * (label - sigmoid_r(x));
+            if (!masked && loss_sum) *loss_sum += softplus_d(k == 0 ? -(double)x : (double)x);
+        }
+    }
+    for (uint32_t c = 0; c < nctx; ++c)
+        for (uint32_t k = 0; k < nout; ++k) {
+            const real_t *I = syn0 + (size_t)ctx[c] * d;
+            const real_t *O = syn1neg + (size_t)out[k] * d;
+            for (uint32_t j = 0; j < d; ++j) {
+                dI[(size_t)c * d + j] += g[c][k] * O[j];
+                dO[(size_t)k * d + j] += g[c][k] * I[j];
+            }
+        }
+    for (uint32_t c = 0; c < nctx; ++c) {
+        real_t *I = syn0 + (size_t)ctx[c] * d;
+        for (uint32_t j = 0; j < d; ++j) I[j] += dI[(size_t)c * d + j];
+    }
+    for (uint32_t k = 0; k < nout; ++k) {
+        real_t *O = syn1neg + (size_t)out[k] * d;
+        for (uint32_t j = 0; j < d; ++j) O[j] += dO[(size_t)k * d + j];
+    }
+    free(dI);
+    free(dO);
+}
+
+/* The other reading of Sec. 4.2 ("pair one sample with all the context
+ * words, then iterate over the samples") with every pairing applied at
+ * once.  Only used to show that the choice of reading does not move the
+ * final loss / neighbour recovery beyond seed noise. */
+void orc_window_step_immediate(real_t *syn0, real_t *syn1neg, uint32_t d,
+                               const int32_t *ctx, uint32_t nctx,
+                               const int32_t *out, uint32_t nout,
+                               real_t alpha, double *loss_sum)
+{
+    for (uint32_t k = 0; k < nout; ++k) {
+        if (k >= 1 && out[k] == out[0]) continue;
+        real_t *O = syn1neg + (size_t)out[k] * d;
+        for (uint32_t c = 0; c < nctx; ++c) {
+            real_t *I = syn0 + (size_t)ctx[c] * d;
+            real_t x = 0;
+            for (uint32_t j = 0; j < d; ++j) x += I[j] * O[j];
+            real_t gg = alpha * (((k == 0) ? (real_t)1 : (real_t)0) - sigmoid_r(x));
+            if (loss_sum) *loss_sum += softplus_d(k == 0 ? -(double)x : (double)x);
+            for (uint32_t j = 0; j < d; ++j) {
+                real_t ij = I[j];
+                I[j] += gg * O[j];
+                O[j] += gg * ij;
+            }
+        }
+    }
+}
+
+/* ------------------------------------------------------------------ */
+/* One epoch, sentences in order, windows in order.                    */
+/* ------------------------------------------------------------------ */
+typedef struct orc_params {
+    uint32_t vocab, dim, window, negatives;
+    uint32_t window_mode;      /* 0 random width, 1 fixed ceil(W/2)        */
+    uint32_t update_mode;      /* 0 window minibatch, 1 immediate pairings */
+    uint32_t total_epochs, epoch;
+    uint64_t tokens_per_epoch, first_token_global_pos, seed, table_size;
+    double lr0, lr_min_frac;
+} orc_params;
+
+/* Optional dumps (any may be NULL), indexed by token offset in `tokens`:
+ *   keep_out[T] 1/0, width_out[T] (0 where dropped), neg_out[T*N] (-1 where dropped). */
+int orc_train_range(const orc_params *P, real_t *syn0, real_t *syn1neg,
+                    const uint64_t *table_end, const uint32_t *thr,
+                    const int32_t *tokens, const uint64_t *sent_off,
+                    uint64_t s_begin, uint64_t s_end, uint64_t s_stride,
+                    double *loss_sum, uint64_t *pairs,
+                    uint8_t *keep_out, uint8_t *width_out, int32_t *neg_out)
+{
+    const uint32_t W = P->window, N = P->negatives, V = P->vocab;
+    if (N > ORC_MAX_NEG || 2 * W > ORC_MAX_CTX) return -1;
+    int32_t *kw = NULL; uint64_t *kp = NULL; size_t cap = 0;
+    for (uint64_t s = s_begin; s < s_end; s += s_stride) {
+        uint64_t a = sent_off[s], b = sent_off[s + 1];
+        if (b - a > cap) {
+            cap = (size_t)(b - a);
+            kw = (int32_t *)realloc(kw, cap * sizeof(int32_t));
+            kp = (uint64_t *)realloc(kp, cap * sizeof(uint64_t));
+        }
+        float alpha = orc_lr(P->lr0, P->lr_min_frac, P->epoch, P->total_epochs,
+                             P->tokens_per_epoch, P->first_token_global_pos + a);
+        size_t nk = 0;
+        for (uint64_t t = a; t < b; ++t) {
+            int32_t w = tokens[t];
+            uint64_t pos = P->first_token_global_pos + t;
+            int keep = (w >= 0 && (uint32_t)w < V) && orc_keep(thr, w, P->seed, P->epoch, pos);
+            if (keep_out) keep_out[t] = (uint8_t)keep;
+            if (width_out) width_out[t] = 0;
+            if (neg_out) for (uint32_t k = 0; k < N; ++k) neg_out[t * N + k] = -1;
+            if (keep) { kw[nk] = w; kp[nk] = t; ++nk; }
+        }
+        for (size_t i = 0; i < nk; ++i) {
+            uint64_t pos = P->first_token_global_pos + kp[i];
+            uint32_t bw = orc_width(W, P->window_mode, P->seed, P->epoch, pos);
+            int32_t out[ORC_MAX_NEG + 1];
+            out[0] = kw[i];
+            for (uint32_t k = 0; k < N; ++k)
+                out[1 + k] = orc_negative(table_end, V, P->table_size, P->seed, P->epoch, pos, k);
+            if (width_out) width_out[kp[i]] = (uint8_t)bw;
+            if (neg_out) for (uint32_t k = 0; k < N; ++k) neg_out[kp[i] * N + k] = out[1 + k];
+            int32_t ctx[ORC_MAX_CTX]; uint32_t nctx = 0;
+            for (int64_t j = (int64_t)i - (int64_t)bw; j <= (int64_t)i + (int64_t)bw; ++j) {
+                if (j < 0 || j >= (int64_t)nk || j == (int64_t)i) continue;
+                ctx[nctx++] = kw[j];
+            }
+            if (nctx == 0) continue;
+            if (P->update_mode == 0)
+                orc_window_step(syn0, syn1neg, P->dim, ctx, nctx, out, N + 1, (real_t)alpha, loss_sum);
+            else
+                orc_window_step_immediate(syn0, syn1neg, P->dim, ctx, nctx, out, N + 1, (real_t)alpha, loss_sum);
+            if (pairs) *pairs += nctx;
+        }
+    }
+    free(kw); free(kp);
+    return 0;
+}
+
+int orc_train_epoch(const orc_params *P, real_t *syn0, real_t *syn1neg,
+                    const uint64_t *table_end, const uint32_t *thr,
+                    const int32_t *tokens, const uint64_t *sent_off, uint64_t n_sent,
+                    double *loss_sum, uint64_t *pairs,
+                    uint8_t *keep_out, uint8_t *width_out, int32_t *neg_out)
+{
+    return orc_train_range(P, syn0, syn1neg, table_end, thr, tokens, sent_off,
+                           0, n_sent, 1, loss_sum, pairs, keep_out, width_out, neg_out);
+}
+
+uint32_t orc_real_size(void) { return (uint32_t)sizeof(real_t); }
