@@ -1,0 +1,138 @@
+/*
+ * w2v.h -- C ABI of the MI355X-native SGNS (skip-gram, negative sampling) trainer.
+ *
+ * The library trains the two word2vec matrices with the window scheme of the FULL-W2V
+ * paper: the N negatives are drawn once per context window and shared by all of its
+ * context words, the N+1 output rows (target + negatives) live in registers for the
+ * window, the context rows live in an on-chip ring for as long as the window can reach
+ * them, sentences are independent lock-free units (Sections 2.1, 3.1, 3.2, 4.2).
+ *
+ * Conventions
+ *   - C99; no C++ types and no exceptions cross this boundary.
+ *   - Every function returns W2V_OK (0) or a negative W2V_E* code; the text of the last
+ *     error of a context is available from w2v_last_error().
+ *   - "device" pointers are HIP device memory valid on cfg.device; "host" pointers are
+ *     ordinary process memory.  The CALLER owns every device buffer and the stream; the
+ *     library owns only the host-side context object and never allocates device memory.
+ *   - All argument validation happens before the first HIP call, so every W2V_EINVAL /
+ *     W2V_ESTATE / W2V_ENOMEM path can be exercised on a machine without a GPU.
+ *   - One context is used by one host thread at a time.  Work is enqueued on cfg.stream;
+ *     functions documented as "asynchronous" return before the GPU has finished.
+ */
+#ifndef W2V_H
+#define W2V_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define W2V_OK      0
+#define W2V_EINVAL -1   /* null pointer, value out of range, struct_size mismatch           */
+#define W2V_ESTATE -2   /* call out of order (training before the unigram table was built) */
+#define W2V_ENOMEM -3   /* caller-provided workspace too small                              */
+#define W2V_EHIP   -4   /* a HIP runtime call failed; see w2v_last_error()                   */
+
+#define W2V_MAX_DIM        512u        /* largest supported embedding size d                  */
+#define W2V_MAX_WINDOW     16u         /* largest W                                           */
+#define W2V_MAX_NEGATIVES  20u         /* largest N (the paper's range is N in [2,20], Sec. 2.1) */
+#define W2V_MAX_VOCAB      (1u << 27)  /* word ids must fit 27 bits                           */
+
+typedef struct w2v_ctx w2v_ctx;        /* opaque */
+
+/* Hyper-parameters follow the problem statement of Section 2.1 (vocabulary V, dimension
+ * d, window W, negatives N); learning-rate schedule and subsampling are the conventional
+ * word2vec ones the evaluation section refers to. */
+typedef struct w2v_config {
+    uint32_t struct_size;         /* = sizeof(w2v_config)                                               */
+    uint32_t vocab;               /* V in [1, W2V_MAX_VOCAB]                                            */
+    uint32_t dim;                 /* d in [1, W2V_MAX_DIM]                                              */
+    uint32_t window;              /* W in [1, W2V_MAX_WINDOW]; dim*window must not exceed 512*10        */
+    uint32_t negatives;           /* N in [0, W2V_MAX_NEGATIVES]                                        */
+    uint32_t window_mode;         /* 0: width of each window drawn uniformly from [1,W] (Sec. 3.2,
+                                     "traditional"); 1: fixed width ceil(W/2) (Sec. 3.2, the paper's) */
+    uint32_t total_epochs;        /* E >= 1, length of the learning-rate decay                          */
+    uint32_t sentences_in_flight; /* 0: as many sentences at once as the GPU holds (lock-free, Sec. 2.2);
+                                     k >= 1: at most k at once; 1 = strict corpus order, deterministic */
+    uint64_t tokens_per_epoch;    /* T >= 1, corpus tokens per epoch before subsampling                 */
+    uint64_t seed;                /* keys every random decision and the weight initialisation          */
+    double   lr0;                 /* starting learning rate (0.025)                                     */
+    double   lr_min_frac;         /* floor of the decay as a fraction of lr0 (1e-4)                     */
+    double   subsample_t;         /* frequent-word subsampling threshold t; 0 switches it off           */
+    void    *syn0;                /* device, float[vocab*ld]: input (context-word) embeddings           */
+    void    *syn1neg;             /* device, float[vocab*ld]: output (target / negative) weights        */
+    uint32_t ld;                  /* row stride in floats, >= dim and a multiple of 4; columns
+                                     dim..ld-1 are never read or written by training                    */
+    int32_t  device;              /* HIP device ordinal                                                 */
+    void    *stream;              /* hipStream_t owned by the caller (NULL = the default stream)        */
+    void    *workspace;           /* device scratch, 256-byte aligned, owned by the caller              */
+    uint64_t workspace_bytes;     /* >= w2v_query_workspace()                                           */
+} w2v_config;
+
+/* Row stride (in floats) that keeps every row aligned to 128-byte memory lines. */
+int w2v_query_ld(uint32_t dim, uint32_t *ld_out);
+
+/* Bytes of device workspace needed for cfg->vocab and a sampling table of table_size slots. */
+int w2v_query_workspace(const w2v_config *cfg, uint32_t table_size, uint64_t *bytes_out);
+
+/* Validates cfg, copies it, and (init_weights != 0) fills syn0 with U(-0.5/d, 0.5/d) values
+ * keyed by cfg->seed and syn1neg with zeros (asynchronous).  With init_weights == 0 the
+ * caller's buffers are used as they are.  *out receives the context on success. */
+int w2v_create(const w2v_config *cfg, int init_weights, w2v_ctx **out);
+
+/* Frees the context.  Waits for the stream; never frees caller-owned buffers. */
+int w2v_destroy(w2v_ctx *ctx);
+
+/* Builds the negative-sampling table (the "weighted distribution" of Sec. 2.1: word i owns a
+ * share count_i^0.75 of table_size slots) and the subsampling thresholds from the host array
+ * counts_host[vocab], and uploads both into the workspace.  table_size in [1, 2^31].
+ * Synchronous.  Must precede training. */
+int w2v_build_unigram_table(w2v_ctx *ctx, const uint64_t *counts_host, uint32_t table_size);
+
+/* One pass over n_sent sentences (Sec. 4.2: one sentence per execution unit, windows in strict
+ * order inside a sentence).  tokens_dev: device int32 word ids (ids outside [0,V) are skipped like
+ * subsampled words); sent_off_dev: device uint64[n_sent+1], sentence s is
+ * tokens[sent_off[s] .. sent_off[s+1]).  first_token_global_pos is the position of tokens_dev[0]
+ * inside the epoch (0 unless the epoch is fed in several calls); it enters the random-number key
+ * and the learning rate.  epoch < total_epochs.  Asynchronous. */
+int w2v_train_epoch(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_t *sent_off_dev,
+                    uint64_t n_sent, uint64_t first_token_global_pos, uint32_t epoch);
+
+/* Same arithmetic without any on-chip reuse: every (target, context) pairing re-reads and
+ * re-writes its context row, and the window's N+1 output rows go through global memory per
+ * context word.  Exists only as the memory-traffic comparator for w2v_train_epoch (the role
+ * the pre-existing GPU kernels play in Table 4).  Asynchronous. */
+int w2v_train_epoch_naive(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_t *sent_off_dev,
+                          uint64_t n_sent, uint64_t first_token_global_pos, uint32_t epoch);
+
+/* Copies matrix `which` (0 = syn0, 1 = syn1neg) as a dense [vocab][dim] float array into dst
+ * (device memory if dst_is_device != 0, else host memory), dst_floats >= vocab*dim.
+ * Waits for the stream. */
+int w2v_get_embeddings(w2v_ctx *ctx, int which, float *dst, uint64_t dst_floats, int dst_is_device);
+
+/* Sum of the SGNS log-loss over all windows trained since the last reset (each window's loss is
+ * evaluated with the weights it started from) and the number of (context, target) pairs.
+ * Mean loss = *loss_sum / *positive_pairs.  Either output may be NULL.  Waits for the stream. */
+int w2v_loss(w2v_ctx *ctx, double *loss_sum, uint64_t *positive_pairs, int reset);
+
+/* Test surface: writes, for every token t of the given range, the integer decisions the trainer
+ * takes for it: keep_dev[t] (1 kept / 0 dropped), width_dev[t] (window width, 0 if dropped),
+ * neg_dev[t*N + k] (k-th negative word id, -1 if dropped).  Device outputs.  Asynchronous. */
+int w2v_debug_draws(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_t *sent_off_dev,
+                    uint64_t n_sent, uint64_t first_token_global_pos, uint32_t epoch,
+                    uint8_t *keep_dev, uint8_t *width_dev, int32_t *neg_dev);
+
+/* Test surface: runs the window kernel's cross-lane reduction on its own.  in_dev: device
+ * float[60*64], value m of lane l at in_dev[m*64 + l]; out_dev: device float[64], out_dev[l] =
+ * sum over lanes of value l for l < 60.  stream: hipStream_t or NULL.  Asynchronous. */
+int w2v_debug_reduce(const float *in_dev, float *out_dev, void *stream);
+
+/* Library-owned text of the last error of ctx (or of the last failed w2v_create when ctx is
+ * NULL); valid until the next call on the same context. */
+const char *w2v_last_error(const w2v_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* W2V_H */

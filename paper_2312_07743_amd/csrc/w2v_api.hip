@@ -1,0 +1,327 @@
+// Host side of the C ABI declared in include/w2v.h: argument validation, the host-built sampling
+// table and subsampling thresholds, kernel launches.  No device memory is allocated here: tables and
+// accumulators live in the caller's workspace.
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "w2v_internal.h"
+#include "w2v_rng.h"
+
+namespace w2v {
+
+static uint64_t align256(uint64_t x) { return (x + 255u) & ~(uint64_t)255u; }
+
+WorkspaceLayout workspace_layout(uint32_t vocab, uint32_t table_size)
+{
+    WorkspaceLayout l;
+    l.accum_off = 0;
+    l.thr_off = align256(sizeof(Accum));
+    l.table_off = l.thr_off + align256((uint64_t)vocab * sizeof(uint32_t));
+    l.total = l.table_off + align256((uint64_t)table_size * sizeof(int32_t));
+    return l;
+}
+
+}  // namespace w2v
+
+namespace {
+
+std::string g_create_error;
+
+int fail(w2v_ctx *ctx, int code, const std::string &msg)
+{
+    if (ctx) ctx->err = msg; else g_create_error = msg;
+    return code;
+}
+
+int fail_hip(w2v_ctx *ctx, hipError_t e, const char *what)
+{
+    return fail(ctx, W2V_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+#define HIP_TRY(ctx, expr)                                         \
+    do {                                                           \
+        hipError_t e_ = (expr);                                    \
+        if (e_ != hipSuccess) return fail_hip((ctx), e_, #expr);   \
+    } while (0)
+
+// returns an empty string when cfg is acceptable
+std::string check_config(const w2v_config *c)
+{
+    if (!c) return "cfg is NULL";
+    if (c->struct_size != sizeof(w2v_config)) return "cfg.struct_size does not match sizeof(w2v_config)";
+    if (c->vocab < 1 || c->vocab > W2V_MAX_VOCAB) return "cfg.vocab out of range [1, 2^27]";
+    if (c->dim < 1 || c->dim > W2V_MAX_DIM) return "cfg.dim out of range [1, 512]";
+    if (c->window < 1 || c->window > W2V_MAX_WINDOW) return "cfg.window out of range [1, 16]";
+    if (c->negatives > W2V_MAX_NEGATIVES) return "cfg.negatives out of range [0, 20]";
+    if (c->window_mode > 1) return "cfg.window_mode must be 0 or 1";
+    if (c->total_epochs < 1) return "cfg.total_epochs must be >= 1";
+    if (c->tokens_per_epoch < 1) return "cfg.tokens_per_epoch must be >= 1";
+    if (c->tokens_per_epoch > (1ull << 52) / c->total_epochs) return "total_epochs * tokens_per_epoch exceeds 2^52";
+    if (!(c->lr0 > 0.0) || !std::isfinite(c->lr0)) return "cfg.lr0 must be positive and finite";
+    if (!(c->lr_min_frac >= 0.0) || c->lr_min_frac > 1.0) return "cfg.lr_min_frac must be in [0, 1]";
+    if (!(c->subsample_t >= 0.0) || !std::isfinite(c->subsample_t)) return "cfg.subsample_t must be >= 0";
+    if (!c->syn0 || !c->syn1neg) return "cfg.syn0 / cfg.syn1neg is NULL";
+    if (c->ld < c->dim || (c->ld % 4u) != 0) return "cfg.ld must be >= dim and a multiple of 4";
+    if (c->device < 0) return "cfg.device must be >= 0";
+    if (!c->workspace) return "cfg.workspace is NULL";
+    if (((uintptr_t)c->workspace & 255u) != 0) return "cfg.workspace must be 256-byte aligned";
+    w2v::RowShape s;
+    if (!w2v::pick_row_shape(c->dim, c->ld, &s)) return "cfg.dim: no lane layout for this dimension";
+    if ((uint32_t)(64 * s.vw * s.r) * c->window > 512u * 10u)
+        return "cfg.dim * cfg.window too large (rows of more than 320 floats need window <= 10)";
+    return std::string();
+}
+
+w2v::KernelArgs kernel_args(const w2v_ctx *ctx, const int32_t *tokens, const uint64_t *sent_off, uint64_t n_sent,
+                            uint64_t first_pos, uint32_t epoch)
+{
+    const w2v_config &c = ctx->cfg;
+    unsigned char *ws = static_cast<unsigned char *>(c.workspace);
+    w2v::KernelArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.syn0 = static_cast<float *>(c.syn0);
+    a.syn1neg = static_cast<float *>(c.syn1neg);
+    a.tokens = tokens;
+    a.sent_off = sent_off;
+    a.table = reinterpret_cast<const int32_t *>(ws + ctx->ws.table_off);
+    a.thr = reinterpret_cast<const uint32_t *>(ws + ctx->ws.thr_off);
+    a.accum = reinterpret_cast<w2v::Accum *>(ws + ctx->ws.accum_off);
+    a.n_sent = n_sent;
+    a.first_pos = first_pos;
+    a.key = w2v::epoch_key(c.seed, epoch);
+    a.lr_done_base = (uint64_t)epoch * c.tokens_per_epoch;
+    a.lr_all = (uint64_t)c.total_epochs * c.tokens_per_epoch;
+    a.lr0 = c.lr0;
+    a.lr_min_frac = c.lr_min_frac;
+    a.vocab = c.vocab;
+    a.dim = c.dim;
+    a.ld = c.ld;
+    a.window = c.window;
+    a.negatives = c.negatives;
+    a.window_mode = c.window_mode;
+    a.table_size = ctx->table_size;
+    a.subsample = c.subsample_t > 0.0 ? 1u : 0u;
+    return a;
+}
+
+int check_train_call(w2v_ctx *ctx, const int32_t *tokens, const uint64_t *sent_off, uint64_t n_sent,
+                     uint64_t first_pos, uint32_t epoch)
+{
+    if (!ctx) return fail(nullptr, W2V_EINVAL, "ctx is NULL");
+    if (!ctx->table_built) return fail(ctx, W2V_ESTATE, "w2v_build_unigram_table must be called first");
+    if (epoch >= ctx->cfg.total_epochs) return fail(ctx, W2V_EINVAL, "epoch must be < cfg.total_epochs");
+    if (first_pos > ctx->cfg.tokens_per_epoch) return fail(ctx, W2V_EINVAL, "first_token_global_pos exceeds cfg.tokens_per_epoch");
+    if (n_sent && (!tokens || !sent_off)) return fail(ctx, W2V_EINVAL, "tokens_dev / sent_off_dev is NULL");
+    return W2V_OK;
+}
+
+hipStream_t stream_of(const w2v_ctx *ctx) { return static_cast<hipStream_t>(ctx->cfg.stream); }
+
+}  // namespace
+
+extern "C" {
+
+int w2v_query_ld(uint32_t dim, uint32_t *ld_out)
+{
+    if (!ld_out || dim < 1 || dim > W2V_MAX_DIM) return W2V_EINVAL;
+    *ld_out = (dim + 31u) & ~31u;     // 32 floats = one 128-byte line
+    return W2V_OK;
+}
+
+int w2v_query_workspace(const w2v_config *cfg, uint32_t table_size, uint64_t *bytes_out)
+{
+    if (!cfg || !bytes_out || cfg->vocab < 1 || cfg->vocab > W2V_MAX_VOCAB || table_size < 1 || table_size > (1u << 31))
+        return W2V_EINVAL;
+    *bytes_out = w2v::workspace_layout(cfg->vocab, table_size).total;
+    return W2V_OK;
+}
+
+int w2v_create(const w2v_config *cfg, int init_weights, w2v_ctx **out)
+{
+    if (!out) return fail(nullptr, W2V_EINVAL, "out is NULL");
+    *out = nullptr;
+    const std::string why = check_config(cfg);
+    if (!why.empty()) return fail(nullptr, W2V_EINVAL, why);
+    const w2v::WorkspaceLayout minimal = w2v::workspace_layout(cfg->vocab, 1);
+    if (cfg->workspace_bytes < minimal.total) return fail(nullptr, W2V_ENOMEM, "cfg.workspace_bytes is smaller than w2v_query_workspace()");
+    w2v_ctx *ctx = new (std::nothrow) w2v_ctx();
+    if (!ctx) return fail(nullptr, W2V_ENOMEM, "out of host memory");
+    ctx->cfg = *cfg;
+    ctx->ws = minimal;
+    hipError_t e = hipSetDevice(cfg->device);
+    if (e == hipSuccess)
+        e = w2v::launch_reset_accum(reinterpret_cast<w2v::Accum *>(static_cast<unsigned char *>(cfg->workspace)), 2, stream_of(ctx));
+    if (e == hipSuccess && init_weights)
+        e = w2v::launch_init_weights(static_cast<float *>(cfg->syn0), static_cast<float *>(cfg->syn1neg), cfg->vocab,
+                                     cfg->dim, cfg->ld, cfg->seed, stream_of(ctx));
+    if (e != hipSuccess) {
+        fail_hip(nullptr, e, "w2v_create");
+        delete ctx;
+        return W2V_EHIP;
+    }
+    *out = ctx;
+    return W2V_OK;
+}
+
+int w2v_destroy(w2v_ctx *ctx)
+{
+    if (!ctx) return W2V_EINVAL;
+    int rc = W2V_OK;
+    if (hipSetDevice(ctx->cfg.device) != hipSuccess || hipStreamSynchronize(stream_of(ctx)) != hipSuccess) rc = W2V_EHIP;
+    delete ctx;
+    return rc;
+}
+
+int w2v_build_unigram_table(w2v_ctx *ctx, const uint64_t *counts_host, uint32_t table_size)
+{
+    if (!ctx) return fail(nullptr, W2V_EINVAL, "ctx is NULL");
+    if (!counts_host) return fail(ctx, W2V_EINVAL, "counts_host is NULL");
+    if (table_size < 1 || table_size > (1u << 31)) return fail(ctx, W2V_EINVAL, "table_size out of range [1, 2^31]");
+    const uint32_t V = ctx->cfg.vocab;
+    const w2v::WorkspaceLayout lay = w2v::workspace_layout(V, table_size);
+    if (ctx->cfg.workspace_bytes < lay.total) return fail(ctx, W2V_ENOMEM, "workspace too small for this table_size");
+
+    // share of word i: count_i^(3/4) = sqrt(c) * sqrt(sqrt(c)), accumulated in id order
+    double total_w = 0.0, total_c = 0.0;
+    for (uint32_t i = 0; i < V; ++i) {
+        const double c = (double)counts_host[i];
+        total_w += std::sqrt(c) * std::sqrt(std::sqrt(c));
+        total_c += c;
+    }
+    if (!(total_w > 0.0)) return fail(ctx, W2V_EINVAL, "all counts are zero");
+
+    std::vector<int32_t> table(table_size);
+    {
+        double cum = 0.0;
+        uint64_t begin = 0;
+        for (uint32_t i = 0; i < V; ++i) {
+            const double c = (double)counts_host[i];
+            cum += std::sqrt(c) * std::sqrt(std::sqrt(c));
+            uint64_t end = (uint64_t)std::floor((cum / total_w) * (double)table_size);
+            if (end > table_size || i == V - 1) end = table_size;
+            for (uint64_t sl = begin; sl < end; ++sl) table[sl] = (int32_t)i;
+            if (end > begin) begin = end;
+        }
+    }
+    // keep probability min(1, sqrt(t / f)), f = count / total, as a 32-bit threshold
+    std::vector<uint32_t> thr(V, 0xFFFFFFFFu);
+    const double t = ctx->cfg.subsample_t;
+    if (t > 0.0) {
+        for (uint32_t i = 0; i < V; ++i) {
+            if (counts_host[i] == 0) continue;
+            const double f = (double)counts_host[i] / total_c;
+            const double p = std::sqrt(t / f);
+            if (p >= 1.0) continue;
+            const double q = std::floor(p * 4294967296.0);
+            thr[i] = q >= 4294967295.0 ? 0xFFFFFFFFu : (uint32_t)q;
+        }
+    }
+
+    unsigned char *ws = static_cast<unsigned char *>(ctx->cfg.workspace);
+    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    HIP_TRY(ctx, hipStreamSynchronize(stream_of(ctx)));
+    HIP_TRY(ctx, hipMemcpy(ws + lay.thr_off, thr.data(), (size_t)V * sizeof(uint32_t), hipMemcpyHostToDevice));
+    HIP_TRY(ctx, hipMemcpy(ws + lay.table_off, table.data(), (size_t)table_size * sizeof(int32_t), hipMemcpyHostToDevice));
+    ctx->ws = lay;
+    ctx->table_size = table_size;
+    ctx->table_built = true;
+    return W2V_OK;
+}
+
+int w2v_train_epoch(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_t *sent_off_dev, uint64_t n_sent,
+                    uint64_t first_token_global_pos, uint32_t epoch)
+{
+    const int rc = check_train_call(ctx, tokens_dev, sent_off_dev, n_sent, first_token_global_pos, epoch);
+    if (rc != W2V_OK) return rc;
+    if (n_sent == 0) return W2V_OK;
+    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    const w2v::KernelArgs a = kernel_args(ctx, tokens_dev, sent_off_dev, n_sent, first_token_global_pos, epoch);
+    uint64_t waves = ctx->cfg.sentences_in_flight;
+    if (waves == 0) {
+        waves = w2v::train_resident_waves(a, ctx->cfg.device);
+        if (waves == 0) return fail(ctx, W2V_EHIP, "could not query kernel occupancy");
+    }
+    if (waves > n_sent) waves = n_sent;
+    HIP_TRY(ctx, w2v::launch_reset_accum(a.accum, 1, stream_of(ctx)));
+    HIP_TRY(ctx, w2v::launch_train(a, (uint32_t)waves, stream_of(ctx)));
+    return W2V_OK;
+}
+
+int w2v_train_epoch_naive(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_t *sent_off_dev, uint64_t n_sent,
+                          uint64_t first_token_global_pos, uint32_t epoch)
+{
+    const int rc = check_train_call(ctx, tokens_dev, sent_off_dev, n_sent, first_token_global_pos, epoch);
+    if (rc != W2V_OK) return rc;
+    if (n_sent == 0) return W2V_OK;
+    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    const w2v::KernelArgs a = kernel_args(ctx, tokens_dev, sent_off_dev, n_sent, first_token_global_pos, epoch);
+    uint64_t waves = ctx->cfg.sentences_in_flight;
+    if (waves == 0) {
+        waves = w2v::naive_resident_waves(ctx->cfg.device);
+        if (waves == 0) return fail(ctx, W2V_EHIP, "could not query kernel occupancy");
+    }
+    if (waves > n_sent) waves = n_sent;
+    HIP_TRY(ctx, w2v::launch_reset_accum(a.accum, 1, stream_of(ctx)));
+    HIP_TRY(ctx, w2v::launch_train_naive(a, (uint32_t)waves, stream_of(ctx)));
+    return W2V_OK;
+}
+
+int w2v_get_embeddings(w2v_ctx *ctx, int which, float *dst, uint64_t dst_floats, int dst_is_device)
+{
+    if (!ctx) return fail(nullptr, W2V_EINVAL, "ctx is NULL");
+    if (which != 0 && which != 1) return fail(ctx, W2V_EINVAL, "which must be 0 (syn0) or 1 (syn1neg)");
+    if (!dst) return fail(ctx, W2V_EINVAL, "dst is NULL");
+    const w2v_config &c = ctx->cfg;
+    if (dst_floats < (uint64_t)c.vocab * c.dim) return fail(ctx, W2V_EINVAL, "dst_floats is smaller than vocab*dim");
+    HIP_TRY(ctx, hipSetDevice(c.device));
+    const void *src = which == 0 ? c.syn0 : c.syn1neg;
+    HIP_TRY(ctx, hipMemcpy2DAsync(dst, (size_t)c.dim * sizeof(float), src, (size_t)c.ld * sizeof(float),
+                                  (size_t)c.dim * sizeof(float), c.vocab,
+                                  dst_is_device ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost, stream_of(ctx)));
+    HIP_TRY(ctx, hipStreamSynchronize(stream_of(ctx)));
+    return W2V_OK;
+}
+
+int w2v_loss(w2v_ctx *ctx, double *loss_sum, uint64_t *positive_pairs, int reset)
+{
+    if (!ctx) return fail(nullptr, W2V_EINVAL, "ctx is NULL");
+    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    w2v::Accum host;
+    w2v::Accum *dev = reinterpret_cast<w2v::Accum *>(static_cast<unsigned char *>(ctx->cfg.workspace) + ctx->ws.accum_off);
+    HIP_TRY(ctx, hipMemcpyAsync(&host, dev, sizeof(host), hipMemcpyDeviceToHost, stream_of(ctx)));
+    HIP_TRY(ctx, hipStreamSynchronize(stream_of(ctx)));
+    if (loss_sum) *loss_sum = host.loss_sum;
+    if (positive_pairs) *positive_pairs = host.pairs;
+    if (reset) HIP_TRY(ctx, w2v::launch_reset_accum(dev, 2, stream_of(ctx)));
+    return W2V_OK;
+}
+
+int w2v_debug_draws(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_t *sent_off_dev, uint64_t n_sent,
+                    uint64_t first_token_global_pos, uint32_t epoch, uint8_t *keep_dev, uint8_t *width_dev,
+                    int32_t *neg_dev)
+{
+    const int rc = check_train_call(ctx, tokens_dev, sent_off_dev, n_sent, first_token_global_pos, epoch);
+    if (rc != W2V_OK) return rc;
+    if (!keep_dev || !width_dev || (ctx->cfg.negatives && !neg_dev)) return fail(ctx, W2V_EINVAL, "an output pointer is NULL");
+    if (n_sent == 0) return W2V_OK;
+    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    uint64_t n_tokens = 0;
+    HIP_TRY(ctx, hipMemcpyAsync(&n_tokens, sent_off_dev + n_sent, sizeof(uint64_t), hipMemcpyDeviceToHost, stream_of(ctx)));
+    HIP_TRY(ctx, hipStreamSynchronize(stream_of(ctx)));
+    const w2v::KernelArgs a = kernel_args(ctx, tokens_dev, sent_off_dev, n_sent, first_token_global_pos, epoch);
+    HIP_TRY(ctx, w2v::launch_draws(a, n_tokens, keep_dev, width_dev, neg_dev, stream_of(ctx)));
+    return W2V_OK;
+}
+
+int w2v_debug_reduce(const float *in_dev, float *out_dev, void *stream)
+{
+    if (!in_dev || !out_dev) return W2V_EINVAL;
+    return w2v::launch_reduce_selftest(in_dev, out_dev, static_cast<hipStream_t>(stream)) == hipSuccess ? W2V_OK : W2V_EHIP;
+}
+
+const char *w2v_last_error(const w2v_ctx *ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
+
+}  // extern "C"

@@ -1,0 +1,71 @@
+// Internal declarations shared by the host API (w2v_api.hip) and the kernels (w2v_kernels.hip).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+
+#include "../../include/w2v.h"
+
+namespace w2v {
+
+// Device-side accumulators and the work counter, at the start of the caller's workspace.
+struct Accum {
+    double             loss_sum;       // sum of window losses
+    unsigned long long pairs;          // (context, target) pairs trained
+    unsigned long long next_sentence;  // work queue head of the current launch
+    unsigned long long dropped;        // tokens with ids outside [0, V)
+};
+
+// Layout of the caller-provided workspace (all offsets multiples of 256 bytes).
+struct WorkspaceLayout {
+    uint64_t accum_off, thr_off, table_off, total;
+};
+WorkspaceLayout workspace_layout(uint32_t vocab, uint32_t table_size);
+
+// Everything a training / draw kernel needs; passed by value.
+struct KernelArgs {
+    float             *syn0, *syn1neg;
+    const int32_t     *tokens;
+    const uint64_t    *sent_off;
+    const int32_t     *table;
+    const uint32_t    *thr;
+    Accum             *accum;
+    uint64_t           n_sent, first_pos, key;
+    uint64_t           lr_done_base;   // epoch * tokens_per_epoch
+    uint64_t           lr_all;         // total_epochs * tokens_per_epoch
+    double             lr0, lr_min_frac;
+    uint32_t           vocab, dim, ld, window, negatives, window_mode, table_size;
+    uint32_t           subsample;      // 0: every threshold is "always keep", thr is not read
+};
+
+// How a row of `dim` floats is spread over the 64 lanes of a wavefront: R chunks of VW
+// consecutive floats per lane, chunk r of lane l starting at float (r*64 + l)*VW.
+struct RowShape { int vw, r; };
+bool pick_row_shape(uint32_t dim, uint32_t ld, RowShape *out);
+
+// LDS bytes one wavefront (= one workgroup) of the window kernel needs.
+uint32_t train_lds_bytes(const KernelArgs &a, RowShape s);
+
+// Launchers (all asynchronous on `stream`).  Return hipSuccess or the launch error.
+hipError_t launch_init_weights(float *syn0, float *syn1neg, uint32_t vocab, uint32_t dim, uint32_t ld,
+                               uint64_t seed, hipStream_t stream);
+hipError_t launch_reset_accum(Accum *accum, int what /*1: work counter only, 2: everything*/, hipStream_t stream);
+hipError_t launch_train(const KernelArgs &a, uint32_t waves, hipStream_t stream);
+hipError_t launch_train_naive(const KernelArgs &a, uint32_t waves, hipStream_t stream);
+hipError_t launch_draws(const KernelArgs &a, uint64_t n_tokens_hint, uint8_t *keep, uint8_t *width, int32_t *neg,
+                        hipStream_t stream);
+hipError_t launch_reduce_selftest(const float *in, float *out, hipStream_t stream);
+// waves that fit the device at once for this configuration (0 on error)
+uint32_t train_resident_waves(const KernelArgs &a, int device);
+uint32_t naive_resident_waves(int device);
+
+}  // namespace w2v
+
+struct w2v_ctx {
+    w2v_config           cfg;
+    w2v::WorkspaceLayout ws;
+    uint32_t             table_size = 0;
+    bool                 table_built = false;
+    std::string          err;
+};

@@ -1,0 +1,625 @@
+// HIP kernels of the SGNS trainer for gfx950 (MI355X): weight initialisation, the draw dump
+// used by the parity tests, the window kernel (the hot path) and the no-reuse comparator.
+//
+// Window kernel in one paragraph (paper Sections 3.1, 3.2, 4.2, re-mapped to CDNA4):
+// one wavefront owns one sentence at a time (work queue over sentences, lock-free between
+// sentences).  The 64 lanes split every embedding row; the N+1 output rows of a window
+// (target + shared negatives) sit in VGPRs while the window lasts, the context rows sit in an
+// LDS ring from the moment the window span reaches them until it has passed them.  All
+// (context, output) dot products of a window are formed as per-lane partial sums and reduced
+// together by one transposing butterfly (v_permlane32_swap / v_permlane16_swap / DPP), after
+// which lane v holds pairing v and the sigmoid is evaluated lane-parallel.  The window's
+// update is the sum over all pairings evaluated at the values the rows had when the window
+// began.  Sampling decisions (subsampling, width, negatives) are computed lane-parallel for
+// 64 positions at a time from a counter-based generator.
+#include "w2v_internal.h"
+#include "w2v_rng.h"
+
+namespace w2v {
+namespace {
+
+constexpr int kLanes = 64;
+constexpr int KC = 6;              // output rows held in registers at once
+constexpr int CC = 10;             // context rows whose pairings are reduced together (CC*KC <= 64)
+constexpr int FCAP = 256;          // kept-token FIFO entries per wavefront (power of two)
+constexpr uint32_t kIdBits = 27;
+constexpr uint32_t kIdMask = (1u << kIdBits) - 1u;
+
+__device__ __forceinline__ uint32_t uni(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ uint64_t uni64(uint64_t v)
+{
+    return ((uint64_t)uni((uint32_t)(v >> 32)) << 32) | uni((uint32_t)v);
+}
+__device__ __forceinline__ float lane_value(float v, uint32_t lane)
+{
+    return __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(v), lane));
+}
+__device__ __forceinline__ uint32_t lane_value(uint32_t v, uint32_t lane) { return __builtin_amdgcn_readlane(v, lane); }
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+constexpr int kDppRowRor8 = 0x128, kDppHalfMirror = 0x141, kDppQuadXor2 = 0x4E, kDppQuadXor1 = 0xB1;
+
+// In-row stage of the transposing reduction: IN registers become ceil(IN/2); lanes whose index
+// has bit BIT set continue with the upper register of each pair.
+template <int IN, int BIT, int CTRL>
+__device__ __forceinline__ void row_stage(const float *in, float *out, int lane)
+{
+    constexpr int OUT = IN > BIT ? BIT : IN;
+    const bool up = (lane & BIT) != 0;
+#pragma unroll
+    for (int i = 0; i < OUT; ++i) {
+        const float a = in[i];
+        const float b = (i + BIT < IN) ? in[i + BIT] : 0.0f;
+        const float mine = up ? b : a;
+        const float theirs = up ? a : b;
+        out[i] = mine + dpp_move<CTRL>(theirs);
+    }
+}
+
+// Sums each of M per-lane values over the 64 lanes; lane v (v < M) returns the total of value v.
+template <int M>
+__device__ __forceinline__ float transpose_reduce(const float *v, int lane)
+{
+    static_assert(M >= 1 && M <= 64, "at most one value per lane");
+    constexpr int N32 = M < 32 ? M : 32;
+    constexpr int N16 = N32 < 16 ? N32 : 16;
+    constexpr int N8 = N16 < 8 ? N16 : 8;
+    constexpr int N4 = N8 < 4 ? N8 : 4;
+    constexpr int N2 = N4 < 2 ? N4 : 2;
+    float s32[N32], s16[N16], s8[N8], s4[N4], s2[N2], s1[1];
+#pragma unroll
+    for (int i = 0; i < N32; ++i) {   // halves: lanes >= 32 continue with value i+32
+        const float hi = (i + 32 < M) ? v[i + 32] : 0.0f;
+        auto p = __builtin_amdgcn_permlane32_swap(__float_as_uint(v[i]), __float_as_uint(hi), false, false);
+        s32[i] = __uint_as_float(p[0]) + __uint_as_float(p[1]);
+    }
+#pragma unroll
+    for (int i = 0; i < N16; ++i) {   // rows: odd rows continue with value i+16
+        const float hi = (i + 16 < N32) ? s32[i + 16] : 0.0f;
+        auto p = __builtin_amdgcn_permlane16_swap(__float_as_uint(s32[i]), __float_as_uint(hi), false, false);
+        s16[i] = __uint_as_float(p[0]) + __uint_as_float(p[1]);
+    }
+    row_stage<N16, 8, kDppRowRor8>(s16, s8, lane);
+    row_stage<N8, 4, kDppHalfMirror>(s8, s4, lane);
+    row_stage<N4, 2, kDppQuadXor2>(s4, s2, lane);
+    row_stage<N2, 1, kDppQuadXor1>(s2, s1, lane);
+    return s1[0];
+}
+
+// plain 64-lane sum, every lane gets the total (used once per wavefront for the loss)
+__device__ __forceinline__ double wave_sum(double x)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, kLanes);
+    return x;
+}
+
+template <int VW> __device__ __forceinline__ void load_vec(const float *p, float *dst)
+{
+    if constexpr (VW == 1) { dst[0] = *p; }
+    else if constexpr (VW == 2) { const float2 t = *reinterpret_cast<const float2 *>(p); dst[0] = t.x; dst[1] = t.y; }
+    else { const float4 t = *reinterpret_cast<const float4 *>(p); dst[0] = t.x; dst[1] = t.y; dst[2] = t.z; dst[3] = t.w; }
+}
+template <int VW> __device__ __forceinline__ void store_vec(float *p, const float *src)
+{
+    if constexpr (VW == 1) { *p = src[0]; }
+    else if constexpr (VW == 2) { *reinterpret_cast<float2 *>(p) = make_float2(src[0], src[1]); }
+    else { *reinterpret_cast<float4 *>(p) = make_float4(src[0], src[1], src[2], src[3]); }
+}
+
+// learning rate of the sentence that starts at global token offset `start` of this epoch
+__device__ __forceinline__ float sentence_lr(const KernelArgs &A, uint64_t start)
+{
+    const double done = (double)(A.lr_done_base + start);
+    double frac = 1.0 - done / (double)A.lr_all;
+    if (frac < A.lr_min_frac) frac = A.lr_min_frac;
+    return (float)(A.lr0 * frac);
+}
+
+// ---------------------------------------------------------------------------------------------
+// weight initialisation: syn0[i][j] = (u24/2^24 - 0.5)/d from the seed, syn1neg = 0, padding = 0
+// ---------------------------------------------------------------------------------------------
+__global__ void init_weights_kernel(float *syn0, float *syn1neg, uint32_t vocab, uint32_t dim, uint32_t ld, uint64_t k0)
+{
+    const uint64_t n = (uint64_t)vocab * ld;
+    for (uint64_t x = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; x < n; x += (uint64_t)gridDim.x * blockDim.x) {
+        const uint64_t i = x / ld, j = x % ld;
+        float v = 0.0f;
+        if (j < dim) {
+            const uint32_t u = (uint32_t)(mix64(k0 + (i * dim + j)) >> 32);
+            v = (float)(((double)(u >> 8) * (1.0 / 16777216.0) - 0.5) / (double)dim);
+        }
+        syn0[x] = v;
+        syn1neg[x] = 0.0f;
+    }
+}
+
+__global__ void reset_accum_kernel(Accum *a, int what)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        a->next_sentence = 0;
+        if (what >= 2) { a->loss_sum = 0.0; a->pairs = 0; a->dropped = 0; }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// draw dump: the integer decisions of every token, one thread per token
+// ---------------------------------------------------------------------------------------------
+__global__ void draws_kernel(KernelArgs A, uint64_t n_tokens, uint8_t *keep, uint8_t *width, int32_t *neg)
+{
+    for (uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; t < n_tokens; t += (uint64_t)gridDim.x * blockDim.x) {
+        const int32_t w = A.tokens[t];
+        const uint64_t base = position_base(A.key, A.first_pos + t);
+        bool k = w >= 0 && (uint32_t)w < A.vocab;
+        if (k) k = keep_decision(base, A.subsample ? A.thr[w] : 0xFFFFFFFFu);
+        keep[t] = k ? 1 : 0;
+        width[t] = k ? (uint8_t)window_width(base, A.window, A.window_mode) : 0;
+        for (uint32_t j = 0; j < A.negatives; ++j)
+            neg[t * A.negatives + j] = k ? A.table[negative_slot(base, j, A.table_size)] : -1;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// the window kernel
+// ---------------------------------------------------------------------------------------------
+template <int VW, int R, int WCAP, bool FULL>
+__global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
+{
+    constexpr int E = VW * R;            // floats of a row per lane
+    constexpr int ROWF = kLanes * E;     // floats of a ring row in LDS
+    constexpr int NCTX = 2 * WCAP;       // context positions a window can have
+    constexpr int NQ = (NCTX + CC - 1) / CC;
+
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    const int lane = threadIdx.x;
+    const uint32_t W = A.window, N = A.negatives;
+    const uint32_t nslots = 2 * W + 2;
+    float *ring = reinterpret_cast<float *>(lds_raw);
+    int32_t *kw = reinterpret_cast<int32_t *>(ring + (size_t)nslots * ROWF);  // kept word ids (FIFO)
+    uint32_t *kp = reinterpret_cast<uint32_t *>(kw + FCAP);                  // their offsets in the sentence
+    uint32_t *cb_b = kp + FCAP;                                              // widths of the chunk's windows
+    uint32_t *cb_pack = cb_b + kLanes;                                       // [64][N] negative id | multiplicity<<27
+
+    // element offsets of this lane inside a row, and whether they exist (dim may not fill 64*E)
+    int eoff[R];
+    bool evalid[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        eoff[r] = (r * kLanes + lane) * VW;
+        evalid[r] = FULL || (uint32_t)eoff[r] < A.dim;
+    }
+    const int lane_c = lane / KC, lane_k = lane % KC;   // pairing handled by this lane after the reduction
+
+    double loss_acc = 0.0;
+    unsigned long long pairs_acc = 0, dropped_acc = 0;
+
+    for (;;) {
+        // ---- next sentence from the work queue -------------------------------------------------
+        unsigned long long s_raw = 0;
+        if (lane == 0) s_raw = atomicAdd(&A.accum->next_sentence, 1ull);
+        const uint64_t s = uni64(s_raw);
+        if (s >= A.n_sent) break;
+        const uint64_t t0 = uni64(A.sent_off[s]);
+        const uint64_t t1 = uni64(A.sent_off[s + 1]);
+        const uint32_t len = (t1 > t0) ? (uint32_t)(t1 - t0) : 0u;
+        const float alpha = sentence_lr(A, A.first_pos + t0);
+
+        int32_t meta_word = -1;       // lane p&63: word of resident kept position p (-1: none)
+        uint32_t meta_slot = 0;       // lane p&63: its ring slot
+        uint32_t free_slots = (nslots >= 32) ? 0xFFFFFFFFu : ((1u << nslots) - 1u);
+        uint32_t free_hi = (nslots > 32) ? ((1u << (nslots - 32)) - 1u) : 0u;   // slots 32..33 (W = 16)
+        uint32_t n_prod = 0;          // kept tokens found so far
+        uint32_t raw_next = 0;        // next token offset to look at
+        uint32_t n_ins = 0;           // kept positions [0, n_ins) have entered the ring
+        uint32_t i0 = 0;              // first window of the current chunk
+
+        auto take_slot = [&]() -> uint32_t {
+            uint32_t sl;
+            if (free_slots) { sl = __builtin_ctz(free_slots); free_slots &= free_slots - 1u; }
+            else { sl = 32u + __builtin_ctz(free_hi); free_hi &= free_hi - 1u; }
+            return sl;
+        };
+        auto give_slot = [&](uint32_t sl) {
+            if (sl < 32u) free_slots |= 1u << sl; else free_hi |= 1u << (sl - 32u);
+        };
+        // position p enters the ring; returns true when its row must be fetched into `slot`
+        auto ring_enter = [&](uint32_t p, uint32_t &slot, int32_t &word) -> bool {
+            word = (int32_t)uni((uint32_t)kw[p & (FCAP - 1)]);
+            const uint64_t same = __ballot(meta_word == word);
+            bool fetch;
+            if (same) { slot = lane_value(meta_slot, (uint32_t)__builtin_ctzll(same)); fetch = false; }
+            else { slot = take_slot(); fetch = true; }
+            if (lane == (int)(p & 63u)) { meta_word = word; meta_slot = slot; }
+            return fetch;
+        };
+        // position p leaves the ring; its row goes back to syn0 unless another position shares it
+        auto ring_leave = [&](uint32_t p) {
+            const uint32_t l = p & 63u;
+            const uint32_t slot = lane_value(meta_slot, l);
+            const int32_t word = (int32_t)lane_value((uint32_t)meta_word, l);
+            if (lane == (int)l) meta_word = -1;
+            const uint64_t shared = __ballot(meta_word >= 0 && meta_slot == slot);
+            if (!shared) {
+                const float *src = ring + (size_t)slot * ROWF;
+                float *dst = A.syn0 + (size_t)word * A.ld;
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    float t[VW];
+                    load_vec<VW>(src + eoff[r], t);
+                    if (evalid[r]) store_vec<VW>(dst + eoff[r], t);
+                }
+                give_slot(slot);
+            }
+        };
+
+        for (;;) {
+            // ---- look at more tokens until this chunk's windows know all their context ----------
+            while (n_prod < i0 + kLanes + W + 1 && raw_next < len) {
+                const uint32_t off = raw_next + lane;
+                bool k = false;
+                int32_t w = -1;
+                if (off < len) {
+                    w = A.tokens[t0 + off];
+                    k = w >= 0 && (uint32_t)w < A.vocab;
+                    if (!k) ++dropped_acc;
+                    if (k && A.subsample) {
+                        const uint32_t th = A.thr[w];
+                        if (th != 0xFFFFFFFFu) k = keep_decision(position_base(A.key, A.first_pos + t0 + off), th);
+                    }
+                }
+                const uint64_t km = __ballot(k);
+                if (k) {
+                    const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(km >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)km, 0u));
+                    kw[(n_prod + rank) & (FCAP - 1)] = w;
+                    kp[(n_prod + rank) & (FCAP - 1)] = off;
+                }
+                n_prod += (uint32_t)__popcll(km);
+                raw_next += kLanes;
+            }
+            __syncthreads();
+            if (i0 >= n_prod) break;
+            const uint32_t nwin = (n_prod - i0 < (uint32_t)kLanes) ? n_prod - i0 : (uint32_t)kLanes;
+
+            // ---- width and negatives of the chunk's windows, one window per lane ----------------
+            if ((uint32_t)lane < nwin) {
+                const uint32_t idx = (i0 + lane) & (FCAP - 1);
+                const int32_t w = kw[idx];
+                const uint64_t base = position_base(A.key, A.first_pos + t0 + kp[idx]);
+                cb_b[lane] = window_width(base, W, A.window_mode);
+                uint32_t *pk = cb_pack + (size_t)lane * N;
+                for (uint32_t k = 0; k < N; ++k) pk[k] = (uint32_t)A.table[negative_slot(base, k, A.table_size)];
+                // multiplicity: 0 for a negative equal to the target and for repeats of an earlier
+                // negative, otherwise the number of times the id was drawn
+                for (uint32_t k = 0; k < N; ++k) {
+                    const uint32_t id = pk[k] & kIdMask;
+                    uint32_t m = (id == (uint32_t)w) ? 0u : 1u;
+                    for (uint32_t k1 = 0; k1 < k && m; ++k1) if ((pk[k1] & kIdMask) == id) m = 0u;
+                    if (m) for (uint32_t k2 = k + 1; k2 < N; ++k2) if ((pk[k2] & kIdMask) == id) ++m;
+                    pk[k] = id | (m << kIdBits);
+                }
+            }
+            __syncthreads();
+
+            // ---- the chunk's windows, strictly in order -----------------------------------------
+            for (uint32_t j = 0; j < nwin; ++j) {
+                const uint32_t i = i0 + j;
+                const uint32_t b = uni(cb_b[j]);
+                const int32_t center = (int32_t)uni((uint32_t)kw[i & (FCAP - 1)]);
+
+                // rows entering the span: positions up to i+W+1 (the last one is fetched now and
+                // written into the ring after this window's arithmetic)
+                uint32_t pend_slot = 0;
+                bool pend = false;
+                float pend_row[E] = {};
+                {
+                    const uint32_t want = (i + W + 2 < n_prod) ? i + W + 2 : n_prod;
+                    while (n_ins < want) {
+                        uint32_t slot; int32_t word;
+                        const bool fetch = ring_enter(n_ins, slot, word);
+                        const bool last = (n_ins + 1 == want) && (n_ins == i + W + 1);
+                        if (fetch) {
+                            const float *src = A.syn0 + (size_t)word * A.ld;
+                            float t[E];
+#pragma unroll
+                            for (int r = 0; r < R; ++r) {
+#pragma unroll
+                                for (int x = 0; x < VW; ++x) t[r * VW + x] = 0.0f;
+                                if (evalid[r]) load_vec<VW>(src + eoff[r], t + r * VW);
+                            }
+                            if (last) {
+                                pend = true; pend_slot = slot;
+#pragma unroll
+                                for (int x = 0; x < E; ++x) pend_row[x] = t[x];
+                            } else {
+                                float *dst = ring + (size_t)slot * ROWF;
+#pragma unroll
+                                for (int r = 0; r < R; ++r) store_vec<VW>(dst + eoff[r], t + r * VW);
+                            }
+                        }
+                        ++n_ins;
+                    }
+                }
+
+                // which context positions exist: slot c <-> distance a=(c>>1)+1, right side if c odd
+                auto ctx_active = [&](int c) -> bool {
+                    const uint32_t a = (uint32_t)(c >> 1) + 1u;
+                    return a <= b && ((c & 1) ? (i + a < n_prod) : (i >= a));
+                };
+                uint32_t nact = 0;
+#pragma unroll
+                for (int c = 0; c < NCTX; ++c) nact += ctx_active(c) ? 1u : 0u;
+
+                if (nact) {
+                    pairs_acc += nact;
+                    // context rows: snapshot into registers
+                    float I[NCTX][E];
+                    uint32_t cslot[NCTX];
+#pragma unroll
+                    for (int c = 0; c < NCTX; ++c) {
+                        cslot[c] = 0;
+#pragma unroll
+                        for (int x = 0; x < E; ++x) I[c][x] = 0.0f;
+                        if (ctx_active(c)) {
+                            const uint32_t a = (uint32_t)(c >> 1) + 1u;
+                            const uint32_t p = (c & 1) ? i + a : i - a;
+                            cslot[c] = lane_value(meta_slot, p & 63u);
+                            const float *src = ring + (size_t)cslot[c] * ROWF;
+#pragma unroll
+                            for (int r = 0; r < R; ++r) load_vec<VW>(src + eoff[r], &I[c][r * VW]);
+                        }
+                    }
+
+                    for (uint32_t kb = 0; kb <= N; kb += KC) {
+                        // this lane's output row after the reduction, packed id | multiplicity
+                        const uint32_t gk = kb + lane_k;
+                        uint32_t packv = 0;
+                        if (gk == 0) packv = (uint32_t)center | (1u << kIdBits);
+                        else if (gk <= N) packv = cb_pack[(size_t)j * N + (gk - 1)];
+                        const float mult_lane = (float)(packv >> kIdBits);
+
+                        float O[KC][E];
+                        uint32_t oid[KC], omult[KC];
+#pragma unroll
+                        for (int kk = 0; kk < KC; ++kk) {
+                            const uint32_t pk = lane_value(packv, (uint32_t)kk);   // lanes 0..KC-1 have lane_k = kk
+                            oid[kk] = pk & kIdMask;
+                            omult[kk] = (kb + kk <= N) ? (pk >> kIdBits) : 0u;
+#pragma unroll
+                            for (int x = 0; x < E; ++x) O[kk][x] = 0.0f;
+                            if (omult[kk]) {
+                                const float *src = A.syn1neg + (size_t)oid[kk] * A.ld;
+#pragma unroll
+                                for (int r = 0; r < R; ++r)
+                                    if (evalid[r]) load_vec<VW>(src + eoff[r], &O[kk][r * VW]);
+                            }
+                        }
+
+                        float dO[KC][E];
+#pragma unroll
+                        for (int kk = 0; kk < KC; ++kk)
+#pragma unroll
+                            for (int x = 0; x < E; ++x) dO[kk][x] = 0.0f;
+
+#pragma unroll
+                        for (int q = 0; q < NQ; ++q) {
+                            if (2u * b <= (uint32_t)(q * CC)) continue;     // no pairing in this block of contexts
+                            float acc[CC * KC];
+#pragma unroll
+                            for (int cc = 0; cc < CC; ++cc) {
+                                const int c = q * CC + cc;
+#pragma unroll
+                                for (int kk = 0; kk < KC; ++kk) acc[cc * KC + kk] = 0.0f;
+                                if (c < NCTX && ctx_active(c)) {
+#pragma unroll
+                                    for (int kk = 0; kk < KC; ++kk) {
+                                        float p = 0.0f;
+#pragma unroll
+                                        for (int x = 0; x < E; ++x) p = __builtin_fmaf(I[c][x], O[kk][x], p);
+                                        acc[cc * KC + kk] = p;
+                                    }
+                                }
+                            }
+                            const float xv = transpose_reduce<CC * KC>(acc, lane);
+
+                            // lane v = (context q*CC + lane_c, output kb + lane_k)
+                            const int gc = q * CC + lane_c;
+                            bool act = lane < CC * KC && gc < NCTX && gk <= N && mult_lane > 0.0f;
+                            {
+                                const uint32_t a = (uint32_t)(gc >> 1) + 1u;
+                                act = act && a <= b && ((gc & 1) ? (i + a < n_prod) : (i >= a));
+                            }
+                            const float ex = __expf(-xv);
+                            const float sig = __frcp_rn(1.0f + ex);
+                            const float label = (gk == 0) ? 1.0f : 0.0f;
+                            const float g = act ? alpha * mult_lane * (label - sig) : 0.0f;
+                            if (act) {
+                                const float z = (gk == 0) ? -xv : xv;       // softplus(z), stable form
+                                const float sp = fmaxf(z, 0.0f) + __logf(1.0f + __expf(-fabsf(z)));
+                                loss_acc += (double)(mult_lane * sp);
+                            }
+
+#pragma unroll
+                            for (int cc = 0; cc < CC; ++cc) {
+                                const int c = q * CC + cc;
+                                if (c < NCTX && ctx_active(c)) {
+                                    float dI[E];
+#pragma unroll
+                                    for (int x = 0; x < E; ++x) dI[x] = 0.0f;
+#pragma unroll
+                                    for (int kk = 0; kk < KC; ++kk) {
+                                        const float gs = lane_value(g, (uint32_t)(cc * KC + kk));
+#pragma unroll
+                                        for (int x = 0; x < E; ++x) {
+                                            dI[x] = __builtin_fmaf(gs, O[kk][x], dI[x]);
+                                            dO[kk][x] = __builtin_fmaf(gs, I[c][x], dO[kk][x]);
+                                        }
+                                    }
+                                    // the ring row accumulates; positions sharing a row add up
+                                    float *dst = ring + (size_t)cslot[c] * ROWF;
+#pragma unroll
+                                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                                        for (int x = 0; x < VW; ++x)
+                                            __hip_atomic_fetch_add(dst + eoff[r] + x, dI[r * VW + x], __ATOMIC_RELAXED,
+                                                                   __HIP_MEMORY_SCOPE_WAVEFRONT);
+                                }
+                            }
+                        }
+
+                        // output rows go back (lock-free) once per window
+#pragma unroll
+                        for (int kk = 0; kk < KC; ++kk) {
+                            if (omult[kk]) {
+                                float *dst = A.syn1neg + (size_t)oid[kk] * A.ld;
+#pragma unroll
+                                for (int r = 0; r < R; ++r) {
+                                    float t[VW];
+#pragma unroll
+                                    for (int x = 0; x < VW; ++x) t[x] = O[kk][r * VW + x] + dO[kk][r * VW + x];
+                                    if (evalid[r]) store_vec<VW>(dst + eoff[r], t);
+                                }
+                            }
+                        }
+                    }
+                }
+
+                // (every lane only ever touches its own elements of a ring row, so the ring needs no
+                // synchronisation between lanes)
+                if (pend) {
+                    float *dst = ring + (size_t)pend_slot * ROWF;
+#pragma unroll
+                    for (int r = 0; r < R; ++r) store_vec<VW>(dst + eoff[r], pend_row + r * VW);
+                }
+                if (i >= W) ring_leave(i - W);
+            }
+            i0 += nwin;
+        }
+
+        // ---- sentence done: the rows still in the ring go back -------------------------------------
+        {
+            const uint32_t first = (n_prod > W) ? n_prod - W : 0u;   // positions < first left already
+            for (uint32_t p = first; p < n_ins; ++p) ring_leave(p);
+        }
+        __syncthreads();
+    }
+
+    const double lsum = wave_sum(loss_acc);
+    const unsigned long long dsum = (unsigned long long)wave_sum((double)dropped_acc);
+    if (lane == 0) {
+        atomicAdd(&A.accum->loss_sum, lsum);
+        atomicAdd(&A.accum->pairs, pairs_acc);
+        if (dsum) atomicAdd(&A.accum->dropped, dsum);
+    }
+}
+
+__global__ void __launch_bounds__(kLanes) reduce_selftest_kernel(const float *in, float *out)
+{
+    float v[CC * KC];
+#pragma unroll
+    for (int m = 0; m < CC * KC; ++m) v[m] = in[m * kLanes + threadIdx.x];
+    out[threadIdx.x] = transpose_reduce<CC * KC>(v, threadIdx.x);
+}
+
+using TrainFn = void (*)(KernelArgs);
+
+template <int VW, int R, bool FULL>
+TrainFn train_fn_for_window(uint32_t W)
+{
+    if (W <= 5) return train_kernel<VW, R, 5, FULL>;
+    if (W <= 10) return train_kernel<VW, R, 10, FULL>;
+    if constexpr (VW * R <= 5) return train_kernel<VW, R, 16, FULL>;
+    return nullptr;
+}
+
+TrainFn train_fn(const KernelArgs &a, RowShape s)
+{
+    const bool full = a.dim == (uint32_t)(kLanes * s.vw * s.r);
+    if (s.vw == 1 && s.r == 1) return full ? train_fn_for_window<1, 1, true>(a.window) : train_fn_for_window<1, 1, false>(a.window);
+    if (s.vw == 2 && s.r == 1) return full ? train_fn_for_window<2, 1, true>(a.window) : train_fn_for_window<2, 1, false>(a.window);
+    if (s.vw == 4 && s.r == 1) return full ? train_fn_for_window<4, 1, true>(a.window) : train_fn_for_window<4, 1, false>(a.window);
+    if (s.vw == 1 && s.r == 5) return train_fn_for_window<1, 5, false>(a.window);
+    if (s.vw == 4 && s.r == 2) return full ? train_fn_for_window<4, 2, true>(a.window) : train_fn_for_window<4, 2, false>(a.window);
+    return nullptr;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+// host side of the kernels
+// ---------------------------------------------------------------------------------------------
+bool pick_row_shape(uint32_t dim, uint32_t ld, RowShape *out)
+{
+    static const RowShape shapes[] = {{1, 1}, {2, 1}, {4, 1}, {1, 5}, {4, 2}};   // by floats per lane
+    for (const RowShape &s : shapes) {
+        if ((uint32_t)(kLanes * s.vw * s.r) < dim) continue;
+        if (dim % s.vw || ld % s.vw) continue;
+        *out = s;
+        return true;
+    }
+    return false;
+}
+
+uint32_t train_lds_bytes(const KernelArgs &a, RowShape s)
+{
+    const uint32_t rowf = kLanes * s.vw * s.r;
+    return (2 * a.window + 2) * rowf * 4u + FCAP * 8u + kLanes * 4u + kLanes * a.negatives * 4u;
+}
+
+hipError_t launch_init_weights(float *syn0, float *syn1neg, uint32_t vocab, uint32_t dim, uint32_t ld,
+                               uint64_t seed, hipStream_t stream)
+{
+    const uint64_t n = (uint64_t)vocab * ld;
+    const uint32_t blocks = (uint32_t)((n + 255) / 256 < 8192 ? (n + 255) / 256 : 8192);
+    hipLaunchKernelGGL(init_weights_kernel, dim3(blocks), dim3(256), 0, stream, syn0, syn1neg, vocab, dim, ld,
+                       mix64(seed ^ 0x696E6974ull));
+    return hipGetLastError();
+}
+
+hipError_t launch_reset_accum(Accum *accum, int what, hipStream_t stream)
+{
+    hipLaunchKernelGGL(reset_accum_kernel, dim3(1), dim3(64), 0, stream, accum, what);
+    return hipGetLastError();
+}
+
+uint32_t train_resident_waves(const KernelArgs &a, int device)
+{
+    RowShape s;
+    if (!pick_row_shape(a.dim, a.ld, &s)) return 0;
+    TrainFn fn = train_fn(a, s);
+    if (!fn) return 0;
+    int per_cu = 0, cus = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kLanes, train_lds_bytes(a, s)) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) return 0;
+    return (uint32_t)(per_cu > 0 ? per_cu : 1) * (uint32_t)(cus > 0 ? cus : 1);
+}
+
+hipError_t launch_train(const KernelArgs &a, uint32_t waves, hipStream_t stream)
+{
+    RowShape s;
+    if (!pick_row_shape(a.dim, a.ld, &s)) return hipErrorInvalidValue;
+    TrainFn fn = train_fn(a, s);
+    if (!fn) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(fn, dim3(waves), dim3(kLanes), train_lds_bytes(a, s), stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_draws(const KernelArgs &a, uint64_t n_tokens, uint8_t *keep, uint8_t *width, int32_t *neg,
+                        hipStream_t stream)
+{
+    if (n_tokens == 0) return hipSuccess;
+    const uint32_t blocks = (uint32_t)((n_tokens + 255) / 256 < 16384 ? (n_tokens + 255) / 256 : 16384);
+    hipLaunchKernelGGL(draws_kernel, dim3(blocks), dim3(256), 0, stream, a, n_tokens, keep, width, neg);
+    return hipGetLastError();
+}
+
+hipError_t launch_reduce_selftest(const float *in, float *out, hipStream_t stream)
+{
+    hipLaunchKernelGGL(reduce_selftest_kernel, dim3(1), dim3(kLanes), 0, stream, in, out);
+    return hipGetLastError();
+}
+
+}  // namespace w2v

@@ -1,0 +1,78 @@
+"""Convenience holder of the device buffers one training context needs (torch tensors for memory,
+the current torch stream for ordering).  All computation is done by the C-ABI library."""
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+class Trainer:
+    def __init__(self, *, vocab, dim, window, negatives, counts, tokens_per_epoch, seed, table_size=1 << 24,
+                 subsample_t=0.0, total_epochs=1, sentences_in_flight=0, window_mode=0, lr0=0.025,
+                 lr_min_frac=1e-4, device=0, init_weights=True, syn0=None, syn1neg=None):
+        if not torch.cuda.is_available():
+            raise RuntimeError("the SGNS trainer needs a GPU; there is no CPU implementation in this package")
+        self.dev = torch.device("cuda", device)
+        self.vocab, self.dim, self.window, self.negatives = vocab, dim, window, negatives
+        self.ld = B.w2v_query_ld(dim)
+        self.syn0 = torch.zeros((vocab, self.ld), dtype=torch.float32, device=self.dev)
+        self.syn1neg = torch.zeros((vocab, self.ld), dtype=torch.float32, device=self.dev)
+        if syn0 is not None:
+            self.syn0[:, :dim] = torch.as_tensor(np.asarray(syn0, np.float32)).to(self.dev)
+            self.syn1neg[:, :dim] = torch.as_tensor(np.asarray(syn1neg, np.float32)).to(self.dev)
+            init_weights = False
+        ws_bytes = B.w2v_query_workspace(vocab, table_size)
+        self.workspace = torch.zeros(ws_bytes, dtype=torch.uint8, device=self.dev)
+        assert self.workspace.data_ptr() % 256 == 0
+        self.stream = torch.cuda.current_stream(self.dev)
+        self.cfg = B.make_config(vocab=vocab, dim=dim, window=window, negatives=negatives,
+                                 tokens_per_epoch=tokens_per_epoch, seed=seed, syn0=self.syn0, syn1neg=self.syn1neg,
+                                 ld=self.ld, workspace=self.workspace, workspace_bytes=ws_bytes, device=device,
+                                 stream=self.stream.cuda_stream, window_mode=window_mode, total_epochs=total_epochs,
+                                 sentences_in_flight=sentences_in_flight, lr0=lr0, lr_min_frac=lr_min_frac,
+                                 subsample_t=subsample_t)
+        torch.cuda.synchronize(self.dev)
+        self.ctx = B.w2v_create(self.cfg, 1 if init_weights else 0)
+        B.w2v_build_unigram_table(self.ctx, counts, table_size)
+        self.tokens = self.sent_off = None
+        self.n_sent = 0
+
+    def set_corpus(self, tokens, sent_off):
+        self.tokens = torch.as_tensor(np.ascontiguousarray(tokens, np.int32)).to(self.dev)
+        # torch has no uint64 arithmetic, but the bytes are all the library needs
+        self.sent_off = torch.as_tensor(np.ascontiguousarray(sent_off, np.uint64).view(np.int64)).to(self.dev)
+        self.n_sent = len(sent_off) - 1
+        torch.cuda.synchronize(self.dev)
+
+    def train_epoch(self, epoch=0, first_token_global_pos=0, naive=False):
+        f = B.w2v_train_epoch_naive if naive else B.w2v_train_epoch
+        f(self.ctx, self.tokens, self.sent_off, self.n_sent, first_token_global_pos, epoch)
+
+    def loss(self, reset=False):
+        return B.w2v_loss(self.ctx, reset)
+
+    def embeddings(self, which=0):
+        out = np.empty((self.vocab, self.dim), np.float32)
+        B.w2v_get_embeddings(self.ctx, which, out, out.size, False)
+        return out
+
+    def draws(self, epoch=0, first_token_global_pos=0):
+        T = int(self.tokens.numel())
+        keep = torch.zeros(T, dtype=torch.uint8, device=self.dev)
+        width = torch.zeros(T, dtype=torch.uint8, device=self.dev)
+        neg = torch.zeros((T, max(self.negatives, 1)), dtype=torch.int32, device=self.dev)
+        B.w2v_debug_draws(self.ctx, self.tokens, self.sent_off, self.n_sent, first_token_global_pos, epoch, keep,
+                          width, neg)
+        torch.cuda.synchronize(self.dev)
+        return keep.cpu().numpy(), width.cpu().numpy(), neg.cpu().numpy()[:, :self.negatives]
+
+    def close(self):
+        if self.ctx is not None:
+            B.w2v_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
