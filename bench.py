@@ -1,0 +1,123 @@
+#!/usr/bin/env python3
+"""Benchmark of the SGNS training hot path on one MI355X.
+
+A step is one pass of the whole hot path (subsampling, width and negative draws, row gathers,
+window arithmetic, scatter, loss) over one synthetic corpus resident in HBM: the 'Mid' workload,
+vocabulary 71,000 Zipf(1.05) with 16 planted clusters, 17M tokens in 1,000-token sentences, d=128,
+W=5, N=5, subsampling t=1e-4, min-count 5.  Step e is epoch e of a (warmup+steps)-epoch schedule.
+
+Prints one JSON line: words/sec (corpus tokens, pre-subsampling), the HBM roofline of the window
+kernel from its algorithmic bytes ((2N+4) rows of 4d bytes per kept word) and live HIP-event
+timing, and the CPU oracle timed on a prefix of the same corpus.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+WORKLOADS = {
+    # name: (generator kwargs, dim, window, negatives, subsample_t, table_size)
+    "mid": (dict(vocab=71000, s=1.05, n_sent=17000, sent_len=1000, seed=1), 128, 5, 5, 1e-4, 1 << 24),
+    "small": (dict(vocab=8000, s=1.05, n_sent=600, sent_len=1000, seed=1, band_start=400), 128, 5, 5, 1e-4, 1 << 20),
+}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="mid", choices=sorted(WORKLOADS))
+    ap.add_argument("--dim", type=int, default=None, help="override d (dimension sweep)")
+    ap.add_argument("--in-flight", type=int, default=0, help="sentences_in_flight (0 = fill the GPU)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sentences", type=int, default=2500)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (a second GPU is never used); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2312_07743_amd import synth
+    from paper_2312_07743_amd.trainer import Trainer
+
+    gen_kw, dim, window, negatives, t_sub, table_size = WORKLOADS[args.workload]
+    if args.dim:
+        dim = args.dim
+    corpus = synth.planted_corpus(**gen_kw)
+    E = args.warmup + args.steps
+    tr = Trainer(vocab=corpus.vocab, dim=dim, window=window, negatives=negatives, counts=corpus.counts,
+                 tokens_per_epoch=corpus.n_tokens, seed=2024, table_size=table_size, subsample_t=t_sub,
+                 total_epochs=E, sentences_in_flight=args.in_flight)
+    tr.set_corpus(corpus.tokens, corpus.sent_off)
+    for e in range(args.warmup):
+        tr.train_epoch(e)
+    torch.cuda.synchronize()
+    tr.loss(reset=True)
+
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        starts[k].record()                       # torch's current stream is the one the library launches on
+        tr.train_epoch(args.warmup + k)
+        stops[k].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kernel_ms = [a.elapsed_time(b) for a, b in zip(starts, stops)]
+    kept, _ = tr.counters()
+    loss_sum, pairs = tr.loss()
+
+    words = corpus.n_tokens * args.steps
+    row_bytes = 4 * dim
+    algo_bytes_per_launch = (2 * negatives + 4) * row_bytes * (kept / args.steps)
+    avg_kernel_s = float(np.mean(kernel_ms)) / 1e3
+    achieved = algo_bytes_per_launch / avg_kernel_s / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"window_kernel_{args.workload}_d{dim}_traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+
+    out = {
+        "metric": "trained words/sec on 1 MI355X; achieved HBM GB/s vs peak",
+        "value": words / wall, "unit": "words/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: vocab {corpus.vocab} Zipf(1.05) + 16 planted clusters, "
+                               f"{corpus.n_tokens} tokens in {corpus.n_sent} sentences, d={dim}, W={window}, "
+                               f"N={negatives}, subsample t={t_sub}, min-count 5, lr 0.025 linear decay",
+                   "kept_words_per_s": kept / wall, "kept_fraction": kept / words,
+                   "mean_loss": loss_sum / max(pairs, 1), "sentences_in_flight": args.in_flight},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": "train_kernel", "avg_launch_ms": avg_kernel_s * 1e3,
+                     "algorithmic_bytes_per_launch": algo_bytes_per_launch},
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import Oracle                     # the CPU oracle, timed as it stands (never tuned)
+        orc = Oracle("float")
+        ns = min(args.cpu_sentences, corpus.n_sent)
+        syn0, syn1 = orc.init_weights(2024, corpus.vocab, dim)
+        c0 = time.perf_counter()
+        orc.train_epoch(syn0, syn1, corpus.counts, corpus.tokens, corpus.sent_off, window=window, negatives=negatives,
+                        seed=2024, epoch=0, total_epochs=E, table_size=table_size, subsample_t=t_sub, s_end=ns)
+        cdt = time.perf_counter() - c0
+        out["cpu_baseline"] = {"value": int(corpus.sent_off[ns]) / cdt, "unit": "words/s", "cores": 1,
+                               "kind": "oracle",
+                               "sample": f"first {ns} sentences ({int(corpus.sent_off[ns])} tokens) of the same corpus, "
+                                         f"one epoch, {cdt:.1f} s"}
+    tr.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

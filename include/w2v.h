@@ -116,6 +116,11 @@ int w2v_get_embeddings(w2v_ctx *ctx, int which, float *dst, uint64_t dst_floats,
  * Mean loss = *loss_sum / *positive_pairs.  Either output may be NULL.  Waits for the stream. */
 int w2v_loss(w2v_ctx *ctx, double *loss_sum, uint64_t *positive_pairs, int reset);
 
+/* Token counters since the last reset: kept_tokens = tokens that survived subsampling (= context
+ * windows processed), invalid_tokens = ids outside [0, vocab).  Either output may be NULL.
+ * Waits for the stream. */
+int w2v_counters(w2v_ctx *ctx, uint64_t *kept_tokens, uint64_t *invalid_tokens, int reset);
+
 /* Test surface: writes, for every token t of the given range, the integer decisions the trainer
  * takes for it: keep_dev[t] (1 kept / 0 dropped), width_dev[t] (window width, 0 if dropped),
  * neg_dev[t*N + k] (k-th negative word id, -1 if dropped).  Device outputs.  Asynchronous. */

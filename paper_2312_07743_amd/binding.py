@@ -14,7 +14,7 @@ W2V_OK, W2V_EINVAL, W2V_ESTATE, W2V_ENOMEM, W2V_EHIP = 0, -1, -2, -3, -4
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libw2v.so")
 EXPORTS = ["w2v_query_ld", "w2v_query_workspace", "w2v_create", "w2v_destroy", "w2v_build_unigram_table",
-           "w2v_train_epoch", "w2v_train_epoch_naive", "w2v_get_embeddings", "w2v_loss", "w2v_debug_draws",
+           "w2v_train_epoch", "w2v_train_epoch_naive", "w2v_get_embeddings", "w2v_loss", "w2v_counters", "w2v_debug_draws",
            "w2v_debug_reduce", "w2v_last_error"]
 
 
@@ -54,6 +54,7 @@ def lib():
         L.w2v_train_epoch_naive.argtypes = [vp, vp, vp, u64, u64, u32]
         L.w2v_get_embeddings.argtypes = [vp, i32, vp, u64, i32]
         L.w2v_loss.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(u64), i32]
+        L.w2v_counters.argtypes = [vp, C.POINTER(u64), C.POINTER(u64), i32]
         L.w2v_debug_draws.argtypes = [vp, vp, vp, u64, u64, u32, vp, vp, vp]
         L.w2v_debug_reduce.argtypes = [vp, vp, vp]
         L.w2v_last_error.argtypes = [vp]
@@ -140,6 +141,12 @@ def w2v_loss(ctx, reset=0):
     s, p = C.c_double(0.0), C.c_uint64(0)
     _check(lib().w2v_loss(ctx, C.byref(s), C.byref(p), int(reset)), ctx)
     return s.value, p.value
+
+
+def w2v_counters(ctx, reset=0):
+    k, d = C.c_uint64(0), C.c_uint64(0)
+    _check(lib().w2v_counters(ctx, C.byref(k), C.byref(d), int(reset)), ctx)
+    return k.value, d.value
 
 
 def w2v_debug_draws(ctx, tokens_dev, sent_off_dev, n_sent, first_token_global_pos, epoch, keep_dev, width_dev, neg_dev):

@@ -299,6 +299,20 @@ int w2v_loss(w2v_ctx *ctx, double *loss_sum, uint64_t *positive_pairs, int reset
     return W2V_OK;
 }
 
+int w2v_counters(w2v_ctx *ctx, uint64_t *kept_tokens, uint64_t *invalid_tokens, int reset)
+{
+    if (!ctx) return fail(nullptr, W2V_EINVAL, "ctx is NULL");
+    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    w2v::Accum host;
+    w2v::Accum *dev = reinterpret_cast<w2v::Accum *>(static_cast<unsigned char *>(ctx->cfg.workspace) + ctx->ws.accum_off);
+    HIP_TRY(ctx, hipMemcpyAsync(&host, dev, sizeof(host), hipMemcpyDeviceToHost, stream_of(ctx)));
+    HIP_TRY(ctx, hipStreamSynchronize(stream_of(ctx)));
+    if (kept_tokens) *kept_tokens = host.kept;
+    if (invalid_tokens) *invalid_tokens = host.dropped;
+    if (reset) HIP_TRY(ctx, w2v::launch_reset_accum(dev, 2, stream_of(ctx)));
+    return W2V_OK;
+}
+
 int w2v_debug_draws(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_t *sent_off_dev, uint64_t n_sent,
                     uint64_t first_token_global_pos, uint32_t epoch, uint8_t *keep_dev, uint8_t *width_dev,
                     int32_t *neg_dev)

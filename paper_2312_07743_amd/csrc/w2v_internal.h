@@ -15,6 +15,7 @@ struct Accum {
     unsigned long long pairs;          // (context, target) pairs trained
     unsigned long long next_sentence;  // work queue head of the current launch
     unsigned long long dropped;        // tokens with ids outside [0, V)
+    unsigned long long kept;           // tokens that survived subsampling (windows processed)
 };
 
 // Layout of the caller-provided workspace (all offsets multiples of 256 bytes).

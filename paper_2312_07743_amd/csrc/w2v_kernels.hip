@@ -142,7 +142,7 @@ __global__ void reset_accum_kernel(Accum *a, int what)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
         a->next_sentence = 0;
-        if (what >= 2) { a->loss_sum = 0.0; a->pairs = 0; a->dropped = 0; }
+        if (what >= 2) { a->loss_sum = 0.0; a->pairs = 0; a->dropped = 0; a->kept = 0; }
     }
 }
 
@@ -195,7 +195,7 @@ __global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
     const int lane_c = lane / KC, lane_k = lane % KC;   // pairing handled by this lane after the reduction
 
     double loss_acc = 0.0;
-    unsigned long long pairs_acc = 0, dropped_acc = 0;
+    unsigned long long pairs_acc = 0, dropped_acc = 0, kept_acc = 0;
 
     for (;;) {
         // ---- next sentence from the work queue -------------------------------------------------
@@ -498,6 +498,7 @@ __global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
             }
             i0 += nwin;
         }
+        kept_acc += n_prod;
 
         // ---- sentence done: the rows still in the ring go back -------------------------------------
         {
@@ -512,6 +513,7 @@ __global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
     if (lane == 0) {
         atomicAdd(&A.accum->loss_sum, lsum);
         atomicAdd(&A.accum->pairs, pairs_acc);
+        atomicAdd(&A.accum->kept, kept_acc);
         if (dsum) atomicAdd(&A.accum->dropped, dsum);
     }
 }

@@ -51,6 +51,9 @@ class Trainer:
     def loss(self, reset=False):
         return B.w2v_loss(self.ctx, reset)
 
+    def counters(self, reset=False):
+        return B.w2v_counters(self.ctx, reset)
+
     def embeddings(self, which=0):
         out = np.empty((self.vocab, self.dim), np.float32)
         B.w2v_get_embeddings(self.ctx, which, out, out.size, False)
