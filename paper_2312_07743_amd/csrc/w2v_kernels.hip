@@ -15,6 +15,8 @@
 #include "w2v_internal.h"
 #include "w2v_rng.h"
 
+#include <type_traits>
+
 namespace w2v {
 namespace {
 
@@ -166,6 +168,14 @@ __global__ void draws_kernel(KernelArgs A, uint64_t n_tokens, uint8_t *keep, uin
 // ---------------------------------------------------------------------------------------------
 // the window kernel
 // ---------------------------------------------------------------------------------------------
+// Per-window scalars the sampling stage leaves in LDS for the window loop (one uint4 per window):
+//   x = width b | (reload bits << 8) | (dup << 16)
+//       reload bit k': output row k' (k' < KC) of this window is also an output row of the previous
+//       window, so a copy fetched before that window's write-back is stale;
+//       dup: two context positions of the window hold the same word and share a ring row
+//   y = target word, z = word of the kept position that enters the ring at this window (or none)
+constexpr uint32_t kNoWord = 0xFFFFFFFFu;
+
 template <int VW, int R, int WCAP, bool FULL>
 __global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
 {
@@ -181,8 +191,8 @@ __global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
     float *ring = reinterpret_cast<float *>(lds_raw);
     int32_t *kw = reinterpret_cast<int32_t *>(ring + (size_t)nslots * ROWF);  // kept word ids (FIFO)
     uint32_t *kp = reinterpret_cast<uint32_t *>(kw + FCAP);                  // their offsets in the sentence
-    uint32_t *cb_b = kp + FCAP;                                              // widths of the chunk's windows
-    uint32_t *cb_pack = cb_b + kLanes;                                       // [64][N] negative id | multiplicity<<27
+    uint4 *cb_meta = reinterpret_cast<uint4 *>(kp + FCAP);                   // per-window scalars of the chunk
+    uint32_t *cb_pack = reinterpret_cast<uint32_t *>(cb_meta + kLanes);      // [64][N] negative id | multiplicity<<27
 
     // element offsets of this lane inside a row, and whether they exist (dim may not fill 64*E)
     int eoff[R];
@@ -196,6 +206,20 @@ __global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
 
     double loss_acc = 0.0;
     unsigned long long pairs_acc = 0, dropped_acc = 0, kept_acc = 0;
+
+    auto load_row = [&](const float *row, float *dst) {           // global row -> registers (zeros beyond dim)
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+#pragma unroll
+            for (int x = 0; x < VW; ++x) dst[r * VW + x] = 0.0f;
+            if (evalid[r]) load_vec<VW>(row + eoff[r], dst + r * VW);
+        }
+    };
+    auto store_row = [&](float *row, const float *src) {          // registers -> global row
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            if (evalid[r]) store_vec<VW>(row + eoff[r], src + r * VW);
+    };
 
     for (;;) {
         // ---- next sentence from the work queue -------------------------------------------------
@@ -226,9 +250,8 @@ __global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
         auto give_slot = [&](uint32_t sl) {
             if (sl < 32u) free_slots |= 1u << sl; else free_hi |= 1u << (sl - 32u);
         };
-        // position p enters the ring; returns true when its row must be fetched into `slot`
-        auto ring_enter = [&](uint32_t p, uint32_t &slot, int32_t &word) -> bool {
-            word = (int32_t)uni((uint32_t)kw[p & (FCAP - 1)]);
+        // kept position p (word `word`) enters the ring; true when its row must be fetched into `slot`
+        auto ring_enter = [&](uint32_t p, int32_t word, uint32_t &slot) -> bool {
             const uint64_t same = __ballot(meta_word == word);
             bool fetch;
             if (same) { slot = lane_value(meta_slot, (uint32_t)__builtin_ctzll(same)); fetch = false; }
@@ -285,51 +308,105 @@ __global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
             const uint32_t nwin = (n_prod - i0 < (uint32_t)kLanes) ? n_prod - i0 : (uint32_t)kLanes;
 
             // ---- width and negatives of the chunk's windows, one window per lane ----------------
+            int32_t my_w = -1;
+            uint32_t my_b = 0, my_enter = kNoWord;
             if ((uint32_t)lane < nwin) {
                 const uint32_t idx = (i0 + lane) & (FCAP - 1);
-                const int32_t w = kw[idx];
+                my_w = kw[idx];
                 const uint64_t base = position_base(A.key, A.first_pos + t0 + kp[idx]);
-                cb_b[lane] = window_width(base, W, A.window_mode);
+                my_b = window_width(base, W, A.window_mode);
+                const uint32_t pe = i0 + lane + W + 1;
+                if (pe < n_prod) my_enter = (uint32_t)kw[pe & (FCAP - 1)];
                 uint32_t *pk = cb_pack + (size_t)lane * N;
                 for (uint32_t k = 0; k < N; ++k) pk[k] = (uint32_t)A.table[negative_slot(base, k, A.table_size)];
                 // multiplicity: 0 for a negative equal to the target and for repeats of an earlier
                 // negative, otherwise the number of times the id was drawn
                 for (uint32_t k = 0; k < N; ++k) {
                     const uint32_t id = pk[k] & kIdMask;
-                    uint32_t m = (id == (uint32_t)w) ? 0u : 1u;
+                    uint32_t m = (id == (uint32_t)my_w) ? 0u : 1u;
                     for (uint32_t k1 = 0; k1 < k && m; ++k1) if ((pk[k1] & kIdMask) == id) m = 0u;
                     if (m) for (uint32_t k2 = k + 1; k2 < N; ++k2) if ((pk[k2] & kIdMask) == id) ++m;
                     pk[k] = id | (m << kIdBits);
                 }
             }
             __syncthreads();
+            if ((uint32_t)lane < nwin) {
+                // which of my first KC output rows does the previous window also write?
+                uint32_t reload = 0;
+                if (lane > 0) {
+                    const uint32_t pw = (uint32_t)kw[(i0 + lane - 1) & (FCAP - 1)];
+                    const uint32_t *mine = cb_pack + (size_t)lane * N;
+                    const uint32_t *prev = cb_pack + (size_t)(lane - 1) * N;
+                    for (uint32_t kk = 0; kk < (uint32_t)KC && kk <= N; ++kk) {
+                        uint32_t id;
+                        if (kk == 0) id = (uint32_t)my_w;
+                        else { const uint32_t p = mine[kk - 1]; if ((p >> kIdBits) == 0) continue; id = p & kIdMask; }
+                        bool hit = id == pw;
+                        for (uint32_t k = 0; k < N && !hit; ++k) hit = (prev[k] >> kIdBits) != 0 && (prev[k] & kIdMask) == id;
+                        if (hit) reload |= 1u << kk;
+                    }
+                }
+                // do two context positions of my window hold the same word (and so share a ring row)?
+                uint32_t dup = 0;
+                {
+                    const uint32_t me = i0 + lane;
+                    const uint32_t lo = (me > my_b) ? me - my_b : 0u;
+                    const uint32_t hi = (me + my_b < n_prod) ? me + my_b : n_prod - 1u;
+                    for (uint32_t p1 = lo; p1 < hi; ++p1) {
+                        if (p1 == me) continue;
+                        const int32_t w1 = kw[p1 & (FCAP - 1)];
+                        for (uint32_t p2 = p1 + 1; p2 <= hi; ++p2)
+                            if (p2 != me && kw[p2 & (FCAP - 1)] == w1) dup = 1u;
+                    }
+                }
+                cb_meta[lane] = make_uint4(my_b | (reload << 8) | (dup << 16), (uint32_t)my_w, my_enter, 0u);
+            }
+            __syncthreads();
 
             // ---- the chunk's windows, strictly in order -----------------------------------------
+            // scalars and output rows of the first window; later windows get theirs one window ahead
+            uint4 mraw = cb_meta[0];
+            uint32_t packv = 0;
+            if (lane_k >= 1 && (uint32_t)lane_k <= N) packv = cb_pack[lane_k - 1];
+            if (lane_k == 0) packv = mraw.y | (1u << kIdBits);
+            float O[KC][E];
+#pragma unroll
+            for (int kk = 0; kk < KC; ++kk) {
+                const uint32_t pk = lane_value(packv, (uint32_t)kk);
+#pragma unroll
+                for (int x = 0; x < E; ++x) O[kk][x] = 0.0f;
+                if ((uint32_t)kk <= N && (pk >> kIdBits)) load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, O[kk]);
+            }
+
             for (uint32_t j = 0; j < nwin; ++j) {
                 const uint32_t i = i0 + j;
-                const uint32_t b = uni(cb_b[j]);
-                const int32_t center = (int32_t)uni((uint32_t)kw[i & (FCAP - 1)]);
+                const uint32_t b = uni(mraw.x) & 0xFFu;
+                const bool shared_rows = (uni(mraw.x) >> 16) & 1u;
+                const uint32_t enter_word = uni(mraw.z);
+                const bool has_next = j + 1 < nwin;
 
-                // rows entering the span: positions up to i+W+1 (the last one is fetched now and
-                // written into the ring after this window's arithmetic)
+                // (a) ask LDS for the next window's scalars now, use them after the ring work below
+                uint4 mraw_next = make_uint4(0u, 0u, kNoWord, 0u);
+                uint32_t pack_next = 0;
+                if (has_next) {
+                    mraw_next = cb_meta[j + 1];
+                    if (lane_k >= 1 && (uint32_t)lane_k <= N) pack_next = cb_pack[(size_t)(j + 1) * N + (lane_k - 1)];
+                }
+
+                // (b) rows entering the span: positions up to i+W+1; the last one is fetched now and
+                //     written into the ring after this window's arithmetic
                 uint32_t pend_slot = 0;
                 bool pend = false;
                 float pend_row[E] = {};
                 {
                     const uint32_t want = (i + W + 2 < n_prod) ? i + W + 2 : n_prod;
                     while (n_ins < want) {
-                        uint32_t slot; int32_t word;
-                        const bool fetch = ring_enter(n_ins, slot, word);
                         const bool last = (n_ins + 1 == want) && (n_ins == i + W + 1);
-                        if (fetch) {
-                            const float *src = A.syn0 + (size_t)word * A.ld;
+                        const int32_t word = last ? (int32_t)enter_word : (int32_t)uni((uint32_t)kw[n_ins & (FCAP - 1)]);
+                        uint32_t slot;
+                        if (ring_enter(n_ins, word, slot)) {
                             float t[E];
-#pragma unroll
-                            for (int r = 0; r < R; ++r) {
-#pragma unroll
-                                for (int x = 0; x < VW; ++x) t[r * VW + x] = 0.0f;
-                                if (evalid[r]) load_vec<VW>(src + eoff[r], t + r * VW);
-                            }
+                            load_row(A.syn0 + (size_t)word * A.ld, t);
                             if (last) {
                                 pend = true; pend_slot = slot;
 #pragma unroll
@@ -344,108 +421,102 @@ __global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
                     }
                 }
 
-                // which context positions exist: slot c <-> distance a=(c>>1)+1, right side if c odd
-                auto ctx_active = [&](int c) -> bool {
-                    const uint32_t a = (uint32_t)(c >> 1) + 1u;
-                    return a <= b && ((c & 1) ? (i + a < n_prod) : (i >= a));
-                };
-                uint32_t nact = 0;
-#pragma unroll
-                for (int c = 0; c < NCTX; ++c) nact += ctx_active(c) ? 1u : 0u;
+                // (c) contexts of this window: slot c <-> distance a=(c>>1)+1, right side if c odd;
+                //     amask bit c set when that position exists and lies within the width
+                const uint32_t nl = (b < i) ? b : i;
+                const uint32_t nr = (b < n_prod - 1 - i) ? b : n_prod - 1 - i;
+                const uint32_t amask = uni((0x55555555u & (uint32_t)((1ull << (2 * nl)) - 1ull)) | (0xAAAAAAAAu & (uint32_t)((1ull << (2 * nr)) - 1ull)));
+                const uint32_t nact = nl + nr;
+                const bool interior = nl == b && nr == b;
 
+                float I[NCTX][E];
+                uint32_t cslot[NCTX];
+#pragma unroll
+                for (int c = 0; c < NCTX; ++c) {
+                    cslot[c] = 0;
+#pragma unroll
+                    for (int x = 0; x < E; ++x) I[c][x] = 0.0f;
+                    if ((amask >> c) & 1u) {
+                        const uint32_t a = (uint32_t)(c >> 1) + 1u;
+                        const uint32_t p = (c & 1) ? i + a : i - a;
+                        cslot[c] = lane_value(meta_slot, p & 63u);
+                        const float *src = ring + (size_t)cslot[c] * ROWF;
+#pragma unroll
+                        for (int r = 0; r < R; ++r) load_vec<VW>(src + eoff[r], &I[c][r * VW]);
+                    }
+                }
+
+                // (d) the next window's output rows start their trip from memory
+                uint32_t packv_next = pack_next;
+                float On[KC][E];
+                if (has_next) {
+                    if (lane_k == 0) packv_next = mraw_next.y | (1u << kIdBits);
+#pragma unroll
+                    for (int kk = 0; kk < KC; ++kk) {
+                        const uint32_t pk = lane_value(packv_next, (uint32_t)kk);
+#pragma unroll
+                        for (int x = 0; x < E; ++x) On[kk][x] = 0.0f;
+                        if ((uint32_t)kk <= N && (pk >> kIdBits)) load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, On[kk]);
+                    }
+                }
+
+                // (e) the window's arithmetic
                 if (nact) {
                     pairs_acc += nact;
-                    // context rows: snapshot into registers
-                    float I[NCTX][E];
-                    uint32_t cslot[NCTX];
-#pragma unroll
-                    for (int c = 0; c < NCTX; ++c) {
-                        cslot[c] = 0;
-#pragma unroll
-                        for (int x = 0; x < E; ++x) I[c][x] = 0.0f;
-                        if (ctx_active(c)) {
-                            const uint32_t a = (uint32_t)(c >> 1) + 1u;
-                            const uint32_t p = (c & 1) ? i + a : i - a;
-                            cslot[c] = lane_value(meta_slot, p & 63u);
-                            const float *src = ring + (size_t)cslot[c] * ROWF;
-#pragma unroll
-                            for (int r = 0; r < R; ++r) load_vec<VW>(src + eoff[r], &I[c][r * VW]);
-                        }
-                    }
-
                     for (uint32_t kb = 0; kb <= N; kb += KC) {
-                        // this lane's output row after the reduction, packed id | multiplicity
                         const uint32_t gk = kb + lane_k;
-                        uint32_t packv = 0;
-                        if (gk == 0) packv = (uint32_t)center | (1u << kIdBits);
-                        else if (gk <= N) packv = cb_pack[(size_t)j * N + (gk - 1)];
-                        const float mult_lane = (float)(packv >> kIdBits);
-
-                        float O[KC][E];
-                        uint32_t oid[KC], omult[KC];
+                        uint32_t pv = packv;
+                        if (kb) {                                   // further output rows: fetched here
+                            pv = (gk <= N) ? cb_pack[(size_t)j * N + (gk - 1)] : 0u;
 #pragma unroll
-                        for (int kk = 0; kk < KC; ++kk) {
-                            const uint32_t pk = lane_value(packv, (uint32_t)kk);   // lanes 0..KC-1 have lane_k = kk
-                            oid[kk] = pk & kIdMask;
-                            omult[kk] = (kb + kk <= N) ? (pk >> kIdBits) : 0u;
+                            for (int kk = 0; kk < KC; ++kk) {
+                                const uint32_t pk = lane_value(pv, (uint32_t)kk);
 #pragma unroll
-                            for (int x = 0; x < E; ++x) O[kk][x] = 0.0f;
-                            if (omult[kk]) {
-                                const float *src = A.syn1neg + (size_t)oid[kk] * A.ld;
-#pragma unroll
-                                for (int r = 0; r < R; ++r)
-                                    if (evalid[r]) load_vec<VW>(src + eoff[r], &O[kk][r * VW]);
+                                for (int x = 0; x < E; ++x) O[kk][x] = 0.0f;
+                                if (kb + kk <= N && (pk >> kIdBits)) load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, O[kk]);
                             }
                         }
-
+                        const float mult_lane = (gk <= N) ? (float)(pv >> kIdBits) : 0.0f;
+                        const float label = (gk == 0) ? 1.0f : 0.0f;
+                        const float gscale = alpha * mult_lane;
                         float dO[KC][E];
 #pragma unroll
                         for (int kk = 0; kk < KC; ++kk)
 #pragma unroll
                             for (int x = 0; x < E; ++x) dO[kk][x] = 0.0f;
 
+                        // NC context rows (slots q*CC .. q*CC+NC-1) against the KC output rows
+                        auto block = [&](auto nc_tag, auto masked_tag, auto q_tag) {
+                            constexpr int NC = decltype(nc_tag)::value;
+                            constexpr bool MASKED = decltype(masked_tag)::value;
+                            constexpr int q = decltype(q_tag)::value;
+                            float acc[NC * KC];
 #pragma unroll
-                        for (int q = 0; q < NQ; ++q) {
-                            if (2u * b <= (uint32_t)(q * CC)) continue;     // no pairing in this block of contexts
-                            float acc[CC * KC];
-#pragma unroll
-                            for (int cc = 0; cc < CC; ++cc) {
+                            for (int cc = 0; cc < NC; ++cc) {
                                 const int c = q * CC + cc;
 #pragma unroll
-                                for (int kk = 0; kk < KC; ++kk) acc[cc * KC + kk] = 0.0f;
-                                if (c < NCTX && ctx_active(c)) {
-#pragma unroll
-                                    for (int kk = 0; kk < KC; ++kk) {
-                                        float p = 0.0f;
+                                for (int kk = 0; kk < KC; ++kk) {
+                                    float p = 0.0f;
+                                    if (!MASKED || ((amask >> c) & 1u)) {
 #pragma unroll
                                         for (int x = 0; x < E; ++x) p = __builtin_fmaf(I[c][x], O[kk][x], p);
-                                        acc[cc * KC + kk] = p;
                                     }
+                                    acc[cc * KC + kk] = p;
                                 }
                             }
-                            const float xv = transpose_reduce<CC * KC>(acc, lane);
-
-                            // lane v = (context q*CC + lane_c, output kb + lane_k)
-                            const int gc = q * CC + lane_c;
-                            bool act = lane < CC * KC && gc < NCTX && gk <= N && mult_lane > 0.0f;
-                            {
-                                const uint32_t a = (uint32_t)(gc >> 1) + 1u;
-                                act = act && a <= b && ((gc & 1) ? (i + a < n_prod) : (i >= a));
-                            }
-                            const float ex = __expf(-xv);
-                            const float sig = __frcp_rn(1.0f + ex);
-                            const float label = (gk == 0) ? 1.0f : 0.0f;
-                            const float g = act ? alpha * mult_lane * (label - sig) : 0.0f;
+                            const float xv = transpose_reduce<NC * KC>(acc, lane);
+                            bool act = lane < NC * KC && mult_lane > 0.0f;
+                            if (MASKED) act = act && ((amask >> (q * CC + lane_c)) & 1u);
+                            const float sig = __frcp_rn(1.0f + __expf(-xv));
+                            const float g = act ? gscale * (label - sig) : 0.0f;
                             if (act) {
                                 const float z = (gk == 0) ? -xv : xv;       // softplus(z), stable form
-                                const float sp = fmaxf(z, 0.0f) + __logf(1.0f + __expf(-fabsf(z)));
-                                loss_acc += (double)(mult_lane * sp);
+                                loss_acc += (double)(mult_lane * (fmaxf(z, 0.0f) + __logf(1.0f + __expf(-fabsf(z)))));
                             }
-
 #pragma unroll
-                            for (int cc = 0; cc < CC; ++cc) {
+                            for (int cc = 0; cc < NC; ++cc) {
                                 const int c = q * CC + cc;
-                                if (c < NCTX && ctx_active(c)) {
+                                if (!MASKED || ((amask >> c) & 1u)) {
                                     float dI[E];
 #pragma unroll
                                     for (int x = 0; x < E; ++x) dI[x] = 0.0f;
@@ -458,43 +529,113 @@ __global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
                                             dO[kk][x] = __builtin_fmaf(gs, I[c][x], dO[kk][x]);
                                         }
                                     }
-                                    // the ring row accumulates; positions sharing a row add up
                                     float *dst = ring + (size_t)cslot[c] * ROWF;
+                                    if (shared_rows || kb) {
+                                        // positions that share a ring row add up (LDS float add)
 #pragma unroll
-                                    for (int r = 0; r < R; ++r)
+                                        for (int r = 0; r < R; ++r)
 #pragma unroll
-                                        for (int x = 0; x < VW; ++x)
-                                            __hip_atomic_fetch_add(dst + eoff[r] + x, dI[r * VW + x], __ATOMIC_RELAXED,
-                                                                   __HIP_MEMORY_SCOPE_WAVEFRONT);
+                                            for (int x = 0; x < VW; ++x)
+                                                __hip_atomic_fetch_add(dst + eoff[r] + x, dI[r * VW + x], __ATOMIC_RELAXED,
+                                                                       __HIP_MEMORY_SCOPE_WAVEFRONT);
+                                    } else {
+                                        // the row still equals the copy in registers: plain write of copy + delta
+#pragma unroll
+                                        for (int r = 0; r < R; ++r) {
+                                            float t[VW];
+#pragma unroll
+                                            for (int x = 0; x < VW; ++x) t[x] = I[c][r * VW + x] + dI[r * VW + x];
+                                            store_vec<VW>(dst + eoff[r], t);
+                                        }
+                                    }
+                                }
+                            }
+                        };
+                        using std::integral_constant;
+                        using T = integral_constant<bool, true>;
+                        using F = integral_constant<bool, false>;
+#define W2V_BLOCK(NCV, Q) block(integral_constant<int, (NCV)>{}, F{}, integral_constant<int, (Q)>{})
+                        bool done = false;
+                        if (interior) {
+                            // every one of the 2b nearest positions exists: straight-line code per width
+                            done = true;
+                            switch (b) {
+                            case 1: W2V_BLOCK(2, 0); break;
+                            case 2: W2V_BLOCK(4, 0); break;
+                            case 3: W2V_BLOCK(6, 0); break;
+                            case 4: W2V_BLOCK(8, 0); break;
+                            case 5: W2V_BLOCK(10, 0); break;
+                            default: done = false; break;
+                            }
+                            if constexpr (WCAP >= 10) {
+                                if (!done) {
+                                    done = true;
+                                    switch (b) {
+                                    case 6: W2V_BLOCK(10, 0); W2V_BLOCK(2, 1); break;
+                                    case 7: W2V_BLOCK(10, 0); W2V_BLOCK(4, 1); break;
+                                    case 8: W2V_BLOCK(10, 0); W2V_BLOCK(6, 1); break;
+                                    case 9: W2V_BLOCK(10, 0); W2V_BLOCK(8, 1); break;
+                                    case 10: W2V_BLOCK(10, 0); W2V_BLOCK(10, 1); break;
+                                    default: done = false; break;
+                                    }
                                 }
                             }
                         }
+#undef W2V_BLOCK
+                        if (!done) {
+                            // windows cut by a sentence end (and widths above 10): every slot checked
+                            block(integral_constant<int, (NCTX < CC ? NCTX : CC)>{}, T{}, integral_constant<int, 0>{});
+                            if constexpr (NQ > 1) if (amask >> CC) block(integral_constant<int, (NCTX - CC < CC ? NCTX - CC : CC)>{}, T{}, integral_constant<int, 1>{});
+                            if constexpr (NQ > 2) if (amask >> (2 * CC)) block(integral_constant<int, (NCTX - 2 * CC < CC ? NCTX - 2 * CC : CC)>{}, T{}, integral_constant<int, 2>{});
+                            if constexpr (NQ > 3) if (amask >> (3 * CC)) block(integral_constant<int, NCTX - 3 * CC>{}, T{}, integral_constant<int, 3>{});
+                        }
 
-                        // output rows go back (lock-free) once per window
+                        // (f) output rows go back (lock-free) once per window
 #pragma unroll
                         for (int kk = 0; kk < KC; ++kk) {
-                            if (omult[kk]) {
-                                float *dst = A.syn1neg + (size_t)oid[kk] * A.ld;
+                            const uint32_t pk = lane_value(pv, (uint32_t)kk);
+                            if (kb + kk <= N && (pk >> kIdBits)) {
+                                float t[E];
 #pragma unroll
-                                for (int r = 0; r < R; ++r) {
-                                    float t[VW];
-#pragma unroll
-                                    for (int x = 0; x < VW; ++x) t[x] = O[kk][r * VW + x] + dO[kk][r * VW + x];
-                                    if (evalid[r]) store_vec<VW>(dst + eoff[r], t);
-                                }
+                                for (int x = 0; x < E; ++x) t[x] = O[kk][x] + dO[kk][x];
+                                store_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, t);
                             }
                         }
                     }
                 }
 
-                // (every lane only ever touches its own elements of a ring row, so the ring needs no
-                // synchronisation between lanes)
+                // (g) rows of the next window that this window has just rewritten are fetched again
+                //     (a load issued after a store of the same wavefront sees the stored data)
+                if (has_next) {
+                    const uint32_t reload = nact ? (uni(mraw_next.x) >> 8) : 0u;
+                    if (reload) {
+#pragma unroll
+                        for (int kk = 0; kk < KC; ++kk)
+                            if ((reload >> kk) & 1u) {
+                                const uint32_t pk = lane_value(packv_next, (uint32_t)kk);
+                                load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, On[kk]);
+                            }
+                    }
+                }
+
+                // (h) the fetched context row enters the ring, the oldest position leaves it
+                //     (every lane only touches its own elements of a ring row: no barrier needed)
                 if (pend) {
                     float *dst = ring + (size_t)pend_slot * ROWF;
 #pragma unroll
                     for (int r = 0; r < R; ++r) store_vec<VW>(dst + eoff[r], pend_row + r * VW);
                 }
                 if (i >= W) ring_leave(i - W);
+
+                // (i) next window's scalars and rows become current
+                if (has_next) {
+                    mraw = mraw_next;
+                    packv = packv_next;
+#pragma unroll
+                    for (int kk = 0; kk < KC; ++kk)
+#pragma unroll
+                        for (int x = 0; x < E; ++x) O[kk][x] = On[kk][x];
+                }
             }
             i0 += nwin;
         }
@@ -568,7 +709,7 @@ bool pick_row_shape(uint32_t dim, uint32_t ld, RowShape *out)
 uint32_t train_lds_bytes(const KernelArgs &a, RowShape s)
 {
     const uint32_t rowf = kLanes * s.vw * s.r;
-    return (2 * a.window + 2) * rowf * 4u + FCAP * 8u + kLanes * 4u + kLanes * a.negatives * 4u;
+    return (2 * a.window + 2) * rowf * 4u + FCAP * 8u + kLanes * 16u + kLanes * a.negatives * 4u;
 }
 
 hipError_t launch_init_weights(float *syn0, float *syn1neg, uint32_t vocab, uint32_t dim, uint32_t ld,
