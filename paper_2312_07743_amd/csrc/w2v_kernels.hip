@@ -45,8 +45,11 @@ __device__ __forceinline__ float dpp_move(float v)
 }
 constexpr int kDppRowRor8 = 0x128, kDppHalfMirror = 0x141, kDppQuadXor2 = 0x4E, kDppQuadXor1 = 0xB1;
 
-// In-row stage of the transposing reduction: IN registers become ceil(IN/2); lanes whose index
-// has bit BIT set continue with the upper register of each pair.
+// Transposing reduction: sums each of M per-lane values over the 64 lanes; lane v (v < M) returns
+// the total of value v.  Stage B (32, 16, .., 1) pairs register i with register i+B: lanes with bit B
+// set continue with the upper one, so every stage halves the registers and the lanes a value is
+// spread over.  A register without a partner (i+B >= M) is carried on unchanged and its two halves
+// are folded once at the end, which costs one operation per stage instead of one per register.
 template <int IN, int BIT, int CTRL>
 __device__ __forceinline__ void row_stage(const float *in, float *out, int lane)
 {
@@ -54,42 +57,67 @@ __device__ __forceinline__ void row_stage(const float *in, float *out, int lane)
     const bool up = (lane & BIT) != 0;
 #pragma unroll
     for (int i = 0; i < OUT; ++i) {
-        const float a = in[i];
-        const float b = (i + BIT < IN) ? in[i + BIT] : 0.0f;
-        const float mine = up ? b : a;
-        const float theirs = up ? a : b;
-        out[i] = mine + dpp_move<CTRL>(theirs);
+        if (i + BIT < IN) {
+            const float a = in[i], b = in[i + BIT];
+            const float mine = up ? b : a;
+            const float theirs = up ? a : b;
+            out[i] = mine + dpp_move<CTRL>(theirs);
+        } else {
+            out[i] = in[i];
+        }
     }
 }
 
-// Sums each of M per-lane values over the 64 lanes; lane v (v < M) returns the total of value v.
 template <int M>
 __device__ __forceinline__ float transpose_reduce(const float *v, int lane)
 {
-    static_assert(M >= 1 && M <= 64, "at most one value per lane");
+    static_assert(M >= 8 && M <= 64, "between 8 and 64 values");
     constexpr int N32 = M < 32 ? M : 32;
     constexpr int N16 = N32 < 16 ? N32 : 16;
     constexpr int N8 = N16 < 8 ? N16 : 8;
-    constexpr int N4 = N8 < 4 ? N8 : 4;
-    constexpr int N2 = N4 < 2 ? N4 : 2;
-    float s32[N32], s16[N16], s8[N8], s4[N4], s2[N2], s1[1];
+    float s32[N32], s16[N16], s8[N8], s4[4], s2[2], s1[1];
 #pragma unroll
     for (int i = 0; i < N32; ++i) {   // halves: lanes >= 32 continue with value i+32
-        const float hi = (i + 32 < M) ? v[i + 32] : 0.0f;
-        auto p = __builtin_amdgcn_permlane32_swap(__float_as_uint(v[i]), __float_as_uint(hi), false, false);
-        s32[i] = __uint_as_float(p[0]) + __uint_as_float(p[1]);
+        if (i + 32 < M) {
+            auto p = __builtin_amdgcn_permlane32_swap(__float_as_uint(v[i]), __float_as_uint(v[i + 32]), false, false);
+            s32[i] = __uint_as_float(p[0]) + __uint_as_float(p[1]);
+        } else {
+            s32[i] = v[i];
+        }
     }
 #pragma unroll
     for (int i = 0; i < N16; ++i) {   // rows: odd rows continue with value i+16
-        const float hi = (i + 16 < N32) ? s32[i + 16] : 0.0f;
-        auto p = __builtin_amdgcn_permlane16_swap(__float_as_uint(s32[i]), __float_as_uint(hi), false, false);
-        s16[i] = __uint_as_float(p[0]) + __uint_as_float(p[1]);
+        if (i + 16 < N32) {
+            auto p = __builtin_amdgcn_permlane16_swap(__float_as_uint(s32[i]), __float_as_uint(s32[i + 16]), false, false);
+            s16[i] = __uint_as_float(p[0]) + __uint_as_float(p[1]);
+        } else {
+            s16[i] = s32[i];
+        }
     }
     row_stage<N16, 8, kDppRowRor8>(s16, s8, lane);
     row_stage<N8, 4, kDppHalfMirror>(s8, s4, lane);
-    row_stage<N4, 2, kDppQuadXor2>(s4, s2, lane);
-    row_stage<N2, 1, kDppQuadXor1>(s2, s1, lane);
-    return s1[0];
+    row_stage<4, 2, kDppQuadXor2>(s4, s2, lane);
+    row_stage<2, 1, kDppQuadXor1>(s2, s1, lane);
+    float x = s1[0];
+    // late folds, innermost first.  Lane l ends on the register chain of value (l mod B) at stage B
+    // (lower stages are always paired for M >= 8); that register had no partner iff (l mod B) + B >= M.
+    if constexpr (M < 16) {
+        const float t = x + dpp_move<kDppRowRor8>(x);
+        x = ((lane & 7) + 8 >= M) ? t : x;
+    }
+    if constexpr (M < 32) {
+        auto p = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+        const float t = __uint_as_float(p[0]) + __uint_as_float(p[1]);
+        constexpr int B = M < 16 ? 8 : 16;          // bits of the chain index known at this stage
+        x = ((lane & (B - 1)) + 16 >= M) ? t : x;
+    }
+    {
+        auto p = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+        const float t = __uint_as_float(p[0]) + __uint_as_float(p[1]);
+        constexpr int B = M < 16 ? 8 : (M < 32 ? 16 : 32);
+        x = ((lane & (B - 1)) + 32 >= M) ? t : x;
+    }
+    return x;
 }
 
 // plain 64-lane sum, every lane gets the total (used once per wavefront for the loss)
@@ -429,23 +457,6 @@ __global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
                 const uint32_t nact = nl + nr;
                 const bool interior = nl == b && nr == b;
 
-                float I[NCTX][E];
-                uint32_t cslot[NCTX];
-#pragma unroll
-                for (int c = 0; c < NCTX; ++c) {
-                    cslot[c] = 0;
-#pragma unroll
-                    for (int x = 0; x < E; ++x) I[c][x] = 0.0f;
-                    if ((amask >> c) & 1u) {
-                        const uint32_t a = (uint32_t)(c >> 1) + 1u;
-                        const uint32_t p = (c & 1) ? i + a : i - a;
-                        cslot[c] = lane_value(meta_slot, p & 63u);
-                        const float *src = ring + (size_t)cslot[c] * ROWF;
-#pragma unroll
-                        for (int r = 0; r < R; ++r) load_vec<VW>(src + eoff[r], &I[c][r * VW]);
-                    }
-                }
-
                 // (d) the next window's output rows start their trip from memory
                 uint32_t packv_next = pack_next;
                 float On[KC][E];
@@ -460,9 +471,28 @@ __global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
                     }
                 }
 
-                // (e) the window's arithmetic
-                if (nact) {
-                    pairs_acc += nact;
+                // (e) the window's arithmetic over context slots 0..NCW-1; MASKED: slot c takes part only
+                //     if bit c of amask is set (windows cut by a sentence end), otherwise all of them do
+                auto do_window = [&](auto ncw_tag, auto masked_tag) {
+                    constexpr int NCW = decltype(ncw_tag)::value;
+                    constexpr bool MASKED = decltype(masked_tag)::value;
+                    constexpr int NQW = (NCW + CC - 1) / CC;
+                    float I[NCW][E];
+                    uint32_t cslot[NCW];
+#pragma unroll
+                    for (int c = 0; c < NCW; ++c) {
+                        cslot[c] = 0;
+#pragma unroll
+                        for (int x = 0; x < E; ++x) I[c][x] = 0.0f;
+                        if (!MASKED || ((amask >> c) & 1u)) {
+                            const uint32_t a = (uint32_t)(c >> 1) + 1u;
+                            const uint32_t p = (c & 1) ? i + a : i - a;
+                            cslot[c] = lane_value(meta_slot, p & 63u);
+                            const float *src = ring + (size_t)cslot[c] * ROWF;
+#pragma unroll
+                            for (int r = 0; r < R; ++r) load_vec<VW>(src + eoff[r], &I[c][r * VW]);
+                        }
+                    }
                     for (uint32_t kb = 0; kb <= N; kb += KC) {
                         const uint32_t gk = kb + lane_k;
                         uint32_t pv = packv;
@@ -485,38 +515,40 @@ __global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
 #pragma unroll
                             for (int x = 0; x < E; ++x) dO[kk][x] = 0.0f;
 
-                        // NC context rows (slots q*CC .. q*CC+NC-1) against the KC output rows
-                        auto block = [&](auto nc_tag, auto masked_tag, auto q_tag) {
-                            constexpr int NC = decltype(nc_tag)::value;
-                            constexpr bool MASKED = decltype(masked_tag)::value;
-                            constexpr int q = decltype(q_tag)::value;
-                            float acc[NC * KC];
 #pragma unroll
-                            for (int cc = 0; cc < NC; ++cc) {
+                        for (int q = 0; q < NQW; ++q) {
+                            // NC context rows (slots q*CC .. q*CC+NC-1) against the KC output rows
+                            constexpr int NCLAST = NCW - (NQW - 1) * CC;
+                            const int NC = (q == NQW - 1) ? NCLAST : CC;
+                            if (MASKED && !(amask >> (q * CC))) break;
+                            float acc[CC * KC];
+#pragma unroll
+                            for (int cc = 0; cc < CC; ++cc) {
                                 const int c = q * CC + cc;
 #pragma unroll
                                 for (int kk = 0; kk < KC; ++kk) {
                                     float p = 0.0f;
-                                    if (!MASKED || ((amask >> c) & 1u)) {
+                                    if (cc < NC && (!MASKED || ((amask >> c) & 1u))) {
 #pragma unroll
                                         for (int x = 0; x < E; ++x) p = __builtin_fmaf(I[c][x], O[kk][x], p);
                                     }
                                     acc[cc * KC + kk] = p;
                                 }
                             }
-                            const float xv = transpose_reduce<NC * KC>(acc, lane);
+                            const float xraw = (q == NQW - 1) ? transpose_reduce<NCLAST * KC>(acc, lane)
+                                                              : transpose_reduce<CC * KC>(acc, lane);
                             bool act = lane < NC * KC && mult_lane > 0.0f;
                             if (MASKED) act = act && ((amask >> (q * CC + lane_c)) & 1u);
-                            const float sig = __frcp_rn(1.0f + __expf(-xv));
-                            const float g = act ? gscale * (label - sig) : 0.0f;
-                            if (act) {
-                                const float z = (gk == 0) ? -xv : xv;       // softplus(z), stable form
-                                loss_acc += (double)(mult_lane * (fmaxf(z, 0.0f) + __logf(1.0f + __expf(-fabsf(z)))));
-                            }
+                            // sigmoid and log-loss from u = 1 + exp(-x): sigma = 1/u, -log sigma(x) = log u,
+                            // -log sigma(-x) = x + log u   (x clamped where exp would overflow)
+                            const float xv = __builtin_amdgcn_fmed3f(xraw, -80.0f, 80.0f);
+                            const float u = 1.0f + __expf(-xv);
+                            const float g = act ? gscale * (label - __frcp_rn(u)) : 0.0f;
+                            if (act) loss_acc += (double)(mult_lane * (__logf(u) + ((gk == 0) ? 0.0f : xv)));
 #pragma unroll
-                            for (int cc = 0; cc < NC; ++cc) {
+                            for (int cc = 0; cc < CC; ++cc) {
                                 const int c = q * CC + cc;
-                                if (!MASKED || ((amask >> c) & 1u)) {
+                                if (cc < NC && (!MASKED || ((amask >> c) & 1u))) {
                                     float dI[E];
 #pragma unroll
                                     for (int x = 0; x < E; ++x) dI[x] = 0.0f;
@@ -550,44 +582,6 @@ __global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
                                     }
                                 }
                             }
-                        };
-                        using std::integral_constant;
-                        using T = integral_constant<bool, true>;
-                        using F = integral_constant<bool, false>;
-#define W2V_BLOCK(NCV, Q) block(integral_constant<int, (NCV)>{}, F{}, integral_constant<int, (Q)>{})
-                        bool done = false;
-                        if (interior) {
-                            // every one of the 2b nearest positions exists: straight-line code per width
-                            done = true;
-                            switch (b) {
-                            case 1: W2V_BLOCK(2, 0); break;
-                            case 2: W2V_BLOCK(4, 0); break;
-                            case 3: W2V_BLOCK(6, 0); break;
-                            case 4: W2V_BLOCK(8, 0); break;
-                            case 5: W2V_BLOCK(10, 0); break;
-                            default: done = false; break;
-                            }
-                            if constexpr (WCAP >= 10) {
-                                if (!done) {
-                                    done = true;
-                                    switch (b) {
-                                    case 6: W2V_BLOCK(10, 0); W2V_BLOCK(2, 1); break;
-                                    case 7: W2V_BLOCK(10, 0); W2V_BLOCK(4, 1); break;
-                                    case 8: W2V_BLOCK(10, 0); W2V_BLOCK(6, 1); break;
-                                    case 9: W2V_BLOCK(10, 0); W2V_BLOCK(8, 1); break;
-                                    case 10: W2V_BLOCK(10, 0); W2V_BLOCK(10, 1); break;
-                                    default: done = false; break;
-                                    }
-                                }
-                            }
-                        }
-#undef W2V_BLOCK
-                        if (!done) {
-                            // windows cut by a sentence end (and widths above 10): every slot checked
-                            block(integral_constant<int, (NCTX < CC ? NCTX : CC)>{}, T{}, integral_constant<int, 0>{});
-                            if constexpr (NQ > 1) if (amask >> CC) block(integral_constant<int, (NCTX - CC < CC ? NCTX - CC : CC)>{}, T{}, integral_constant<int, 1>{});
-                            if constexpr (NQ > 2) if (amask >> (2 * CC)) block(integral_constant<int, (NCTX - 2 * CC < CC ? NCTX - 2 * CC : CC)>{}, T{}, integral_constant<int, 2>{});
-                            if constexpr (NQ > 3) if (amask >> (3 * CC)) block(integral_constant<int, NCTX - 3 * CC>{}, T{}, integral_constant<int, 3>{});
                         }
 
                         // (f) output rows go back (lock-free) once per window
@@ -602,6 +596,41 @@ __global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
                             }
                         }
                     }
+                };
+                if (nact) {
+                    pairs_acc += nact;
+                    using std::integral_constant;
+                    using T = integral_constant<bool, true>;
+                    using F = integral_constant<bool, false>;
+#define W2V_WIN(NCV) do_window(integral_constant<int, (NCV)>{}, F{})
+                    bool done = false;
+                    if (interior) {
+                        // every one of the 2b nearest positions exists: straight-line code per width
+                        done = true;
+                        switch (b) {
+                        case 1: W2V_WIN(2); break;
+                        case 2: W2V_WIN(4); break;
+                        case 3: W2V_WIN(6); break;
+                        case 4: W2V_WIN(8); break;
+                        case 5: W2V_WIN(10); break;
+                        default: done = false; break;
+                        }
+                        if constexpr (WCAP >= 10) {
+                            if (!done) {
+                                done = true;
+                                switch (b) {
+                                case 6: W2V_WIN(12); break;
+                                case 7: W2V_WIN(14); break;
+                                case 8: W2V_WIN(16); break;
+                                case 9: W2V_WIN(18); break;
+                                case 10: W2V_WIN(20); break;
+                                default: done = false; break;
+                                }
+                            }
+                        }
+                    }
+#undef W2V_WIN
+                    if (!done) do_window(integral_constant<int, NCTX>{}, T{});   // cut by a sentence end, or wide
                 }
 
                 // (g) rows of the next window that this window has just rewritten are fetched again
