@@ -8,7 +8,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libw2v.so")
-SOURCES = ["w2v_api.hip", "w2v_kernels.hip", "w2v_naive.hip"]
+SOURCES = ["w2v_api.hip", "w2v_kernels.hip", "w2v_naive.hip"] + [
+    f"w2v_train_v{vw}r{r}m{m}.hip" for vw, r in ((2, 1), (1, 5), (4, 2), (4, 1), (1, 1)) for m in (0, 1)]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -28,7 +29,7 @@ def _compile(src: str, extra) -> str:
 
 def build(extra=()) -> str:
     os.makedirs(BUILD, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
+    with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 4, 16)) as ex:
         objs = list(ex.map(lambda s: _compile(s, extra), SOURCES))
     subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs)
     return LIB

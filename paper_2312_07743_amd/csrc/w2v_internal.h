@@ -40,6 +40,8 @@ struct KernelArgs {
     uint32_t           subsample;      // 0: every threshold is "always keep", thr is not read
 };
 
+using TrainFn = void (*)(KernelArgs);
+
 // How a row of `dim` floats is spread over the 64 lanes of a wavefront: R chunks of VW
 // consecutive floats per lane, chunk r of lane l starting at float (r*64 + l)*VW.
 struct RowShape { int vw, r; };

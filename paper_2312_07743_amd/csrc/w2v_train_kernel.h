@@ -1,0 +1,653 @@
+// The window kernel of the SGNS trainer for gfx950 (MI355X) and its device helpers.  Included by
+// the translation units that instantiate it (one per row shape, see w2v_train_inst.inc).
+//
+// Window kernel in one paragraph (paper Sections 3.1, 3.2, 4.2, re-mapped to CDNA4):
+// one wavefront owns one sentence at a time (work queue over sentences, lock-free between
+// sentences).  The 64 lanes split every embedding row; the N+1 output rows of a window
+// (target + shared negatives) sit in VGPRs while the window lasts, the context rows sit in an
+// LDS ring from the moment the window span reaches them until it has passed them.  All
+// (context, output) dot products of a window are formed as per-lane partial sums and reduced
+// together by one transposing butterfly (v_permlane32_swap / v_permlane16_swap / DPP), after
+// which lane v holds pairing v and the sigmoid is evaluated lane-parallel.  The window's
+// update is the sum over all pairings evaluated at the values the rows had when the window
+// began.  Sampling decisions (subsampling, width, negatives) are computed lane-parallel for
+// 64 positions at a time from a counter-based generator.
+#pragma once
+#include "w2v_internal.h"
+#include "w2v_rng.h"
+
+#include <type_traits>
+
+namespace w2v {
+namespace {
+
+constexpr int kLanes = 64;
+constexpr int KC = 6;              // output rows held in registers at once
+constexpr int CC = 10;             // context rows whose pairings are reduced together (CC*KC <= 64)
+constexpr int FCAP = 256;          // kept-token FIFO entries per wavefront (power of two)
+constexpr uint32_t kIdBits = 27;
+constexpr uint32_t kIdMask = (1u << kIdBits) - 1u;
+
+__device__ __forceinline__ uint32_t uni(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ uint64_t uni64(uint64_t v)
+{
+    return ((uint64_t)uni((uint32_t)(v >> 32)) << 32) | uni((uint32_t)v);
+}
+__device__ __forceinline__ float lane_value(float v, uint32_t lane)
+{
+    return __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(v), lane));
+}
+__device__ __forceinline__ uint32_t lane_value(uint32_t v, uint32_t lane) { return __builtin_amdgcn_readlane(v, lane); }
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+constexpr int kDppRowRor8 = 0x128, kDppHalfMirror = 0x141, kDppQuadXor2 = 0x4E, kDppQuadXor1 = 0xB1;
+
+// Transposing reduction: sums each of M per-lane values over the 64 lanes; lane v (v < M) returns
+// the total of value v.  Stage B (32, 16, .., 1) pairs register i with register i+B: lanes with bit B
+// set continue with the upper one, so every stage halves the registers and the lanes a value is
+// spread over.  A register without a partner (i+B >= M) is carried on unchanged and its two halves
+// are folded once at the end, which costs one operation per stage instead of one per register.
+template <int IN, int BIT, int CTRL>
+__device__ __forceinline__ void row_stage(const float *in, float *out, int lane)
+{
+    constexpr int OUT = IN > BIT ? BIT : IN;
+    const bool up = (lane & BIT) != 0;
+#pragma unroll
+    for (int i = 0; i < OUT; ++i) {
+        if (i + BIT < IN) {
+            const float a = in[i], b = in[i + BIT];
+            const float mine = up ? b : a;
+            const float theirs = up ? a : b;
+            out[i] = mine + dpp_move<CTRL>(theirs);
+        } else {
+            out[i] = in[i];
+        }
+    }
+}
+
+template <int M>
+__device__ __forceinline__ float transpose_reduce(const float *v, int lane)
+{
+    static_assert(M >= 8 && M <= 64, "between 8 and 64 values");
+    constexpr int N32 = M < 32 ? M : 32;
+    constexpr int N16 = N32 < 16 ? N32 : 16;
+    constexpr int N8 = N16 < 8 ? N16 : 8;
+    float s32[N32], s16[N16], s8[N8], s4[4], s2[2], s1[1];
+#pragma unroll
+    for (int i = 0; i < N32; ++i) {   // halves: lanes >= 32 continue with value i+32
+        if (i + 32 < M) {
+            auto p = __builtin_amdgcn_permlane32_swap(__float_as_uint(v[i]), __float_as_uint(v[i + 32]), false, false);
+            s32[i] = __uint_as_float(p[0]) + __uint_as_float(p[1]);
+        } else {
+            s32[i] = v[i];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < N16; ++i) {   // rows: odd rows continue with value i+16
+        if (i + 16 < N32) {
+            auto p = __builtin_amdgcn_permlane16_swap(__float_as_uint(s32[i]), __float_as_uint(s32[i + 16]), false, false);
+            s16[i] = __uint_as_float(p[0]) + __uint_as_float(p[1]);
+        } else {
+            s16[i] = s32[i];
+        }
+    }
+    row_stage<N16, 8, kDppRowRor8>(s16, s8, lane);
+    row_stage<N8, 4, kDppHalfMirror>(s8, s4, lane);
+    row_stage<4, 2, kDppQuadXor2>(s4, s2, lane);
+    row_stage<2, 1, kDppQuadXor1>(s2, s1, lane);
+    float x = s1[0];
+    // late folds, innermost first.  Lane l ends on the register chain of value (l mod B) at stage B
+    // (lower stages are always paired for M >= 8); that register had no partner iff (l mod B) + B >= M.
+    if constexpr (M < 16) {
+        const float t = x + dpp_move<kDppRowRor8>(x);
+        x = ((lane & 7) + 8 >= M) ? t : x;
+    }
+    if constexpr (M < 32) {
+        auto p = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+        const float t = __uint_as_float(p[0]) + __uint_as_float(p[1]);
+        constexpr int B = M < 16 ? 8 : 16;          // bits of the chain index known at this stage
+        x = ((lane & (B - 1)) + 16 >= M) ? t : x;
+    }
+    {
+        auto p = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+        const float t = __uint_as_float(p[0]) + __uint_as_float(p[1]);
+        constexpr int B = M < 16 ? 8 : (M < 32 ? 16 : 32);
+        x = ((lane & (B - 1)) + 32 >= M) ? t : x;
+    }
+    return x;
+}
+
+// plain 64-lane sum, every lane gets the total (used once per wavefront for the loss)
+__device__ __forceinline__ double wave_sum(double x)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, kLanes);
+    return x;
+}
+
+template <int VW> __device__ __forceinline__ void load_vec(const float *p, float *dst)
+{
+    if constexpr (VW == 1) { dst[0] = *p; }
+    else if constexpr (VW == 2) { const float2 t = *reinterpret_cast<const float2 *>(p); dst[0] = t.x; dst[1] = t.y; }
+    else { const float4 t = *reinterpret_cast<const float4 *>(p); dst[0] = t.x; dst[1] = t.y; dst[2] = t.z; dst[3] = t.w; }
+}
+template <int VW> __device__ __forceinline__ void store_vec(float *p, const float *src)
+{
+    if constexpr (VW == 1) { *p = src[0]; }
+    else if constexpr (VW == 2) { *reinterpret_cast<float2 *>(p) = make_float2(src[0], src[1]); }
+    else { *reinterpret_cast<float4 *>(p) = make_float4(src[0], src[1], src[2], src[3]); }
+}
+
+// learning rate of the sentence that starts at global token offset `start` of this epoch
+__device__ __forceinline__ float sentence_lr(const KernelArgs &A, uint64_t start)
+{
+    const double done = (double)(A.lr_done_base + start);
+    double frac = 1.0 - done / (double)A.lr_all;
+    if (frac < A.lr_min_frac) frac = A.lr_min_frac;
+    return (float)(A.lr0 * frac);
+}
+
+// ---------------------------------------------------------------------------------------------
+// the window kernel
+// ---------------------------------------------------------------------------------------------
+// Per-window scalars the sampling stage leaves in LDS for the window loop (one uint4 per window):
+//   x = width b | (reload bits << 8) | (dup << 16)
+//       reload bit k': output row k' (k' < KC) of this window is also an output row of the previous
+//       window, so a copy fetched before that window's write-back is stale;
+//       dup: two context positions of the window hold the same word and share a ring row
+//   y = target word, z = word of the kept position that enters the ring at this window (or none)
+constexpr uint32_t kNoWord = 0xFFFFFFFFu;
+
+// MULTI: more than KC output rows per window (N + 1 > KC), handled KC at a time
+template <int VW, int R, int WCAP, bool FULL, bool MULTI>
+__global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
+{
+    constexpr int E = VW * R;            // floats of a row per lane
+    constexpr int ROWF = kLanes * E;     // floats of a ring row in LDS
+    constexpr int NCTX = 2 * WCAP;       // context positions a window can have
+
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    const int lane = threadIdx.x;
+    const uint32_t W = A.window, N = A.negatives;
+    const uint32_t nslots = 2 * W + 2;
+    float *ring = reinterpret_cast<float *>(lds_raw);
+    int32_t *kw = reinterpret_cast<int32_t *>(ring + (size_t)nslots * ROWF);  // kept word ids (FIFO)
+    uint32_t *kp = reinterpret_cast<uint32_t *>(kw + FCAP);                  // their offsets in the sentence
+    uint4 *cb_meta = reinterpret_cast<uint4 *>(kp + FCAP);                   // per-window scalars of the chunk
+    uint32_t *cb_pack = reinterpret_cast<uint32_t *>(cb_meta + kLanes);      // [64][N] negative id | multiplicity<<27
+
+    // element offsets of this lane inside a row, and whether they exist (dim may not fill 64*E)
+    int eoff[R];
+    bool evalid[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        eoff[r] = (r * kLanes + lane) * VW;
+        evalid[r] = FULL || (uint32_t)eoff[r] < A.dim;
+    }
+    const int lane_c = lane / KC, lane_k = lane % KC;   // pairing handled by this lane after the reduction
+
+    double loss_acc = 0.0;
+    unsigned long long pairs_acc = 0, dropped_acc = 0, kept_acc = 0;
+
+    auto load_row = [&](const float *row, float *dst) {           // global row -> registers (zeros beyond dim)
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+#pragma unroll
+            for (int x = 0; x < VW; ++x) dst[r * VW + x] = 0.0f;
+            if (evalid[r]) load_vec<VW>(row + eoff[r], dst + r * VW);
+        }
+    };
+    auto store_row = [&](float *row, const float *src) {          // registers -> global row
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            if (evalid[r]) store_vec<VW>(row + eoff[r], src + r * VW);
+    };
+
+    for (;;) {
+        // ---- next sentence from the work queue -------------------------------------------------
+        unsigned long long s_raw = 0;
+        if (lane == 0) s_raw = atomicAdd(&A.accum->next_sentence, 1ull);
+        const uint64_t s = uni64(s_raw);
+        if (s >= A.n_sent) break;
+        const uint64_t t0 = uni64(A.sent_off[s]);
+        const uint64_t t1 = uni64(A.sent_off[s + 1]);
+        const uint32_t len = (t1 > t0) ? (uint32_t)(t1 - t0) : 0u;
+        const float alpha = sentence_lr(A, A.first_pos + t0);
+
+        int32_t meta_word = -1;       // lane p&63: word of resident kept position p (-1: none)
+        uint32_t meta_slot = 0;       // lane p&63: its ring slot
+        uint32_t free_slots = (nslots >= 32) ? 0xFFFFFFFFu : ((1u << nslots) - 1u);
+        uint32_t free_hi = (nslots > 32) ? ((1u << (nslots - 32)) - 1u) : 0u;   // slots 32..33 (W = 16)
+        uint32_t n_prod = 0;          // kept tokens found so far
+        uint32_t raw_next = 0;        // next token offset to look at
+        uint32_t n_ins = 0;           // kept positions [0, n_ins) have entered the ring
+        uint32_t i0 = 0;              // first window of the current chunk
+
+        auto take_slot = [&]() -> uint32_t {
+            uint32_t sl;
+            if (free_slots) { sl = __builtin_ctz(free_slots); free_slots &= free_slots - 1u; }
+            else { sl = 32u + __builtin_ctz(free_hi); free_hi &= free_hi - 1u; }
+            return sl;
+        };
+        auto give_slot = [&](uint32_t sl) {
+            if (sl < 32u) free_slots |= 1u << sl; else free_hi |= 1u << (sl - 32u);
+        };
+        // kept position p (word `word`) enters the ring; true when its row must be fetched into `slot`
+        auto ring_enter = [&](uint32_t p, int32_t word, uint32_t &slot) -> bool {
+            const uint64_t same = __ballot(meta_word == word);
+            bool fetch;
+            if (same) { slot = lane_value(meta_slot, (uint32_t)__builtin_ctzll(same)); fetch = false; }
+            else { slot = take_slot(); fetch = true; }
+            if (lane == (int)(p & 63u)) { meta_word = word; meta_slot = slot; }
+            return fetch;
+        };
+        // position p leaves the ring; its row goes back to syn0 unless another position shares it
+        auto ring_leave = [&](uint32_t p) {
+            const uint32_t l = p & 63u;
+            const uint32_t slot = lane_value(meta_slot, l);
+            const int32_t word = (int32_t)lane_value((uint32_t)meta_word, l);
+            if (lane == (int)l) meta_word = -1;
+            const uint64_t shared = __ballot(meta_word >= 0 && meta_slot == slot);
+            if (!shared) {
+                const float *src = ring + (size_t)slot * ROWF;
+                float *dst = A.syn0 + (size_t)word * A.ld;
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    float t[VW];
+                    load_vec<VW>(src + eoff[r], t);
+                    if (evalid[r]) store_vec<VW>(dst + eoff[r], t);
+                }
+                give_slot(slot);
+            }
+        };
+
+        for (;;) {
+            // ---- look at more tokens until this chunk's windows know all their context ----------
+            while (n_prod < i0 + kLanes + W + 1 && raw_next < len) {
+                const uint32_t off = raw_next + lane;
+                bool k = false;
+                int32_t w = -1;
+                if (off < len) {
+                    w = A.tokens[t0 + off];
+                    k = w >= 0 && (uint32_t)w < A.vocab;
+                    if (!k) ++dropped_acc;
+                    if (k && A.subsample) {
+                        const uint32_t th = A.thr[w];
+                        if (th != 0xFFFFFFFFu) k = keep_decision(position_base(A.key, A.first_pos + t0 + off), th);
+                    }
+                }
+                const uint64_t km = __ballot(k);
+                if (k) {
+                    const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(km >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)km, 0u));
+                    kw[(n_prod + rank) & (FCAP - 1)] = w;
+                    kp[(n_prod + rank) & (FCAP - 1)] = off;
+                }
+                n_prod += (uint32_t)__popcll(km);
+                raw_next += kLanes;
+            }
+            __syncthreads();
+            if (i0 >= n_prod) break;
+            const uint32_t nwin = (n_prod - i0 < (uint32_t)kLanes) ? n_prod - i0 : (uint32_t)kLanes;
+
+            // ---- width and negatives of the chunk's windows, one window per lane ----------------
+            int32_t my_w = -1;
+            uint32_t my_b = 0, my_enter = kNoWord;
+            if ((uint32_t)lane < nwin) {
+                const uint32_t idx = (i0 + lane) & (FCAP - 1);
+                my_w = kw[idx];
+                const uint64_t base = position_base(A.key, A.first_pos + t0 + kp[idx]);
+                my_b = window_width(base, W, A.window_mode);
+                const uint32_t pe = i0 + lane + W + 1;
+                if (pe < n_prod) my_enter = (uint32_t)kw[pe & (FCAP - 1)];
+                uint32_t *pk = cb_pack + (size_t)lane * N;
+                for (uint32_t k = 0; k < N; ++k) pk[k] = (uint32_t)A.table[negative_slot(base, k, A.table_size)];
+                // multiplicity: 0 for a negative equal to the target and for repeats of an earlier
+                // negative, otherwise the number of times the id was drawn
+                for (uint32_t k = 0; k < N; ++k) {
+                    const uint32_t id = pk[k] & kIdMask;
+                    uint32_t m = (id == (uint32_t)my_w) ? 0u : 1u;
+                    for (uint32_t k1 = 0; k1 < k && m; ++k1) if ((pk[k1] & kIdMask) == id) m = 0u;
+                    if (m) for (uint32_t k2 = k + 1; k2 < N; ++k2) if ((pk[k2] & kIdMask) == id) ++m;
+                    pk[k] = id | (m << kIdBits);
+                }
+            }
+            __syncthreads();
+            if ((uint32_t)lane < nwin) {
+                // which of my first KC output rows does the previous window also write?
+                uint32_t reload = 0;
+                if (lane > 0) {
+                    const uint32_t pw = (uint32_t)kw[(i0 + lane - 1) & (FCAP - 1)];
+                    const uint32_t *mine = cb_pack + (size_t)lane * N;
+                    const uint32_t *prev = cb_pack + (size_t)(lane - 1) * N;
+                    for (uint32_t kk = 0; kk < (uint32_t)KC && kk <= N; ++kk) {
+                        uint32_t id;
+                        if (kk == 0) id = (uint32_t)my_w;
+                        else { const uint32_t p = mine[kk - 1]; if ((p >> kIdBits) == 0) continue; id = p & kIdMask; }
+                        bool hit = id == pw;
+                        for (uint32_t k = 0; k < N && !hit; ++k) hit = (prev[k] >> kIdBits) != 0 && (prev[k] & kIdMask) == id;
+                        if (hit) reload |= 1u << kk;
+                    }
+                }
+                // do two context positions of my window hold the same word (and so share a ring row)?
+                uint32_t dup = 0;
+                {
+                    const uint32_t me = i0 + lane;
+                    const uint32_t lo = (me > my_b) ? me - my_b : 0u;
+                    const uint32_t hi = (me + my_b < n_prod) ? me + my_b : n_prod - 1u;
+                    for (uint32_t p1 = lo; p1 < hi; ++p1) {
+                        if (p1 == me) continue;
+                        const int32_t w1 = kw[p1 & (FCAP - 1)];
+                        for (uint32_t p2 = p1 + 1; p2 <= hi; ++p2)
+                            if (p2 != me && kw[p2 & (FCAP - 1)] == w1) dup = 1u;
+                    }
+                }
+                cb_meta[lane] = make_uint4(my_b | (reload << 8) | (dup << 16), (uint32_t)my_w, my_enter, 0u);
+            }
+            __syncthreads();
+
+            // ---- first chunk of a sentence: positions 0..W enter the ring before the first window ----
+            if (i0 == 0) {
+                const uint32_t want = (W + 1 < n_prod) ? W + 1 : n_prod;
+                while (n_ins < want) {
+                    const int32_t word = (int32_t)uni((uint32_t)kw[n_ins & (FCAP - 1)]);
+                    uint32_t slot;
+                    if (ring_enter(n_ins, word, slot)) {
+                        float t[E];
+                        load_row(A.syn0 + (size_t)word * A.ld, t);
+                        float *dst = ring + (size_t)slot * ROWF;
+#pragma unroll
+                        for (int r = 0; r < R; ++r) store_vec<VW>(dst + eoff[r], t + r * VW);
+                    }
+                    ++n_ins;
+                }
+            }
+
+            // ---- the chunk's windows, strictly in order -----------------------------------------
+            // scalars and output rows of the first window; later windows get theirs one window ahead
+            uint4 mraw = cb_meta[0];
+            uint32_t packv = 0;
+            if (lane_k >= 1 && (uint32_t)lane_k <= N) packv = cb_pack[lane_k - 1];
+            if (lane_k == 0) packv = mraw.y | (1u << kIdBits);
+            float O[KC][E];
+#pragma unroll
+            for (int kk = 0; kk < KC; ++kk) {
+                const uint32_t pk = lane_value(packv, (uint32_t)kk);
+#pragma unroll
+                for (int x = 0; x < E; ++x) O[kk][x] = 0.0f;
+                if ((uint32_t)kk <= N && (pk >> kIdBits)) load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, O[kk]);
+            }
+
+            for (uint32_t j = 0; j < nwin; ++j) {
+                const uint32_t i = i0 + j;
+                const uint32_t b = uni(mraw.x) & 0xFFu;
+                const bool shared_rows = (uni(mraw.x) >> 16) & 1u;
+                const uint32_t enter_word = uni(mraw.z);
+                const bool has_next = j + 1 < nwin;
+
+                // (a) ask LDS for the next window's scalars now, use them after the ring work below
+                uint4 mraw_next = make_uint4(0u, 0u, kNoWord, 0u);
+                uint32_t pack_next = 0;
+                if (has_next) {
+                    mraw_next = cb_meta[j + 1];
+                    if (lane_k >= 1 && (uint32_t)lane_k <= N) pack_next = cb_pack[(size_t)(j + 1) * N + (lane_k - 1)];
+                }
+
+                // (b) the kept position i+W+1 enters the span: its row is fetched now and written into
+                //     the ring after this window's arithmetic
+                uint32_t pend_slot = 0;
+                bool pend = false;
+                float pend_row[E] = {};
+                if (enter_word != kNoWord) {
+                    pend = ring_enter(n_ins, (int32_t)enter_word, pend_slot);
+                    if (pend) load_row(A.syn0 + (size_t)enter_word * A.ld, pend_row);
+                    ++n_ins;
+                }
+
+                // (c) contexts of this window: slot c <-> distance a=(c>>1)+1, right side if c odd;
+                //     amask bit c set when that position exists and lies within the width
+                const uint32_t nl = (b < i) ? b : i;
+                const uint32_t nr = (b < n_prod - 1 - i) ? b : n_prod - 1 - i;
+                const uint32_t amask = uni((0x55555555u & (uint32_t)((1ull << (2 * nl)) - 1ull)) | (0xAAAAAAAAu & (uint32_t)((1ull << (2 * nr)) - 1ull)));
+                const uint32_t nact = nl + nr;
+                const bool interior = nl == b && nr == b;
+
+                // (d) the next window's output rows start their trip from memory
+                uint32_t packv_next = pack_next;
+                float On[KC][E];
+                if (has_next) {
+                    if (lane_k == 0) packv_next = mraw_next.y | (1u << kIdBits);
+#pragma unroll
+                    for (int kk = 0; kk < KC; ++kk) {
+                        const uint32_t pk = lane_value(packv_next, (uint32_t)kk);
+#pragma unroll
+                        for (int x = 0; x < E; ++x) On[kk][x] = 0.0f;
+                        if ((uint32_t)kk <= N && (pk >> kIdBits)) load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, On[kk]);
+                    }
+                }
+
+                // (e) the window's arithmetic over context slots 0..NCW-1; MASKED: slot c takes part only
+                //     if bit c of amask is set (windows cut by a sentence end), otherwise all of them do
+                auto do_window = [&](auto ncw_tag, auto masked_tag) {
+                    constexpr int NCW = decltype(ncw_tag)::value;
+                    constexpr bool MASKED = decltype(masked_tag)::value;
+                    constexpr int NQW = (NCW + CC - 1) / CC;
+                    float I[NCW][E];
+                    uint32_t cslot[NCW];
+#pragma unroll
+                    for (int c = 0; c < NCW; ++c) {
+                        cslot[c] = 0;
+#pragma unroll
+                        for (int x = 0; x < E; ++x) I[c][x] = 0.0f;
+                        if (!MASKED || ((amask >> c) & 1u)) {
+                            const uint32_t a = (uint32_t)(c >> 1) + 1u;
+                            const uint32_t p = (c & 1) ? i + a : i - a;
+                            cslot[c] = lane_value(meta_slot, p & 63u);
+                            const float *src = ring + (size_t)cslot[c] * ROWF;
+#pragma unroll
+                            for (int r = 0; r < R; ++r) load_vec<VW>(src + eoff[r], &I[c][r * VW]);
+                        }
+                    }
+                    for (uint32_t kb = 0; kb <= (MULTI ? N : 0u); kb += KC) {
+                        const uint32_t gk = kb + lane_k;
+                        uint32_t pv = packv;
+                        if (MULTI && kb) {                          // further output rows: fetched here
+                            pv = (gk <= N) ? cb_pack[(size_t)j * N + (gk - 1)] : 0u;
+#pragma unroll
+                            for (int kk = 0; kk < KC; ++kk) {
+                                const uint32_t pk = lane_value(pv, (uint32_t)kk);
+#pragma unroll
+                                for (int x = 0; x < E; ++x) O[kk][x] = 0.0f;
+                                if (kb + kk <= N && (pk >> kIdBits)) load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, O[kk]);
+                            }
+                        }
+                        const float mult_lane = (gk <= N) ? (float)(pv >> kIdBits) : 0.0f;
+                        const float label = (gk == 0) ? 1.0f : 0.0f;
+                        const float gscale = alpha * mult_lane;
+                        float dO[KC][E];
+#pragma unroll
+                        for (int kk = 0; kk < KC; ++kk)
+#pragma unroll
+                            for (int x = 0; x < E; ++x) dO[kk][x] = 0.0f;
+
+#pragma unroll
+                        for (int q = 0; q < NQW; ++q) {
+                            // NC context rows (slots q*CC .. q*CC+NC-1) against the KC output rows
+                            constexpr int NCLAST = NCW - (NQW - 1) * CC;
+                            const int NC = (q == NQW - 1) ? NCLAST : CC;
+                            if (MASKED && !(amask >> (q * CC))) break;
+                            float acc[CC * KC];
+#pragma unroll
+                            for (int cc = 0; cc < CC; ++cc) {
+                                const int c = q * CC + cc;
+#pragma unroll
+                                for (int kk = 0; kk < KC; ++kk) {
+                                    float p = 0.0f;
+                                    if (cc < NC && (!MASKED || ((amask >> c) & 1u))) {
+#pragma unroll
+                                        for (int x = 0; x < E; ++x) p = __builtin_fmaf(I[c][x], O[kk][x], p);
+                                    }
+                                    acc[cc * KC + kk] = p;
+                                }
+                            }
+                            const float xraw = (q == NQW - 1) ? transpose_reduce<NCLAST * KC>(acc, lane)
+                                                              : transpose_reduce<CC * KC>(acc, lane);
+                            bool act = lane < NC * KC && mult_lane > 0.0f;
+                            if (MASKED) act = act && ((amask >> (q * CC + lane_c)) & 1u);
+                            // sigmoid and log-loss from u = 1 + exp(-x): sigma = 1/u, -log sigma(x) = log u,
+                            // -log sigma(-x) = x + log u   (x clamped where exp would overflow)
+                            // (hardware exp2 / log2 / rcp: about 1 ulp each, far inside the parity budget)
+                            const float xv = __builtin_amdgcn_fmed3f(xraw, -80.0f, 80.0f);
+                            const float u = 1.0f + __builtin_amdgcn_exp2f(xv * -1.44269504088896341f);
+                            const float g = act ? gscale * (label - __builtin_amdgcn_rcpf(u)) : 0.0f;
+                            if (act)
+                                loss_acc += (double)(mult_lane * __builtin_fmaf(__builtin_amdgcn_logf(u), 0.693147180559945309f,
+                                                                              (gk == 0) ? 0.0f : xv));
+#pragma unroll
+                            for (int cc = 0; cc < CC; ++cc) {
+                                const int c = q * CC + cc;
+                                if (cc < NC && (!MASKED || ((amask >> c) & 1u))) {
+                                    float dI[E];
+#pragma unroll
+                                    for (int x = 0; x < E; ++x) dI[x] = 0.0f;
+#pragma unroll
+                                    for (int kk = 0; kk < KC; ++kk) {
+                                        const float gs = lane_value(g, (uint32_t)(cc * KC + kk));
+#pragma unroll
+                                        for (int x = 0; x < E; ++x) {
+                                            dI[x] = __builtin_fmaf(gs, O[kk][x], dI[x]);
+                                            dO[kk][x] = __builtin_fmaf(gs, I[c][x], dO[kk][x]);
+                                        }
+                                    }
+                                    float *dst = ring + (size_t)cslot[c] * ROWF;
+                                    if (shared_rows || (MULTI && kb)) {
+                                        // positions that share a ring row add up (LDS float add)
+#pragma unroll
+                                        for (int r = 0; r < R; ++r)
+#pragma unroll
+                                            for (int x = 0; x < VW; ++x)
+                                                __hip_atomic_fetch_add(dst + eoff[r] + x, dI[r * VW + x], __ATOMIC_RELAXED,
+                                                                       __HIP_MEMORY_SCOPE_WAVEFRONT);
+                                    } else {
+                                        // the row still equals the copy in registers: plain write of copy + delta
+#pragma unroll
+                                        for (int r = 0; r < R; ++r) {
+                                            float t[VW];
+#pragma unroll
+                                            for (int x = 0; x < VW; ++x) t[x] = I[c][r * VW + x] + dI[r * VW + x];
+                                            store_vec<VW>(dst + eoff[r], t);
+                                        }
+                                    }
+                                }
+                            }
+                        }
+
+                        // (f) output rows go back (lock-free) once per window
+#pragma unroll
+                        for (int kk = 0; kk < KC; ++kk) {
+                            const uint32_t pk = lane_value(pv, (uint32_t)kk);
+                            if (kb + kk <= N && (pk >> kIdBits)) {
+                                float t[E];
+#pragma unroll
+                                for (int x = 0; x < E; ++x) t[x] = O[kk][x] + dO[kk][x];
+                                store_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, t);
+                            }
+                        }
+                    }
+                };
+                if (nact) {
+                    pairs_acc += nact;
+                    using std::integral_constant;
+                    using T = integral_constant<bool, true>;
+                    using F = integral_constant<bool, false>;
+#define W2V_WIN(NCV) do_window(integral_constant<int, (NCV)>{}, F{})
+                    bool done = false;
+                    if (interior) {
+                        // every one of the 2b nearest positions exists: straight-line code per width
+                        done = true;
+                        switch (b) {
+                        case 1: W2V_WIN(2); break;
+                        case 2: W2V_WIN(4); break;
+                        case 3: W2V_WIN(6); break;
+                        case 4: W2V_WIN(8); break;
+                        case 5: W2V_WIN(10); break;
+                        default: done = false; break;
+                        }
+                        if constexpr (WCAP >= 10) {
+                            if (!done) {
+                                done = true;
+                                switch (b) {
+                                case 6: W2V_WIN(12); break;
+                                case 7: W2V_WIN(14); break;
+                                case 8: W2V_WIN(16); break;
+                                case 9: W2V_WIN(18); break;
+                                case 10: W2V_WIN(20); break;
+                                default: done = false; break;
+                                }
+                            }
+                        }
+                    }
+#undef W2V_WIN
+                    if (!done) do_window(integral_constant<int, NCTX>{}, T{});   // cut by a sentence end, or wide
+                }
+
+                // (g) rows of the next window that this window has just rewritten are fetched again
+                //     (a load issued after a store of the same wavefront sees the stored data)
+                if (has_next) {
+                    const uint32_t reload = nact ? (uni(mraw_next.x) >> 8) : 0u;
+                    if (reload) {
+#pragma unroll
+                        for (int kk = 0; kk < KC; ++kk)
+                            if ((reload >> kk) & 1u) {
+                                const uint32_t pk = lane_value(packv_next, (uint32_t)kk);
+                                load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, On[kk]);
+                            }
+                    }
+                }
+
+                // (h) the fetched context row enters the ring, the oldest position leaves it
+                //     (every lane only touches its own elements of a ring row: no barrier needed)
+                if (pend) {
+                    float *dst = ring + (size_t)pend_slot * ROWF;
+#pragma unroll
+                    for (int r = 0; r < R; ++r) store_vec<VW>(dst + eoff[r], pend_row + r * VW);
+                }
+                if (i >= W) ring_leave(i - W);
+
+                // (i) next window's scalars and rows become current
+                if (has_next) {
+                    mraw = mraw_next;
+                    packv = packv_next;
+#pragma unroll
+                    for (int kk = 0; kk < KC; ++kk)
+#pragma unroll
+                        for (int x = 0; x < E; ++x) O[kk][x] = On[kk][x];
+                }
+            }
+            i0 += nwin;
+        }
+        kept_acc += n_prod;
+
+        // ---- sentence done: the rows still in the ring go back -------------------------------------
+        {
+            const uint32_t first = (n_prod > W) ? n_prod - W : 0u;   // positions < first left already
+            for (uint32_t p = first; p < n_ins; ++p) ring_leave(p);
+        }
+        __syncthreads();
+    }
+
+    const double lsum = wave_sum(loss_acc);
+    const unsigned long long dsum = (unsigned long long)wave_sum((double)dropped_acc);
+    if (lane == 0) {
+        atomicAdd(&A.accum->loss_sum, lsum);
+        atomicAdd(&A.accum->pairs, pairs_acc);
+        atomicAdd(&A.accum->kept, kept_acc);
+        if (dsum) atomicAdd(&A.accum->dropped, dsum);
+    }
+}
+
+}  // namespace
+}  // namespace w2v
