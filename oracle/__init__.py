@@ -54,7 +54,7 @@ class Oracle:
         L.orc_lr.argtypes = [C.c_double, C.c_double, C.c_uint32, C.c_uint32, C.c_uint64, C.c_uint64]
         L.orc_init_weights.restype = None
         L.orc_init_weights.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, rp, rp]
-        for name in ("orc_window_step", "orc_window_step_immediate"):
+        for name in ("orc_window_step", "orc_window_step_immediate", "orc_window_step_pairwise"):
             f = getattr(L, name)
             f.restype = None
             f.argtypes = [rp, rp, C.c_uint32, _i32p, C.c_uint32, _i32p, C.c_uint32, creal,
@@ -109,13 +109,15 @@ class Oracle:
         return syn0, syn1
 
     # ---- one window ----------------------------------------------------
-    def window_step(self, syn0, syn1neg, ctx, out, alpha, immediate=False):
+    def window_step(self, syn0, syn1neg, ctx, out, alpha, immediate=False, pairwise=False):
         """In-place update of syn0/syn1neg by one window; returns the window's loss sum."""
         assert syn0.dtype == self.real and syn1neg.dtype == self.real
         ctx = np.ascontiguousarray(ctx, np.int32)
         out = np.ascontiguousarray(out, np.int32)
         loss = C.c_double(0.0)
         f = self.L.orc_window_step_immediate if immediate else self.L.orc_window_step
+        if pairwise:
+            f = self.L.orc_window_step_pairwise
         f(syn0, syn1neg, syn0.shape[1], ctx, len(ctx), out, len(out), alpha, C.byref(loss))
         return loss.value
 

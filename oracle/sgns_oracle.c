@@ -270,13 +270,44 @@ void orc_window_step_immediate(real_t *syn0, real_t *syn1neg, uint32_t d,
     }
 }
 
+/* The classic per-pair order of the original word2vec loop (what the
+ * pre-existing GPU kernels of Section 2.3 execute): context words one
+ * after the other; for each, the N+1 samples in turn, every pairing
+ * applied to the output row at once and to the context row after its
+ * last sample.  Reference for the no-reuse comparator kernel only. */
+void orc_window_step_pairwise(real_t *syn0, real_t *syn1neg, uint32_t d,
+                              const int32_t *ctx, uint32_t nctx,
+                              const int32_t *out, uint32_t nout,
+                              real_t alpha, double *loss_sum)
+{
+    real_t *neu = (real_t *)malloc(sizeof(real_t) * d);
+    for (uint32_t c = 0; c < nctx; ++c) {
+        real_t *I = syn0 + (size_t)ctx[c] * d;
+        for (uint32_t j = 0; j < d; ++j) neu[j] = 0;
+        for (uint32_t k = 0; k < nout; ++k) {
+            if (k >= 1 && out[k] == out[0]) continue;
+            real_t *O = syn1neg + (size_t)out[k] * d;
+            real_t x = 0;
+            for (uint32_t j = 0; j < d; ++j) x += I[j] * O[j];
+            real_t gg = alpha * (((k == 0) ? (real_t)1 : (real_t)0) - sigmoid_r(x));
+            if (loss_sum) *loss_sum += softplus_d(k == 0 ? -(double)x : (double)x);
+            for (uint32_t j = 0; j < d; ++j) {
+                neu[j] += gg * O[j];
+                O[j] += gg * I[j];
+            }
+        }
+        for (uint32_t j = 0; j < d; ++j) I[j] += neu[j];
+    }
+    free(neu);
+}
+
 /* ------------------------------------------------------------------ */
 /* One epoch, sentences in order, windows in order.                    */
 /* ------------------------------------------------------------------ */
 typedef struct orc_params {
     uint32_t vocab, dim, window, negatives;
     uint32_t window_mode;      /* 0 random width, 1 fixed ceil(W/2)        */
-    uint32_t update_mode;      /* 0 window minibatch, 1 immediate pairings */
+    uint32_t update_mode;      /* 0 window minibatch, 1 immediate pairings, 2 classic per-pair order */
     uint32_t total_epochs, epoch;
     uint64_t tokens_per_epoch, first_token_global_pos, seed, table_size;
     double lr0, lr_min_frac;
@@ -330,8 +361,10 @@ int orc_train_range(const orc_params *P, real_t *syn0, real_t *syn1neg,
             if (nctx == 0) continue;
             if (P->update_mode == 0)
                 orc_window_step(syn0, syn1neg, P->dim, ctx, nctx, out, N + 1, (real_t)alpha, loss_sum);
-            else
+            else if (P->update_mode == 1)
                 orc_window_step_immediate(syn0, syn1neg, P->dim, ctx, nctx, out, N + 1, (real_t)alpha, loss_sum);
+            else
+                orc_window_step_pairwise(syn0, syn1neg, P->dim, ctx, nctx, out, N + 1, (real_t)alpha, loss_sum);
             if (pairs) *pairs += nctx;
         }
     }

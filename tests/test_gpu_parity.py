@@ -147,3 +147,22 @@ def test_untouched_rows_and_padding_stay_bit_identical(orc32):
     assert not np.array_equal(a0[:100], s0[:100])
     assert bool((tr.syn0[:, d:] == 7.0).all()) and bool((tr.syn1neg[:, d:] == -7.0).all())
     tr.close()
+
+
+def test_no_reuse_comparator_kernel_matches_the_classic_pair_order(orc32):
+    # the traffic comparator executes the original word2vec loop order; checked so that its byte counts
+    # belong to a correct trainer
+    c = synth.zipf_corpus(300, 1.0, 6, 400, seed=12)
+    kw = dict(dim=128, window=5, negatives=5, seed=9, table_size=1 << 14, subsample_t=1e-2)
+    g0, g1, gl, gp = run_gpu(c, sentences_in_flight=1, naive=True, **kw)
+    r0, r1, rl, rp = run_oracle(orc32, c, update_mode=2, **kw)
+    assert gp == rp and abs(gl - rl) <= 2e-5 * rl
+    assert_rows_close(g0, r0, 1e-4, "syn0")
+    assert_rows_close(g1, r1, 1e-4, "syn1neg")
+    c = synth.zipf_corpus(200, 1.0, 4, 300, seed=13)
+    kw = dict(dim=300, window=3, negatives=7, seed=9, table_size=1 << 14)
+    g0, g1, gl, gp = run_gpu(c, sentences_in_flight=1, naive=True, **kw)
+    r0, r1, rl, rp = run_oracle(orc32, c, update_mode=2, **kw)
+    assert gp == rp
+    assert_rows_close(g0, r0, 1e-4, "syn0")
+    assert_rows_close(g1, r1, 1e-4, "syn1neg")

@@ -4,7 +4,7 @@ import numpy as np
 
 def run_oracle(orc, corpus, *, dim, window, negatives, seed, epochs=1, table_size=1 << 16, subsample_t=0.0,
                window_mode=0, lr0=0.025, syn0=None, syn1neg=None, first_token_global_pos=0, tokens_per_epoch=None,
-               total_epochs=None, start_epoch=0):
+               total_epochs=None, start_epoch=0, update_mode=0):
     if syn0 is None:
         syn0, syn1neg = orc.init_weights(seed, corpus.vocab, dim)
     else:
@@ -14,7 +14,7 @@ def run_oracle(orc, corpus, *, dim, window, negatives, seed, epochs=1, table_siz
     for e in range(start_epoch, start_epoch + epochs):
         r = orc.train_epoch(syn0, syn1neg, corpus.counts, corpus.tokens, corpus.sent_off, window=window,
                             negatives=negatives, seed=seed, epoch=e, total_epochs=total_epochs, table_size=table_size,
-                            subsample_t=subsample_t, window_mode=window_mode, lr0=lr0,
+                            subsample_t=subsample_t, window_mode=window_mode, lr0=lr0, update_mode=update_mode,
                             first_token_global_pos=first_token_global_pos, tokens_per_epoch=tokens_per_epoch)
         loss += r["loss_sum"]
         pairs += r["pairs"]
