@@ -37,6 +37,8 @@ def main():
     ap.add_argument("--in-flight", type=int, default=0, help="sentences_in_flight (0 = fill the GPU)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sentences", type=int, default=2500)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device copy three times (scale for the rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (a second GPU is never used); run with --gpus 1",
@@ -45,6 +47,14 @@ def main():
 
     import numpy as np
     import torch
+    if args.copy_calibration:
+        a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")       # 1 GiB
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": a.numel() * 4, "copy_bytes_written": a.numel() * 4, "copies": 3}))
+        return
     from paper_2312_07743_amd import synth
     from paper_2312_07743_amd.trainer import Trainer
 

@@ -1,0 +1,88 @@
+"""GPU checks at the full 'Mid' size in the launch configuration the benchmark times (all sentences
+lock-free at once): integer decisions sampled against the oracle's scalar functions, counters that are
+independent of scheduling, and the statistical parity of a lock-free run with the serial oracle
+(stored reference written by tests/golden/make_mid_hogwild_reference.py, which calls only the oracle)."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+from paper_2312_07743_amd import synth
+from util import planted_score
+
+pytestmark = pytest.mark.gpu
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+@pytest.fixture(scope="module")
+def reference():
+    with open(os.path.join(HERE, "golden", "mid_hogwild_reference.json")) as f:
+        return json.load(f)
+
+
+@pytest.fixture(scope="module")
+def mid(reference):
+    c = synth.planted_corpus(**reference["corpus"])
+    assert c.vocab == reference["vocab"] and c.n_tokens == reference["tokens"]
+    return c
+
+
+def test_sampled_integer_decisions_at_full_size(orc32, mid, reference):
+    from paper_2312_07743_amd.trainer import Trainer
+    P = reference["params"]
+    tr = Trainer(vocab=mid.vocab, dim=P["dim"], window=P["window"], negatives=P["negatives"], counts=mid.counts,
+                 tokens_per_epoch=mid.n_tokens, seed=P["seed"], table_size=P["table_size"],
+                 subsample_t=P["subsample_t"], total_epochs=P["epochs"])
+    tr.set_corpus(mid.tokens, mid.sent_off)
+    keep, width, neg = tr.draws(epoch=1)
+    tr.close()
+    thr = orc32.thresholds(mid.counts, P["subsample_t"])
+    end = orc32.table_ends(mid.counts, P["table_size"])
+    rng = np.random.default_rng(0)
+    sample = np.concatenate([rng.integers(0, mid.n_tokens, size=3000), [0, mid.n_tokens - 1]])
+    for t in sample:
+        t = int(t)
+        k = orc32.keep(thr, int(mid.tokens[t]), P["seed"], 1, t)
+        assert keep[t] == k
+        if k:
+            assert width[t] == orc32.width(P["window"], 0, P["seed"], 1, t)
+            assert list(neg[t]) == [orc32.negative(end, P["table_size"], P["seed"], 1, t, j) for j in range(P["negatives"])]
+        else:
+            assert width[t] == 0 and np.all(neg[t] == -1)
+    # the kept fraction follows from the thresholds alone
+    pk = np.where(thr == 0xFFFFFFFF, 1.0, thr / 2.0**32)
+    want = float((mid.counts / mid.counts.sum() * pk).sum())
+    assert abs(keep.mean() - want) < 2e-3
+
+
+def test_lock_free_run_matches_serial_oracle_statistically(mid, reference):
+    """Every sentence in flight at once, two epochs: pair counts are schedule-independent and must be
+    exact; the final epoch's mean loss must be within 1 % of the serial oracle's, and the planted
+    clusters must be recovered as well as the oracle recovers them."""
+    import torch
+    from paper_2312_07743_amd.trainer import Trainer
+    P = reference["params"]
+    for seed_shift in (0,):
+        tr = Trainer(vocab=mid.vocab, dim=P["dim"], window=P["window"], negatives=P["negatives"], counts=mid.counts,
+                     tokens_per_epoch=mid.n_tokens, seed=P["seed"], table_size=P["table_size"],
+                     subsample_t=P["subsample_t"], total_epochs=P["epochs"], sentences_in_flight=0)
+        tr.set_corpus(mid.tokens, mid.sent_off)
+        losses, kept, invalid = [], 0, 0
+        for e in range(P["epochs"]):
+            tr.train_epoch(e)
+            k, bad = tr.counters()
+            kept, invalid = kept + k, invalid + bad
+            loss, pairs = tr.loss(reset=True)
+            assert pairs == reference["epochs"][e]["pairs"]
+            losses.append(loss / pairs)
+        assert invalid == 0 and 0.45 * mid.n_tokens * P["epochs"] < kept < 0.56 * mid.n_tokens * P["epochs"]
+        emb = tr.embeddings(0)
+        tr.close()
+        assert np.isfinite(emb).all()
+        ref_last = reference["epochs"][-1]
+        assert abs(losses[-1] - ref_last["mean_loss"]) <= 0.01 * ref_last["mean_loss"], (losses, ref_last)
+        assert losses[1] < losses[0]
+        score = planted_score(emb, mid.labels)
+        assert abs(score - ref_last["planted_score"]) <= 0.01, (score, ref_last)
+        torch.cuda.synchronize()
