@@ -36,6 +36,8 @@ def main():
     ap.add_argument("--dim", type=int, default=None, help="override d (dimension sweep)")
     ap.add_argument("--in-flight", type=int, default=0, help="sentences_in_flight (0 = fill the GPU)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--naive", action="store_true",
+                    help="time the no-reuse comparator kernel instead of the window kernel (traffic comparison only)")
     ap.add_argument("--cpu-sentences", type=int, default=2500)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy three times (scale for the rocprofv3 byte counters)")
@@ -68,7 +70,7 @@ def main():
                  total_epochs=E, sentences_in_flight=args.in_flight)
     tr.set_corpus(corpus.tokens, corpus.sent_off)
     for e in range(args.warmup):
-        tr.train_epoch(e)
+        tr.train_epoch(e, naive=args.naive)
     torch.cuda.synchronize()
     tr.loss(reset=True)
 
@@ -78,7 +80,7 @@ def main():
     t0 = time.perf_counter()
     for k in range(args.steps):
         starts[k].record()                       # torch's current stream is the one the library launches on
-        tr.train_epoch(args.warmup + k)
+        tr.train_epoch(args.warmup + k, naive=args.naive)
         stops[k].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -92,9 +94,12 @@ def main():
     avg_kernel_s = float(np.mean(kernel_ms)) / 1e3
     achieved = algo_bytes_per_launch / avg_kernel_s / 1e9
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"window_kernel_{args.workload}_d{dim}_traffic.json")
-    if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+    # measured L2<->memory bytes per launch, from the committed rocprofv3 counter summary of this workload
+    tpath = os.path.join(ROOT, "profiles", f"window_kernel_{args.workload}_d{dim}_counters.txt")
+    if os.path.exists(tpath) and not args.naive:
+        for line in open(tpath):
+            if line.startswith("hbm_bytes_per_launch:"):
+                traffic = float(line.split(":")[1])
 
     out = {
         "metric": "trained words/sec on 1 MI355X; achieved HBM GB/s vs peak",
@@ -108,7 +113,7 @@ def main():
                    "mean_loss": loss_sum / max(pairs, 1), "sentences_in_flight": args.in_flight},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": "train_kernel", "avg_launch_ms": avg_kernel_s * 1e3,
+                     "kernel": "naive_kernel" if args.naive else "train_kernel", "avg_launch_ms": avg_kernel_s * 1e3,
                      "algorithmic_bytes_per_launch": algo_bytes_per_launch},
     }
 
