@@ -155,16 +155,21 @@ __device__ __forceinline__ float sentence_lr(const KernelArgs &A, uint64_t start
 // the window kernel
 // ---------------------------------------------------------------------------------------------
 // Per-window scalars the sampling stage leaves in LDS for the window loop (one uint4 per window):
-//   x = width b | (reload bits << 8) | (dup << 16)
+//   x = width b | (reload bits << 8) | (dup << 16) | (plain << 17)
 //       reload bit k': output row k' (k' < KC) of this window is also an output row of the previous
 //       window, so a copy fetched before that window's write-back is stale;
-//       dup: two context positions of the window hold the same word and share a ring row
+//       dup: two context positions of the window hold the same word and share a ring row;
+//       plain: no dup, and every negative is distinct and differs from the target (multiplicity 1)
 //   y = target word, z = word of the kept position that enters the ring at this window (or none)
 constexpr uint32_t kNoWord = 0xFFFFFFFFu;
 
 // MULTI: more than KC output rows per window (N + 1 > KC), handled KC at a time
+// wavefronts per SIMD the register allocator is asked to make room for (512 VGPRs per lane in all)
+constexpr int occupancy_goal(int e, int wcap) { return (e <= 2 && wcap <= 5) ? 3 : ((e * wcap <= 20) ? 2 : 1); }
+
 template <int VW, int R, int WCAP, bool FULL, bool MULTI>
-__global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
+__global__ void __launch_bounds__(kLanes) __attribute__((amdgpu_waves_per_eu(occupancy_goal(VW * R, WCAP))))
+train_kernel(KernelArgs A)
 {
     constexpr int E = VW * R;            // floats of a row per lane
     constexpr int ROWF = kLanes * E;     // floats of a ring row in LDS
@@ -295,7 +300,7 @@ __global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
 
             // ---- width and negatives of the chunk's windows, one window per lane ----------------
             int32_t my_w = -1;
-            uint32_t my_b = 0, my_enter = kNoWord;
+            uint32_t my_b = 0, my_enter = kNoWord, my_plain = 0;
             if ((uint32_t)lane < nwin) {
                 const uint32_t idx = (i0 + lane) & (FCAP - 1);
                 my_w = kw[idx];
@@ -305,6 +310,7 @@ __global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
                 if (pe < n_prod) my_enter = (uint32_t)kw[pe & (FCAP - 1)];
                 uint32_t *pk = cb_pack + (size_t)lane * N;
                 for (uint32_t k = 0; k < N; ++k) pk[k] = (uint32_t)A.table[negative_slot(base, k, A.table_size)];
+                my_plain = 1u;
                 // multiplicity: 0 for a negative equal to the target and for repeats of an earlier
                 // negative, otherwise the number of times the id was drawn
                 for (uint32_t k = 0; k < N; ++k) {
@@ -313,6 +319,7 @@ __global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
                     for (uint32_t k1 = 0; k1 < k && m; ++k1) if ((pk[k1] & kIdMask) == id) m = 0u;
                     if (m) for (uint32_t k2 = k + 1; k2 < N; ++k2) if ((pk[k2] & kIdMask) == id) ++m;
                     pk[k] = id | (m << kIdBits);
+                    if (m != 1u) my_plain = 0u;
                 }
             }
             __syncthreads();
@@ -345,7 +352,7 @@ __global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
                             if (p2 != me && kw[p2 & (FCAP - 1)] == w1) dup = 1u;
                     }
                 }
-                cb_meta[lane] = make_uint4(my_b | (reload << 8) | (dup << 16), (uint32_t)my_w, my_enter, 0u);
+                cb_meta[lane] = make_uint4(my_b | (reload << 8) | (dup << 16) | ((my_plain & (dup ^ 1u)) << 17), (uint32_t)my_w, my_enter, 0u);
             }
             __syncthreads();
 
@@ -378,13 +385,14 @@ __global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
                 const uint32_t pk = lane_value(packv, (uint32_t)kk);
 #pragma unroll
                 for (int x = 0; x < E; ++x) O[kk][x] = 0.0f;
-                if ((uint32_t)kk <= N && (pk >> kIdBits)) load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, O[kk]);
+                if ((uint32_t)kk <= N) load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, O[kk]);
             }
 
             for (uint32_t j = 0; j < nwin; ++j) {
                 const uint32_t i = i0 + j;
                 const uint32_t b = uni(mraw.x) & 0xFFu;
                 const bool shared_rows = (uni(mraw.x) >> 16) & 1u;
+                const bool plain = (uni(mraw.x) >> 17) & 1u;
                 const uint32_t enter_word = uni(mraw.z);
                 const bool has_next = j + 1 < nwin;
 
@@ -425,15 +433,19 @@ __global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
                         const uint32_t pk = lane_value(packv_next, (uint32_t)kk);
 #pragma unroll
                         for (int x = 0; x < E; ++x) On[kk][x] = 0.0f;
-                        if ((uint32_t)kk <= N && (pk >> kIdBits)) load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, On[kk]);
+                        if ((uint32_t)kk <= N) load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, On[kk]);
                     }
                 }
 
-                // (e) the window's arithmetic over context slots 0..NCW-1; MASKED: slot c takes part only
-                //     if bit c of amask is set (windows cut by a sentence end), otherwise all of them do
-                auto do_window = [&](auto ncw_tag, auto masked_tag) {
+                // (e) the window's arithmetic over context slots 0..NCW-1.
+                //     GENERAL = false: straight-line code for the common window: all NCW slots exist, no two
+                //     of them share a ring row, every negative is distinct and differs from the target.
+                //     GENERAL = true: slot c takes part only if bit c of amask is set (windows cut by a
+                //     sentence end), multiplicities are honoured, shared ring rows are added to.
+                auto do_window = [&](auto ncw_tag, auto general_tag) {
                     constexpr int NCW = decltype(ncw_tag)::value;
-                    constexpr bool MASKED = decltype(masked_tag)::value;
+                    constexpr bool MASKED = decltype(general_tag)::value;
+                    constexpr bool GENERAL = MASKED;
                     constexpr int NQW = (NCW + CC - 1) / CC;
                     float I[NCW][E];
                     uint32_t cslot[NCW];
@@ -461,12 +473,12 @@ __global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
                                 const uint32_t pk = lane_value(pv, (uint32_t)kk);
 #pragma unroll
                                 for (int x = 0; x < E; ++x) O[kk][x] = 0.0f;
-                                if (kb + kk <= N && (pk >> kIdBits)) load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, O[kk]);
+                                if (kb + kk <= N) load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, O[kk]);
                             }
                         }
-                        const float mult_lane = (gk <= N) ? (float)(pv >> kIdBits) : 0.0f;
+                        const float mult_lane = (gk <= N) ? (GENERAL ? (float)(pv >> kIdBits) : 1.0f) : 0.0f;
                         const float label = (gk == 0) ? 1.0f : 0.0f;
-                        const float gscale = alpha * mult_lane;
+                        const float gscale = GENERAL ? alpha * mult_lane : alpha;
                         float dO[KC][E];
 #pragma unroll
                         for (int kk = 0; kk < KC; ++kk)
@@ -495,7 +507,7 @@ __global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
                             }
                             const float xraw = (q == NQW - 1) ? transpose_reduce<NCLAST * KC>(acc, lane)
                                                               : transpose_reduce<CC * KC>(acc, lane);
-                            bool act = lane < NC * KC && mult_lane > 0.0f;
+                            bool act = lane < NC * KC && (GENERAL ? mult_lane > 0.0f : gk <= N);
                             if (MASKED) act = act && ((amask >> (q * CC + lane_c)) & 1u);
                             // sigmoid and log-loss from u = 1 + exp(-x): sigma = 1/u, -log sigma(x) = log u,
                             // -log sigma(-x) = x + log u   (x clamped where exp would overflow)
@@ -503,9 +515,10 @@ __global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
                             const float xv = __builtin_amdgcn_fmed3f(xraw, -80.0f, 80.0f);
                             const float u = 1.0f + __builtin_amdgcn_exp2f(xv * -1.44269504088896341f);
                             const float g = act ? gscale * (label - __builtin_amdgcn_rcpf(u)) : 0.0f;
-                            if (act)
-                                loss_acc += (double)(mult_lane * __builtin_fmaf(__builtin_amdgcn_logf(u), 0.693147180559945309f,
-                                                                              (gk == 0) ? 0.0f : xv));
+                            if (act) {
+                                const float l1 = __builtin_fmaf(__builtin_amdgcn_logf(u), 0.693147180559945309f, (gk == 0) ? 0.0f : xv);
+                                loss_acc += (double)(GENERAL ? mult_lane * l1 : l1);
+                            }
 #pragma unroll
                             for (int cc = 0; cc < CC; ++cc) {
                                 const int c = q * CC + cc;
@@ -523,7 +536,7 @@ __global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
                                         }
                                     }
                                     float *dst = ring + (size_t)cslot[c] * ROWF;
-                                    if (shared_rows || (MULTI && kb)) {
+                                    if ((GENERAL && shared_rows) || (MULTI && kb)) {
                                         // positions that share a ring row add up (LDS float add)
 #pragma unroll
                                         for (int r = 0; r < R; ++r)
@@ -549,7 +562,7 @@ __global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
 #pragma unroll
                         for (int kk = 0; kk < KC; ++kk) {
                             const uint32_t pk = lane_value(pv, (uint32_t)kk);
-                            if (kb + kk <= N && (pk >> kIdBits)) {
+                            if (kb + kk <= N && (!GENERAL || (pk >> kIdBits))) {
                                 float t[E];
 #pragma unroll
                                 for (int x = 0; x < E; ++x) t[x] = O[kk][x] + dO[kk][x];
@@ -565,8 +578,8 @@ __global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
                     using F = integral_constant<bool, false>;
 #define W2V_WIN(NCV) do_window(integral_constant<int, (NCV)>{}, F{})
                     bool done = false;
-                    if (interior) {
-                        // every one of the 2b nearest positions exists: straight-line code per width
+                    if (interior && plain) {
+                        // the common window: straight-line code per width
                         done = true;
                         switch (b) {
                         case 1: W2V_WIN(2); break;
@@ -591,7 +604,7 @@ __global__ void __launch_bounds__(kLanes) train_kernel(KernelArgs A)
                         }
                     }
 #undef W2V_WIN
-                    if (!done) do_window(integral_constant<int, NCTX>{}, T{});   // cut by a sentence end, or wide
+                    if (!done) do_window(integral_constant<int, NCTX>{}, T{});   // anything else
                 }
 
                 // (g) rows of the next window that this window has just rewritten are fetched again

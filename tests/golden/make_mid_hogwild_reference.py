@@ -1,7 +1,7 @@
 """Writes tests/golden/mid_hogwild_reference.json: the serial CPU oracle's per-epoch mean loss, pair
 count and planted-cluster recovery on the 'Mid' workload (vocabulary 71,000 Zipf(1.05) with 16 planted
-clusters, 17M tokens, d=128, W=5, N=5, t=1e-4), two epochs.  Calls only oracle/ and the input
-generator; takes about four minutes on one core.
+clusters, 17M tokens, d=128, W=5, N=5, t=1e-4), two epochs, for three training seeds (the seed keys the initial weights and every random
+draw).  Calls only oracle/ and the input generator; takes about ten minutes on one core.
 
     python tests/golden/make_mid_hogwild_reference.py
 """
@@ -18,26 +18,30 @@ from oracle import Oracle                                   # noqa: E402
 from paper_2312_07743_amd import synth                      # noqa: E402
 from util import planted_score                              # noqa: E402
 
-PARAMS = dict(dim=128, window=5, negatives=5, seed=5, table_size=1 << 24, subsample_t=1e-4, epochs=2)
+PARAMS = dict(dim=128, window=5, negatives=5, table_size=1 << 24, subsample_t=1e-4, epochs=2)
+SEEDS = (5, 6, 7)
 CORPUS = dict(vocab=71000, s=1.05, n_sent=17000, sent_len=1000, seed=1)
 
 
 def main():
     orc = Oracle("float")
     c = synth.planted_corpus(**CORPUS)
-    syn0, syn1 = orc.init_weights(PARAMS["seed"], c.vocab, PARAMS["dim"])
-    out = {"params": PARAMS, "corpus": CORPUS, "vocab": c.vocab, "tokens": c.n_tokens, "epochs": []}
-    for e in range(PARAMS["epochs"]):
-        t = time.time()
-        r = orc.train_epoch(syn0, syn1, c.counts, c.tokens, c.sent_off, window=PARAMS["window"],
-                            negatives=PARAMS["negatives"], seed=PARAMS["seed"], epoch=e,
-                            total_epochs=PARAMS["epochs"], table_size=PARAMS["table_size"],
-                            subsample_t=PARAMS["subsample_t"])
-        out["epochs"].append({"mean_loss": r["loss_sum"] / r["pairs"], "pairs": r["pairs"],
-                              "planted_score": planted_score(syn0, c.labels)})
-        print(e, out["epochs"][-1], f"{time.time() - t:.0f}s", flush=True)
-    with open(os.path.join(HERE, "mid_hogwild_reference.json"), "w") as f:
-        json.dump(out, f, indent=1)
+    out = {"params": PARAMS, "corpus": CORPUS, "vocab": c.vocab, "tokens": c.n_tokens, "runs": []}
+    for seed in SEEDS:
+        syn0, syn1 = orc.init_weights(seed, c.vocab, PARAMS["dim"])
+        run = {"seed": seed, "epochs": []}
+        for e in range(PARAMS["epochs"]):
+            t = time.time()
+            r = orc.train_epoch(syn0, syn1, c.counts, c.tokens, c.sent_off, window=PARAMS["window"],
+                                negatives=PARAMS["negatives"], seed=seed, epoch=e,
+                                total_epochs=PARAMS["epochs"], table_size=PARAMS["table_size"],
+                                subsample_t=PARAMS["subsample_t"])
+            run["epochs"].append({"mean_loss": r["loss_sum"] / r["pairs"], "pairs": r["pairs"],
+                                  "planted_score": planted_score(syn0, c.labels)})
+            print(seed, e, run["epochs"][-1], f"{time.time() - t:.0f}s", flush=True)
+        out["runs"].append(run)
+        with open(os.path.join(HERE, "mid_hogwild_reference.json"), "w") as f:
+            json.dump(out, f, indent=1)
 
 
 if __name__ == "__main__":
