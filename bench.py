@@ -23,6 +23,8 @@ HBM_PEAK_GBS = 8000.0
 WORKLOADS = {
     # name: (generator kwargs, dim, window, negatives, subsample_t, table_size)
     "mid": (dict(vocab=71000, s=1.05, n_sent=17000, sent_len=1000, seed=1), 128, 5, 5, 1e-4, 1 << 24),
+    # prefixes of the two big configurations (same vocabulary / row sizes, fewer sentences), for --workload only
+    "large": (dict(vocab=550000, s=1.1, n_sent=40000, sent_len=1000, seed=1), 300, 5, 10, 1e-5, 1 << 24),
     "small": (dict(vocab=8000, s=1.05, n_sent=600, sent_len=1000, seed=1, band_start=400), 128, 5, 5, 1e-4, 1 << 20),
 }
 
@@ -106,7 +108,7 @@ def main():
         "value": words / wall, "unit": "words/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": wall / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: vocab {corpus.vocab} Zipf(1.05) + 16 planted clusters, "
+        "config": {"workload": f"{args.workload}: vocab {corpus.vocab} Zipf({gen_kw['s']}) + 16 planted clusters, "
                                f"{corpus.n_tokens} tokens in {corpus.n_sent} sentences, d={dim}, W={window}, "
                                f"N={negatives}, subsample t={t_sub}, min-count 5, lr 0.025 linear decay",
                    "kept_words_per_s": kept / wall, "kept_fraction": kept / words,

@@ -536,7 +536,7 @@ train_kernel(KernelArgs A)
                                         }
                                     }
                                     float *dst = ring + (size_t)cslot[c] * ROWF;
-                                    if ((GENERAL && shared_rows) || (MULTI && kb)) {
+                                    if (GENERAL && shared_rows) {
                                         // positions that share a ring row add up (LDS float add)
 #pragma unroll
                                         for (int r = 0; r < R; ++r)
@@ -544,6 +544,16 @@ train_kernel(KernelArgs A)
                                             for (int x = 0; x < VW; ++x)
                                                 __hip_atomic_fetch_add(dst + eoff[r] + x, dI[r * VW + x], __ATOMIC_RELAXED,
                                                                        __HIP_MEMORY_SCOPE_WAVEFRONT);
+                                    } else if (MULTI && kb) {
+                                        // later output chunks: the row already carries the earlier chunks' deltas
+#pragma unroll
+                                        for (int r = 0; r < R; ++r) {
+                                            float t[VW];
+                                            load_vec<VW>(dst + eoff[r], t);
+#pragma unroll
+                                            for (int x = 0; x < VW; ++x) t[x] += dI[r * VW + x];
+                                            store_vec<VW>(dst + eoff[r], t);
+                                        }
                                     } else {
                                         // the row still equals the copy in registers: plain write of copy + delta
 #pragma unroll

@@ -26,8 +26,15 @@ CORPUS = dict(vocab=71000, s=1.05, n_sent=17000, sent_len=1000, seed=1)
 def main():
     orc = Oracle("float")
     c = synth.planted_corpus(**CORPUS)
+    path = os.path.join(HERE, "mid_hogwild_reference.json")
     out = {"params": PARAMS, "corpus": CORPUS, "vocab": c.vocab, "tokens": c.n_tokens, "runs": []}
+    if os.path.exists(path):                       # resume: keep the seeds that are already complete
+        old = json.load(open(path))
+        if old.get("params") == PARAMS and old.get("corpus") == CORPUS:
+            out["runs"] = [r for r in old.get("runs", []) if len(r["epochs"]) == PARAMS["epochs"]]
     for seed in SEEDS:
+        if any(r["seed"] == seed for r in out["runs"]):
+            continue
         syn0, syn1 = orc.init_weights(seed, c.vocab, PARAMS["dim"])
         run = {"seed": seed, "epochs": []}
         for e in range(PARAMS["epochs"]):
@@ -40,7 +47,7 @@ def main():
                                   "planted_score": planted_score(syn0, c.labels)})
             print(seed, e, run["epochs"][-1], f"{time.time() - t:.0f}s", flush=True)
         out["runs"].append(run)
-        with open(os.path.join(HERE, "mid_hogwild_reference.json"), "w") as f:
+        with open(path, "w") as f:
             json.dump(out, f, indent=1)
 
 
