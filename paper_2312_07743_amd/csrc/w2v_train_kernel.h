@@ -165,7 +165,7 @@ constexpr uint32_t kNoWord = 0xFFFFFFFFu;
 
 // MULTI: more than KC output rows per window (N + 1 > KC), handled KC at a time
 // wavefronts per SIMD the register allocator is asked to make room for (512 VGPRs per lane in all)
-constexpr int occupancy_goal(int e, int wcap) { return (e <= 2 && wcap <= 5) ? 3 : ((e * wcap <= 20) ? 2 : 1); }
+constexpr int occupancy_goal(int e, int wcap) { return (e <= 2 && wcap <= 5) ? 3 : ((e * wcap <= 25) ? 2 : 1); }
 
 template <int VW, int R, int WCAP, bool FULL, bool MULTI>
 __global__ void __launch_bounds__(kLanes) __attribute__((amdgpu_waves_per_eu(occupancy_goal(VW * R, WCAP))))
