@@ -25,6 +25,7 @@ WORKLOADS = {
     "mid": (dict(vocab=71000, s=1.05, n_sent=17000, sent_len=1000, seed=1), 128, 5, 5, 1e-4, 1 << 24),
     # prefixes of the two big configurations (same vocabulary / row sizes, fewer sentences), for --workload only
     "large": (dict(vocab=550000, s=1.1, n_sent=40000, sent_len=1000, seed=1), 300, 5, 10, 1e-5, 1 << 24),
+    "graph": (dict(n_nodes=1000000, m=5, walks_per_node=1, walk_len=80, seed=1), 128, 10, 5, 0.0, 1 << 24),
     "small": (dict(vocab=8000, s=1.05, n_sent=600, sent_len=1000, seed=1, band_start=400), 128, 5, 5, 1e-4, 1 << 20),
 }
 
@@ -65,7 +66,12 @@ def main():
     gen_kw, dim, window, negatives, t_sub, table_size = WORKLOADS[args.workload]
     if args.dim:
         dim = args.dim
-    corpus = synth.planted_corpus(**gen_kw)
+    if args.workload == "graph":
+        corpus = synth.barabasi_albert_walks(**gen_kw)
+        what = f"Barabasi-Albert graph ({gen_kw['n_nodes']} nodes, m={gen_kw['m']}), uniform walks of {gen_kw['walk_len']}"
+    else:
+        corpus = synth.planted_corpus(**gen_kw)
+        what = f"Zipf({gen_kw['s']}) + 16 planted clusters"
     E = args.warmup + args.steps
     tr = Trainer(vocab=corpus.vocab, dim=dim, window=window, negatives=negatives, counts=corpus.counts,
                  tokens_per_epoch=corpus.n_tokens, seed=2024, table_size=table_size, subsample_t=t_sub,
@@ -108,9 +114,9 @@ def main():
         "value": words / wall, "unit": "words/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": wall / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: vocab {corpus.vocab} Zipf({gen_kw['s']}) + 16 planted clusters, "
+        "config": {"workload": f"{args.workload}: vocab {corpus.vocab} {what}, "
                                f"{corpus.n_tokens} tokens in {corpus.n_sent} sentences, d={dim}, W={window}, "
-                               f"N={negatives}, subsample t={t_sub}, min-count 5, lr 0.025 linear decay",
+                               f"N={negatives}, subsample t={t_sub}, lr 0.025 linear decay",
                    "kept_words_per_s": kept / wall, "kept_fraction": kept / words,
                    "mean_loss": loss_sum / max(pairs, 1), "sentences_in_flight": args.in_flight},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
