@@ -155,11 +155,12 @@ __device__ __forceinline__ float sentence_lr(const KernelArgs &A, uint64_t start
 // the window kernel
 // ---------------------------------------------------------------------------------------------
 // Per-window scalars the sampling stage leaves in LDS for the window loop (one uint4 per window):
-//   x = width b | (reload bits << 8) | (dup << 16) | (plain << 17)
+//   x = width b | (reload bits << 8) | (atomic << 16) | (plain << 17),  w = dupmask
 //       reload bit k': output row k' (k' < KC) of this window is also an output row of the previous
 //       window, so a copy fetched before that window's write-back is stale;
-//       dup: two context positions of the window hold the same word and share a ring row;
-//       plain: no dup, and every negative is distinct and differs from the target (multiplicity 1)
+//       dupmask bit c: context slot c holds the same word as an earlier slot and is represented by it;
+//       atomic: a word fills more than 15 slots, multiplicities are not used and ring rows are added to;
+//       plain: no repeated context word, every negative distinct and different from the target
 //   y = target word, z = word of the kept position that enters the ring at this window (or none)
 constexpr uint32_t kNoWord = 0xFFFFFFFFu;
 
@@ -183,7 +184,8 @@ train_kernel(KernelArgs A)
     int32_t *kw = reinterpret_cast<int32_t *>(ring + (size_t)nslots * ROWF);  // kept word ids (FIFO)
     uint32_t *kp = reinterpret_cast<uint32_t *>(kw + FCAP);                  // their offsets in the sentence
     uint4 *cb_meta = reinterpret_cast<uint4 *>(kp + FCAP);                   // per-window scalars of the chunk
-    uint32_t *cb_pack = reinterpret_cast<uint32_t *>(cb_meta + kLanes);      // [64][N] negative id | multiplicity<<27
+    uint32_t *cb_cm = reinterpret_cast<uint32_t *>(cb_meta + kLanes);        // [64][4] context multiplicities, 4 bits per slot
+    uint32_t *cb_pack = cb_cm + 4 * kLanes;                                  // [64][N] negative id | multiplicity<<27
 
     // element offsets of this lane inside a row, and whether they exist (dim may not fill 64*E)
     int eoff[R];
@@ -339,20 +341,38 @@ train_kernel(KernelArgs A)
                         if (hit) reload |= 1u << kk;
                     }
                 }
-                // do two context positions of my window hold the same word (and so share a ring row)?
-                uint32_t dup = 0;
+                // Context positions of my window that hold the same word share one ring row and one set of dot
+                // products: the first such slot (in slot order) stands for all of them with a multiplicity, the
+                // others are switched off (dupmask).  Slot c <-> distance (c>>1)+1, right side if c is odd.
+                uint32_t dupmask = 0, any_dup = 0, overflow = 0;
                 {
                     const uint32_t me = i0 + lane;
-                    const uint32_t lo = (me > my_b) ? me - my_b : 0u;
-                    const uint32_t hi = (me + my_b < n_prod) ? me + my_b : n_prod - 1u;
-                    for (uint32_t p1 = lo; p1 < hi; ++p1) {
-                        if (p1 == me) continue;
-                        const int32_t w1 = kw[p1 & (FCAP - 1)];
-                        for (uint32_t p2 = p1 + 1; p2 <= hi; ++p2)
-                            if (p2 != me && kw[p2 & (FCAP - 1)] == w1) dup = 1u;
+                    uint32_t *cm = cb_cm + 4 * lane;
+                    cm[0] = cm[1] = cm[2] = cm[3] = 0u;
+                    auto slot_pos = [&](uint32_t c, uint32_t &p) -> bool {     // position of slot c, false if absent
+                        const uint32_t a = (c >> 1) + 1u;
+                        if (c & 1u) { p = me + a; return p < n_prod; }
+                        p = me - a;
+                        return me >= a;
+                    };
+                    for (uint32_t c = 0; c < 2u * my_b; ++c) {
+                        uint32_t p, p2;
+                        if (!slot_pos(c, p)) continue;
+                        const int32_t w1 = kw[p & (FCAP - 1)];
+                        bool earlier = false;
+                        for (uint32_t c2 = 0; c2 < c && !earlier; ++c2)
+                            earlier = slot_pos(c2, p2) && kw[p2 & (FCAP - 1)] == w1;
+                        if (earlier) { dupmask |= 1u << c; any_dup = 1u; continue; }
+                        uint32_t m = 1u;
+                        for (uint32_t c2 = c + 1; c2 < 2u * my_b; ++c2)
+                            if (slot_pos(c2, p2) && kw[p2 & (FCAP - 1)] == w1) ++m;
+                        if (m > 15u) overflow = 1u;
+                        cm[c >> 3] |= (m & 15u) << (4u * (c & 7u));
                     }
+                    if (overflow) dupmask = 0u;      // pathological repetition: every slot stays on, rows are added to atomically
                 }
-                cb_meta[lane] = make_uint4(my_b | (reload << 8) | (dup << 16) | ((my_plain & (dup ^ 1u)) << 17), (uint32_t)my_w, my_enter, 0u);
+                cb_meta[lane] = make_uint4(my_b | (reload << 8) | (overflow << 16) | ((my_plain & (any_dup ^ 1u)) << 17),
+                                           (uint32_t)my_w, my_enter, dupmask);
             }
             __syncthreads();
 
@@ -393,6 +413,7 @@ train_kernel(KernelArgs A)
                 const uint32_t b = uni(mraw.x) & 0xFFu;
                 const bool shared_rows = (uni(mraw.x) >> 16) & 1u;
                 const bool plain = (uni(mraw.x) >> 17) & 1u;
+                const uint32_t dupmask = uni(mraw.w);
                 const uint32_t enter_word = uni(mraw.z);
                 const bool has_next = j + 1 < nwin;
 
@@ -419,9 +440,10 @@ train_kernel(KernelArgs A)
                 //     amask bit c set when that position exists and lies within the width
                 const uint32_t nl = (b < i) ? b : i;
                 const uint32_t nr = (b < n_prod - 1 - i) ? b : n_prod - 1 - i;
-                const uint32_t amask = uni((0x55555555u & (uint32_t)((1ull << (2 * nl)) - 1ull)) | (0xAAAAAAAAu & (uint32_t)((1ull << (2 * nr)) - 1ull)));
+                const uint32_t amask_all = uni((0x55555555u & (uint32_t)((1ull << (2 * nl)) - 1ull)) | (0xAAAAAAAAu & (uint32_t)((1ull << (2 * nr)) - 1ull)));
                 const uint32_t nact = nl + nr;
                 const bool interior = nl == b && nr == b;
+                const uint32_t amask = amask_all & ~dupmask;          // slots that take part
 
                 // (d) the next window's output rows start their trip from memory
                 uint32_t packv_next = pack_next;
@@ -508,16 +530,21 @@ train_kernel(KernelArgs A)
                             const float xraw = (q == NQW - 1) ? transpose_reduce<NCLAST * KC>(acc, lane)
                                                               : transpose_reduce<CC * KC>(acc, lane);
                             bool act = lane < NC * KC && (GENERAL ? mult_lane > 0.0f : gk <= N);
-                            if (MASKED) act = act && ((amask >> (q * CC + lane_c)) & 1u);
+                            float cmult = 1.0f;                      // how many context positions this slot stands for
+                            if (MASKED) {
+                                const uint32_t gc = (uint32_t)(q * CC + lane_c);
+                                act = act && gc < 32u && ((amask >> gc) & 1u);
+                                if (dupmask && gc < 32u) cmult = (float)((cb_cm[4 * j + (gc >> 3)] >> (4u * (gc & 7u))) & 15u);
+                            }
                             // sigmoid and log-loss from u = 1 + exp(-x): sigma = 1/u, -log sigma(x) = log u,
                             // -log sigma(-x) = x + log u   (x clamped where exp would overflow)
                             // (hardware exp2 / log2 / rcp: about 1 ulp each, far inside the parity budget)
                             const float xv = __builtin_amdgcn_fmed3f(xraw, -80.0f, 80.0f);
                             const float u = 1.0f + __builtin_amdgcn_exp2f(xv * -1.44269504088896341f);
-                            const float g = act ? gscale * (label - __builtin_amdgcn_rcpf(u)) : 0.0f;
+                            const float g = act ? (GENERAL ? gscale * cmult : gscale) * (label - __builtin_amdgcn_rcpf(u)) : 0.0f;
                             if (act) {
                                 const float l1 = __builtin_fmaf(__builtin_amdgcn_logf(u), 0.693147180559945309f, (gk == 0) ? 0.0f : xv);
-                                loss_acc += (double)(GENERAL ? mult_lane * l1 : l1);
+                                loss_acc += (double)(GENERAL ? mult_lane * cmult * l1 : l1);
                             }
 #pragma unroll
                             for (int cc = 0; cc < CC; ++cc) {

@@ -107,6 +107,31 @@ def test_degenerate_sentences(orc32):
     _parity(orc32, c, dim=128, window=5, negatives=5, seed=5, table_size=4099, subsample_t=2e-2)
 
 
+def test_repeated_context_words(orc32):
+    # walks that step back and stay: most windows hold a word at several context positions (one ring row,
+    # counted with its multiplicity); a run of one word fills more than 15 slots of a wide window
+    rng = np.random.default_rng(8)
+
+    def walk(n, V):
+        out = [int(rng.integers(0, V))]
+        for _ in range(n - 1):
+            r = rng.random()
+            if r < 0.35 and len(out) >= 2:
+                out.append(out[-2])
+            elif r < 0.45:
+                out.append(out[-1])
+            else:
+                out.append(int(rng.integers(0, V)))
+        return out
+
+    parts = [walk(120, 200) for _ in range(6)] + [[7] * 40, [1, 2] * 25]
+    tok = np.array([t for p in parts for t in p], np.int32)
+    off = np.cumsum([0] + [len(p) for p in parts]).astype(np.uint64)
+    c = synth.Corpus(tok, off, np.bincount(tok, minlength=200).astype(np.uint64))
+    for window, negatives in ((10, 5), (16, 3), (5, 10)):
+        _parity(orc32, c, dim=128, window=window, negatives=negatives, seed=2, table_size=4099)
+
+
 def test_second_epoch_and_split_feeding(orc32):
     # epoch index and first_token_global_pos enter the random keys and the learning rate
     c = synth.zipf_corpus(200, 1.0, 6, 300, seed=1)
