@@ -102,7 +102,7 @@ bool pick_row_shape(uint32_t dim, uint32_t ld, RowShape *out)
 uint32_t train_lds_bytes(const KernelArgs &a, RowShape s)
 {
     const uint32_t rowf = kLanes * s.vw * s.r;
-    return (2 * a.window + 2) * rowf * 4u + FCAP * 8u + kLanes * 32u + kLanes * a.negatives * 4u;
+    return (2 * a.window + 3) * rowf * 4u + FCAP * 8u + kLanes * 32u + kLanes * a.negatives * 4u;
 }
 
 hipError_t launch_init_weights(float *syn0, float *syn1neg, uint32_t vocab, uint32_t dim, uint32_t ld,

@@ -155,12 +155,13 @@ __device__ __forceinline__ float sentence_lr(const KernelArgs &A, uint64_t start
 // the window kernel
 // ---------------------------------------------------------------------------------------------
 // Per-window scalars the sampling stage leaves in LDS for the window loop (one uint4 per window):
-//   x = width b | (reload bits << 8) | (atomic << 16) | (plain << 17),  w = dupmask
+//   x = width b | (reload bits << 8) | (atomic << 16) | (plain << 17) | (special << 18),  w = dupmask
 //       reload bit k': output row k' (k' < KC) of this window is also an output row of the previous
 //       window, so a copy fetched before that window's write-back is stale;
-//       dupmask bit c: context slot c holds the same word as an earlier slot and is represented by it;
-//       atomic: a word fills more than 15 slots, multiplicities are not used and ring rows are added to;
-//       plain: no repeated context word, every negative distinct and different from the target
+//       dupmask bit c: context slot c holds the same word as a later slot and is represented by it;
+//       atomic: a word fills more than 15 slots, weights are not used and ring rows are added to;
+//       plain: every negative distinct and different from the target;
+//       special: some context slot of the window is absent or repeats a word (slot weights differ from 1)
 //   y = target word, z = word of the kept position that enters the ring at this window (or none)
 constexpr uint32_t kNoWord = 0xFFFFFFFFu;
 
@@ -181,7 +182,8 @@ train_kernel(KernelArgs A)
     const uint32_t W = A.window, N = A.negatives;
     const uint32_t nslots = 2 * W + 2;
     float *ring = reinterpret_cast<float *>(lds_raw);
-    int32_t *kw = reinterpret_cast<int32_t *>(ring + (size_t)nslots * ROWF);  // kept word ids (FIFO)
+    // ring row `nslots` is never assigned to a word: it holds zeros and stands in for context slots that do not exist
+    int32_t *kw = reinterpret_cast<int32_t *>(ring + (size_t)(nslots + 1) * ROWF);  // kept word ids (FIFO)
     uint32_t *kp = reinterpret_cast<uint32_t *>(kw + FCAP);                  // their offsets in the sentence
     uint4 *cb_meta = reinterpret_cast<uint4 *>(kp + FCAP);                   // per-window scalars of the chunk
     uint32_t *cb_cm = reinterpret_cast<uint32_t *>(cb_meta + kLanes);        // [64][4] context multiplicities, 4 bits per slot
@@ -196,6 +198,10 @@ train_kernel(KernelArgs A)
         evalid[r] = FULL || (uint32_t)eoff[r] < A.dim;
     }
     const int lane_c = lane / KC, lane_k = lane % KC;   // pairing handled by this lane after the reduction
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int x = 0; x < VW; ++x) ring[(size_t)nslots * ROWF + eoff[r] + x] = 0.0f;
 
     double loss_acc = 0.0;
     unsigned long long pairs_acc = 0, dropped_acc = 0, kept_acc = 0;
@@ -341,10 +347,11 @@ train_kernel(KernelArgs A)
                         if (hit) reload |= 1u << kk;
                     }
                 }
-                // Context positions of my window that hold the same word share one ring row and one set of dot
-                // products: the first such slot (in slot order) stands for all of them with a multiplicity, the
-                // others are switched off (dupmask).  Slot c <-> distance (c>>1)+1, right side if c is odd.
-                uint32_t dupmask = 0, any_dup = 0, overflow = 0;
+                // Context slots of my window (slot c <-> distance (c>>1)+1, right side if c is odd) get a 4-bit
+                // weight: 0 for a slot whose position does not exist, 0 for a slot whose word comes again in a
+                // later slot (dupmask), and for the last slot of a word the number of slots that hold it.  Slots
+                // of one word share one ring row and one set of dot products, so the last one stands for all.
+                uint32_t dupmask = 0, special = 0, overflow = 0;
                 {
                     const uint32_t me = i0 + lane;
                     uint32_t *cm = cb_cm + 4 * lane;
@@ -357,21 +364,22 @@ train_kernel(KernelArgs A)
                     };
                     for (uint32_t c = 0; c < 2u * my_b; ++c) {
                         uint32_t p, p2;
-                        if (!slot_pos(c, p)) continue;
+                        if (!slot_pos(c, p)) { special = 1u; continue; }
                         const int32_t w1 = kw[p & (FCAP - 1)];
-                        bool earlier = false;
-                        for (uint32_t c2 = 0; c2 < c && !earlier; ++c2)
-                            earlier = slot_pos(c2, p2) && kw[p2 & (FCAP - 1)] == w1;
-                        if (earlier) { dupmask |= 1u << c; any_dup = 1u; continue; }
+                        bool later = false;
+                        for (uint32_t c2 = c + 1; c2 < 2u * my_b && !later; ++c2)
+                            later = slot_pos(c2, p2) && kw[p2 & (FCAP - 1)] == w1;
+                        if (later) { dupmask |= 1u << c; special = 1u; continue; }
                         uint32_t m = 1u;
-                        for (uint32_t c2 = c + 1; c2 < 2u * my_b; ++c2)
+                        for (uint32_t c2 = 0; c2 < c; ++c2)
                             if (slot_pos(c2, p2) && kw[p2 & (FCAP - 1)] == w1) ++m;
+                        if (m > 1u) special = 1u;
                         if (m > 15u) overflow = 1u;
                         cm[c >> 3] |= (m & 15u) << (4u * (c & 7u));
                     }
                     if (overflow) dupmask = 0u;      // pathological repetition: every slot stays on, rows are added to atomically
                 }
-                cb_meta[lane] = make_uint4(my_b | (reload << 8) | (overflow << 16) | ((my_plain & (any_dup ^ 1u)) << 17),
+                cb_meta[lane] = make_uint4(my_b | (reload << 8) | (overflow << 16) | (my_plain << 17) | (special << 18),
                                            (uint32_t)my_w, my_enter, dupmask);
             }
             __syncthreads();
@@ -413,6 +421,7 @@ train_kernel(KernelArgs A)
                 const uint32_t b = uni(mraw.x) & 0xFFu;
                 const bool shared_rows = (uni(mraw.x) >> 16) & 1u;
                 const bool plain = (uni(mraw.x) >> 17) & 1u;
+                const bool special = (uni(mraw.x) >> 18) & 1u;
                 const uint32_t dupmask = uni(mraw.w);
                 const uint32_t enter_word = uni(mraw.z);
                 const bool has_next = j + 1 < nwin;
@@ -442,7 +451,6 @@ train_kernel(KernelArgs A)
                 const uint32_t nr = (b < n_prod - 1 - i) ? b : n_prod - 1 - i;
                 const uint32_t amask_all = uni((0x55555555u & (uint32_t)((1ull << (2 * nl)) - 1ull)) | (0xAAAAAAAAu & (uint32_t)((1ull << (2 * nr)) - 1ull)));
                 const uint32_t nact = nl + nr;
-                const bool interior = nl == b && nr == b;
                 const uint32_t amask = amask_all & ~dupmask;          // slots that take part
 
                 // (d) the next window's output rows start their trip from memory
@@ -480,6 +488,7 @@ train_kernel(KernelArgs A)
                             const uint32_t a = (uint32_t)(c >> 1) + 1u;
                             const uint32_t p = (c & 1) ? i + a : i - a;
                             cslot[c] = lane_value(meta_slot, p & 63u);
+                            if (!MASKED && !((amask_all >> c) & 1u)) cslot[c] = nslots;    // absent: the zero row
                             const float *src = ring + (size_t)cslot[c] * ROWF;
 #pragma unroll
                             for (int r = 0; r < R; ++r) load_vec<VW>(src + eoff[r], &I[c][r * VW]);
@@ -531,20 +540,23 @@ train_kernel(KernelArgs A)
                                                               : transpose_reduce<CC * KC>(acc, lane);
                             bool act = lane < NC * KC && (GENERAL ? mult_lane > 0.0f : gk <= N);
                             float cmult = 1.0f;                      // how many context positions this slot stands for
-                            if (MASKED) {
+                            {
                                 const uint32_t gc = (uint32_t)(q * CC + lane_c);
-                                act = act && gc < 32u && ((amask >> gc) & 1u);
-                                if (dupmask && gc < 32u) cmult = (float)((cb_cm[4 * j + (gc >> 3)] >> (4u * (gc & 7u))) & 15u);
+                                if (MASKED) act = act && gc < 32u && ((amask >> gc) & 1u);
+                                if ((MASKED ? dupmask != 0u : special) && gc < 32u) {
+                                    cmult = (float)((cb_cm[4 * j + (gc >> 3)] >> (4u * (gc & 7u))) & 15u);
+                                    if (!MASKED) act = act && cmult > 0.0f;
+                                }
                             }
                             // sigmoid and log-loss from u = 1 + exp(-x): sigma = 1/u, -log sigma(x) = log u,
                             // -log sigma(-x) = x + log u   (x clamped where exp would overflow)
                             // (hardware exp2 / log2 / rcp: about 1 ulp each, far inside the parity budget)
                             const float xv = __builtin_amdgcn_fmed3f(xraw, -80.0f, 80.0f);
                             const float u = 1.0f + __builtin_amdgcn_exp2f(xv * -1.44269504088896341f);
-                            const float g = act ? (GENERAL ? gscale * cmult : gscale) * (label - __builtin_amdgcn_rcpf(u)) : 0.0f;
+                            const float g = act ? gscale * cmult * (label - __builtin_amdgcn_rcpf(u)) : 0.0f;
                             if (act) {
                                 const float l1 = __builtin_fmaf(__builtin_amdgcn_logf(u), 0.693147180559945309f, (gk == 0) ? 0.0f : xv);
-                                loss_acc += (double)(GENERAL ? mult_lane * cmult * l1 : l1);
+                                loss_acc += (double)(GENERAL ? mult_lane * cmult * l1 : cmult * l1);
                             }
 #pragma unroll
                             for (int cc = 0; cc < CC; ++cc) {
@@ -615,8 +627,8 @@ train_kernel(KernelArgs A)
                     using F = integral_constant<bool, false>;
 #define W2V_WIN(NCV) do_window(integral_constant<int, (NCV)>{}, F{})
                     bool done = false;
-                    if (interior && plain) {
-                        // the common window: straight-line code per width
+                    if (plain && !shared_rows) {
+                        // straight-line code per width; absent and repeated slots carry weight 0
                         done = true;
                         switch (b) {
                         case 1: W2V_WIN(2); break;
