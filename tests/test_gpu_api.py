@@ -1,0 +1,76 @@
+"""GPU tests of the C ABI's call sequence and error reporting (the argument checks that need a context)."""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2312_07743_amd import binding as B
+from paper_2312_07743_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _raw_context(vocab=50, dim=64, table_size=1 << 10):
+    ld = B.w2v_query_ld(dim)
+    syn0 = torch.zeros((vocab, ld), dtype=torch.float32, device="cuda")
+    syn1 = torch.zeros((vocab, ld), dtype=torch.float32, device="cuda")
+    nbytes = B.w2v_query_workspace(vocab, table_size)
+    ws = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    cfg = B.make_config(vocab=vocab, dim=dim, window=3, negatives=2, tokens_per_epoch=100, seed=1, syn0=syn0,
+                        syn1neg=syn1, ld=ld, workspace=ws, workspace_bytes=nbytes, total_epochs=2,
+                        stream=torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    return B.w2v_create(cfg, 1), (syn0, syn1, ws)
+
+
+def test_call_order_and_argument_errors():
+    ctx, keep = _raw_context()
+    L = B.lib()
+    tok = torch.zeros(100, dtype=torch.int32, device="cuda")
+    off = torch.tensor([0, 100], dtype=torch.int64, device="cuda")
+    # training before the table exists
+    assert L.w2v_train_epoch(ctx, tok.data_ptr(), off.data_ptr(), 1, 0, 0) == B.W2V_ESTATE
+    assert "w2v_build_unigram_table" in B.w2v_last_error(ctx)
+    counts = np.ones(50, np.uint64)
+    # a table larger than the workspace was sized for; all-zero counts; null counts
+    assert L.w2v_build_unigram_table(ctx, counts.ctypes.data, 1 << 20) == B.W2V_ENOMEM
+    assert L.w2v_build_unigram_table(ctx, np.zeros(50, np.uint64).ctypes.data, 1 << 10) == B.W2V_EINVAL
+    assert L.w2v_build_unigram_table(ctx, None, 1 << 10) == B.W2V_EINVAL
+    assert L.w2v_build_unigram_table(ctx, counts.ctypes.data, 0) == B.W2V_EINVAL
+    B.w2v_build_unigram_table(ctx, counts, 1 << 10)
+    assert L.w2v_train_epoch(ctx, tok.data_ptr(), off.data_ptr(), 1, 0, 2) == B.W2V_EINVAL      # epoch >= total_epochs
+    assert L.w2v_train_epoch(ctx, tok.data_ptr(), off.data_ptr(), 1, 101, 0) == B.W2V_EINVAL    # position beyond the epoch
+    assert L.w2v_train_epoch(ctx, None, off.data_ptr(), 1, 0, 0) == B.W2V_EINVAL
+    assert L.w2v_train_epoch(ctx, None, None, 0, 0, 0) == B.W2V_OK                              # nothing to do
+    assert L.w2v_debug_draws(ctx, tok.data_ptr(), off.data_ptr(), 1, 0, 0, None, None, None) == B.W2V_EINVAL
+    assert L.w2v_get_embeddings(ctx, 2, tok.data_ptr(), 10**9, 1) == B.W2V_EINVAL
+    assert L.w2v_get_embeddings(ctx, 0, tok.data_ptr(), 10, 1) == B.W2V_EINVAL                  # destination too small
+    assert L.w2v_get_embeddings(ctx, 0, None, 10**9, 1) == B.W2V_EINVAL
+    B.w2v_train_epoch(ctx, tok, off, 1, 0, 0)
+    B.w2v_destroy(ctx)
+    del keep
+
+
+def test_embeddings_to_device_loss_reset_and_counters():
+    from paper_2312_07743_amd.trainer import Trainer
+    c = synth.zipf_corpus(120, 1.0, 5, 200, seed=3)
+    tok = c.tokens.copy()
+    tok[3] = -7
+    tr = Trainer(vocab=c.vocab, dim=100, window=4, negatives=3, counts=c.counts, tokens_per_epoch=c.n_tokens, seed=8,
+                 table_size=1 << 12, total_epochs=2)
+    tr.set_corpus(tok, c.sent_off)
+    tr.train_epoch(0)
+    kept, invalid = tr.counters()
+    assert invalid == 1 and kept == c.n_tokens - 1
+    loss, pairs = tr.loss(reset=True)
+    assert pairs > 0 and loss > 0
+    assert tr.loss() == (0.0, 0) and tr.counters() == (0, 0)
+    host = tr.embeddings(0)
+    dev = torch.empty((c.vocab, 100), dtype=torch.float32, device="cuda")
+    B.w2v_get_embeddings(tr.ctx, 0, dev, dev.numel(), True)
+    assert np.array_equal(dev.cpu().numpy(), host)
+    assert np.array_equal(tr.syn0[:, :100].cpu().numpy(), host)
+    tr.train_epoch(1)
+    assert tr.loss()[1] > 0
+    tr.close()
