@@ -23,7 +23,10 @@ namespace {
 
 constexpr int kLanes = 64;
 constexpr int KC = 6;              // output rows held in registers at once
-constexpr int CC = 10;             // context rows whose pairings are reduced together (CC*KC <= 64)
+#ifndef W2V_CC
+#define W2V_CC 10
+#endif
+constexpr int CC = W2V_CC;         // most context rows whose pairings are reduced together (CC*KC <= 64)
 constexpr int FCAP = 256;          // kept-token FIFO entries per wavefront (power of two)
 constexpr uint32_t kIdBits = 27;
 constexpr uint32_t kIdMask = (1u << kIdBits) - 1u;
@@ -167,7 +170,10 @@ constexpr uint32_t kNoWord = 0xFFFFFFFFu;
 
 // MULTI: more than KC output rows per window (N + 1 > KC), handled KC at a time
 // wavefronts per SIMD the register allocator is asked to make room for (512 VGPRs per lane in all)
-constexpr int occupancy_goal(int e, int wcap) { return (e <= 2 && wcap <= 5) ? 3 : ((e * wcap <= 25) ? 2 : 1); }
+#ifndef W2V_OCC_SMALL
+#define W2V_OCC_SMALL 3
+#endif
+constexpr int occupancy_goal(int e, int wcap) { return (e <= 2 && wcap <= 5) ? W2V_OCC_SMALL : ((e * wcap <= 25) ? 2 : 1); }
 
 template <int VW, int R, int WCAP, bool FULL, bool MULTI>
 __global__ void __launch_bounds__(kLanes) __attribute__((amdgpu_waves_per_eu(occupancy_goal(VW * R, WCAP))))
@@ -476,7 +482,9 @@ train_kernel(KernelArgs A)
                     constexpr int NCW = decltype(ncw_tag)::value;
                     constexpr bool MASKED = decltype(general_tag)::value;
                     constexpr bool GENERAL = MASKED;
+                    // the NCW slots are handled in NQW blocks of nearly equal size (BASE or BASE+1 slots)
                     constexpr int NQW = (NCW + CC - 1) / CC;
+                    constexpr int BASE = NCW / NQW, REM = NCW % NQW;
                     float I[NCW][E];
                     uint32_t cslot[NCW];
 #pragma unroll
@@ -518,14 +526,14 @@ train_kernel(KernelArgs A)
 
 #pragma unroll
                         for (int q = 0; q < NQW; ++q) {
-                            // NC context rows (slots q*CC .. q*CC+NC-1) against the KC output rows
-                            constexpr int NCLAST = NCW - (NQW - 1) * CC;
-                            const int NC = (q == NQW - 1) ? NCLAST : CC;
-                            if (MASKED && !(amask >> (q * CC))) break;
+                            // NC context rows (slots C0 .. C0+NC-1) against the KC output rows
+                            const int NC = (q < REM) ? BASE + 1 : BASE;
+                            const int C0 = q * BASE + (q < REM ? q : REM);
+                            if (MASKED && !(amask >> C0)) break;
                             float acc[CC * KC];
 #pragma unroll
                             for (int cc = 0; cc < CC; ++cc) {
-                                const int c = q * CC + cc;
+                                const int c = C0 + cc;
 #pragma unroll
                                 for (int kk = 0; kk < KC; ++kk) {
                                     float p = 0.0f;
@@ -536,12 +544,12 @@ train_kernel(KernelArgs A)
                                     acc[cc * KC + kk] = p;
                                 }
                             }
-                            const float xraw = (q == NQW - 1) ? transpose_reduce<NCLAST * KC>(acc, lane)
-                                                              : transpose_reduce<CC * KC>(acc, lane);
+                            const float xraw = (q < REM) ? transpose_reduce<(REM ? BASE + 1 : BASE) * KC>(acc, lane)
+                                                         : transpose_reduce<BASE * KC>(acc, lane);
                             bool act = lane < NC * KC && (GENERAL ? mult_lane > 0.0f : gk <= N);
                             float cmult = 1.0f;                      // how many context positions this slot stands for
                             {
-                                const uint32_t gc = (uint32_t)(q * CC + lane_c);
+                                const uint32_t gc = (uint32_t)(C0 + lane_c);
                                 if (MASKED) act = act && gc < 32u && ((amask >> gc) & 1u);
                                 if ((MASKED ? dupmask != 0u : special) && gc < 32u) {
                                     cmult = (float)((cb_cm[4 * j + (gc >> 3)] >> (4u * (gc & 7u))) & 15u);
@@ -560,7 +568,7 @@ train_kernel(KernelArgs A)
                             }
 #pragma unroll
                             for (int cc = 0; cc < CC; ++cc) {
-                                const int c = q * CC + cc;
+                                const int c = C0 + cc;
                                 if (cc < NC && (!MASKED || ((amask >> c) & 1u))) {
                                     float dI[E];
 #pragma unroll
