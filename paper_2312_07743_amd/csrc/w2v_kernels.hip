@@ -59,27 +59,37 @@ __global__ void __launch_bounds__(kLanes) reduce_selftest_kernel(const float *in
 
 }  // namespace
 
-TrainFn train_fn_v1r1m0(uint32_t window, bool full);
-TrainFn train_fn_v1r1m1(uint32_t window, bool full);
-TrainFn train_fn_v2r1m0(uint32_t window, bool full);
-TrainFn train_fn_v2r1m1(uint32_t window, bool full);
-TrainFn train_fn_v4r1m0(uint32_t window, bool full);
-TrainFn train_fn_v4r1m1(uint32_t window, bool full);
-TrainFn train_fn_v1r5m0(uint32_t window, bool full);
-TrainFn train_fn_v1r5m1(uint32_t window, bool full);
-TrainFn train_fn_v4r2m0(uint32_t window, bool full);
-TrainFn train_fn_v4r2m1(uint32_t window, bool full);
+TrainFn train_fn_v1r1k0(uint32_t window, bool full);
+TrainFn train_fn_v1r1k1(uint32_t window, bool full);
+TrainFn train_fn_v1r1k2(uint32_t window, bool full);
+TrainFn train_fn_v2r1k0(uint32_t window, bool full);
+TrainFn train_fn_v2r1k1(uint32_t window, bool full);
+TrainFn train_fn_v2r1k2(uint32_t window, bool full);
+TrainFn train_fn_v4r1k0(uint32_t window, bool full);
+TrainFn train_fn_v4r1k1(uint32_t window, bool full);
+TrainFn train_fn_v4r1k2(uint32_t window, bool full);
+TrainFn train_fn_v1r5k0(uint32_t window, bool full);
+TrainFn train_fn_v1r5k1(uint32_t window, bool full);
+TrainFn train_fn_v1r5k2(uint32_t window, bool full);
+TrainFn train_fn_v4r2k0(uint32_t window, bool full);
+TrainFn train_fn_v4r2k1(uint32_t window, bool full);
+TrainFn train_fn_v4r2k2(uint32_t window, bool full);
 
 namespace {
 TrainFn train_fn(const KernelArgs &a, RowShape s)
 {
     const bool full = a.dim == (uint32_t)(kLanes * s.vw * s.r);
-    const bool multi = a.negatives + 1 > (uint32_t)KC;
-    if (s.vw == 1 && s.r == 1) return multi ? train_fn_v1r1m1(a.window, full) : train_fn_v1r1m0(a.window, full);
-    if (s.vw == 2 && s.r == 1) return multi ? train_fn_v2r1m1(a.window, full) : train_fn_v2r1m0(a.window, full);
-    if (s.vw == 4 && s.r == 1) return multi ? train_fn_v4r1m1(a.window, full) : train_fn_v4r1m0(a.window, full);
-    if (s.vw == 1 && s.r == 5) return multi ? train_fn_v1r5m1(a.window, full) : train_fn_v1r5m0(a.window, full);
-    if (s.vw == 4 && s.r == 2) return multi ? train_fn_v4r2m1(a.window, full) : train_fn_v4r2m0(a.window, full);
+    const int kmode = (a.negatives + 1 > (uint32_t)KC) ? 2 : (a.negatives + 1 == (uint32_t)KC) ? 1 : 0;
+#define W2V_PICK(VW, R)                                                                              \
+    if (s.vw == VW && s.r == R)                                                                      \
+        return kmode == 2 ? train_fn_v##VW##r##R##k2(a.window, full)                                 \
+             : kmode == 1 ? train_fn_v##VW##r##R##k1(a.window, full) : train_fn_v##VW##r##R##k0(a.window, full);
+    W2V_PICK(1, 1)
+    W2V_PICK(2, 1)
+    W2V_PICK(4, 1)
+    W2V_PICK(1, 5)
+    W2V_PICK(4, 2)
+#undef W2V_PICK
     return nullptr;
 }
 }  // namespace

@@ -168,20 +168,24 @@ __device__ __forceinline__ float sentence_lr(const KernelArgs &A, uint64_t start
 //   y = target word, z = word of the kept position that enters the ring at this window (or none)
 constexpr uint32_t kNoWord = 0xFFFFFFFFu;
 
-// MULTI: more than KC output rows per window (N + 1 > KC), handled KC at a time
+// KMODE: how the N + 1 output rows of a window relate to the KC rows handled at a time:
+//   0: fewer than KC rows, 1: exactly KC rows (every row-exists test folds away), 2: more than KC rows
 // wavefronts per SIMD the register allocator is asked to make room for (512 VGPRs per lane in all)
 #ifndef W2V_OCC_SMALL
 #define W2V_OCC_SMALL 3
 #endif
 constexpr int occupancy_goal(int e, int wcap) { return (e <= 2 && wcap <= 5) ? W2V_OCC_SMALL : ((e * wcap <= 25) ? 2 : 1); }
 
-template <int VW, int R, int WCAP, bool FULL, bool MULTI>
+template <int VW, int R, int WCAP, bool FULL, int KMODE>
 __global__ void __launch_bounds__(kLanes) __attribute__((amdgpu_waves_per_eu(occupancy_goal(VW * R, WCAP))))
 train_kernel(KernelArgs A)
 {
     constexpr int E = VW * R;            // floats of a row per lane
     constexpr int ROWF = kLanes * E;     // floats of a ring row in LDS
     constexpr int NCTX = 2 * WCAP;       // context positions a window can have
+    constexpr bool MULTI = KMODE == 2;   // output rows beyond the first KC are handled in further passes
+    constexpr bool KFULL = KMODE >= 1;   // the first KC output rows all exist
+    constexpr bool KEXACT = KMODE == 1;  // ... and there are no others
 
     extern __shared__ __align__(16) unsigned char lds_raw[];
     const int lane = threadIdx.x;
@@ -411,7 +415,7 @@ train_kernel(KernelArgs A)
             // scalars and output rows of the first window; later windows get theirs one window ahead
             uint4 mraw = cb_meta[0];
             uint32_t packv = 0;
-            if (lane_k >= 1 && (uint32_t)lane_k <= N) packv = cb_pack[lane_k - 1];
+            if (lane_k >= 1 && (KFULL || (uint32_t)lane_k <= N)) packv = cb_pack[lane_k - 1];
             if (lane_k == 0) packv = mraw.y | (1u << kIdBits);
             float O[KC][E];
 #pragma unroll
@@ -419,7 +423,7 @@ train_kernel(KernelArgs A)
                 const uint32_t pk = lane_value(packv, (uint32_t)kk);
 #pragma unroll
                 for (int x = 0; x < E; ++x) O[kk][x] = 0.0f;
-                if ((uint32_t)kk <= N) load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, O[kk]);
+                if (KFULL || (uint32_t)kk <= N) load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, O[kk]);
             }
 
             for (uint32_t j = 0; j < nwin; ++j) {
@@ -437,7 +441,7 @@ train_kernel(KernelArgs A)
                 uint32_t pack_next = 0;
                 if (has_next) {
                     mraw_next = cb_meta[j + 1];
-                    if (lane_k >= 1 && (uint32_t)lane_k <= N) pack_next = cb_pack[(size_t)(j + 1) * N + (lane_k - 1)];
+                    if (lane_k >= 1 && (KFULL || (uint32_t)lane_k <= N)) pack_next = cb_pack[(size_t)(j + 1) * N + (lane_k - 1)];
                 }
 
                 // (b) the kept position i+W+1 enters the span: its row is fetched now and written into
@@ -469,7 +473,7 @@ train_kernel(KernelArgs A)
                         const uint32_t pk = lane_value(packv_next, (uint32_t)kk);
 #pragma unroll
                         for (int x = 0; x < E; ++x) On[kk][x] = 0.0f;
-                        if ((uint32_t)kk <= N) load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, On[kk]);
+                        if (KFULL || (uint32_t)kk <= N) load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, On[kk]);
                     }
                 }
 
@@ -515,7 +519,7 @@ train_kernel(KernelArgs A)
                                 if (kb + kk <= N) load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, O[kk]);
                             }
                         }
-                        const float mult_lane = (gk <= N) ? (GENERAL ? (float)(pv >> kIdBits) : 1.0f) : 0.0f;
+                        const float mult_lane = (KEXACT || gk <= N) ? (GENERAL ? (float)(pv >> kIdBits) : 1.0f) : 0.0f;
                         const float label = (gk == 0) ? 1.0f : 0.0f;
                         const float gscale = GENERAL ? alpha * mult_lane : alpha;
                         float dO[KC][E];
@@ -546,7 +550,7 @@ train_kernel(KernelArgs A)
                             }
                             const float xraw = (q < REM) ? transpose_reduce<(REM ? BASE + 1 : BASE) * KC>(acc, lane)
                                                          : transpose_reduce<BASE * KC>(acc, lane);
-                            bool act = lane < NC * KC && (GENERAL ? mult_lane > 0.0f : gk <= N);
+                            bool act = lane < NC * KC && (GENERAL ? mult_lane > 0.0f : (KEXACT || gk <= N));
                             float cmult = 1.0f;                      // how many context positions this slot stands for
                             {
                                 const uint32_t gc = (uint32_t)(C0 + lane_c);
@@ -619,7 +623,7 @@ train_kernel(KernelArgs A)
 #pragma unroll
                         for (int kk = 0; kk < KC; ++kk) {
                             const uint32_t pk = lane_value(pv, (uint32_t)kk);
-                            if (kb + kk <= N && (!GENERAL || (pk >> kIdBits))) {
+                            if ((KEXACT || kb + kk <= N) && (!GENERAL || (pk >> kIdBits))) {
                                 float t[E];
 #pragma unroll
                                 for (int x = 0; x < E; ++x) t[x] = O[kk][x] + dO[kk][x];

@@ -1,0 +1,7 @@
+// window kernel, rows of 1 x 1 floats per lane, fewer than 6 output rows per window
+#define W2V_VW 1
+#define W2V_R 1
+#define W2V_KMODE 0
+#define W2V_GUARDED_ONLY 0
+#define W2V_ENTRY train_fn_v1r1k0
+#include "w2v_train_inst.inc"

@@ -1,7 +1,7 @@
 // window kernel, rows of 1 x 5 floats per lane, more than 6 output rows per window
 #define W2V_VW 1
 #define W2V_R 5
-#define W2V_MULTI true
+#define W2V_KMODE 2
 #define W2V_GUARDED_ONLY 1
-#define W2V_ENTRY train_fn_v1r5m1
+#define W2V_ENTRY train_fn_v1r5k2
 #include "w2v_train_inst.inc"
