@@ -186,6 +186,7 @@ train_kernel(KernelArgs A)
     constexpr bool MULTI = KMODE == 2;   // output rows beyond the first KC are handled in further passes
     constexpr bool KFULL = KMODE >= 1;   // the first KC output rows all exist
     constexpr bool KEXACT = KMODE == 1;  // ... and there are no others
+    constexpr bool NREG = KMODE <= 1;    // at most KC - 1 negatives: the sampling stage keeps them in registers
 
     extern __shared__ __align__(16) unsigned char lds_raw[];
     const int lane = threadIdx.x;
@@ -317,9 +318,15 @@ train_kernel(KernelArgs A)
             const uint32_t nwin = (n_prod - i0 < (uint32_t)kLanes) ? n_prod - i0 : (uint32_t)kLanes;
 
             // ---- width and negatives of the chunk's windows, one window per lane ----------------
+            // Negative k of a window carries a multiplicity: 0 if it equals the target or an earlier negative,
+            // otherwise the number of times its id was drawn.  With at most KC-1 negatives (NREG) ids and
+            // multiplicities stay in registers and every comparison is unrolled; otherwise they are worked on
+            // in LDS.  Negatives that do not exist (k >= N) get ids no word has, so they match nothing.
             int32_t my_w = -1;
             uint32_t my_b = 0, my_enter = kNoWord, my_plain = 0;
-            if ((uint32_t)lane < nwin) {
+            uint32_t nid[NREG ? KC - 1 : 1] = {}, nmult[NREG ? KC - 1 : 1] = {};
+            const bool have = (uint32_t)lane < nwin;
+            if (have) {
                 const uint32_t idx = (i0 + lane) & (FCAP - 1);
                 my_w = kw[idx];
                 const uint64_t base = position_base(A.key, A.first_pos + t0 + kp[idx]);
@@ -327,68 +334,116 @@ train_kernel(KernelArgs A)
                 const uint32_t pe = i0 + lane + W + 1;
                 if (pe < n_prod) my_enter = (uint32_t)kw[pe & (FCAP - 1)];
                 uint32_t *pk = cb_pack + (size_t)lane * N;
-                for (uint32_t k = 0; k < N; ++k) pk[k] = (uint32_t)A.table[negative_slot(base, k, A.table_size)];
                 my_plain = 1u;
-                // multiplicity: 0 for a negative equal to the target and for repeats of an earlier
-                // negative, otherwise the number of times the id was drawn
-                for (uint32_t k = 0; k < N; ++k) {
-                    const uint32_t id = pk[k] & kIdMask;
-                    uint32_t m = (id == (uint32_t)my_w) ? 0u : 1u;
-                    for (uint32_t k1 = 0; k1 < k && m; ++k1) if ((pk[k1] & kIdMask) == id) m = 0u;
-                    if (m) for (uint32_t k2 = k + 1; k2 < N; ++k2) if ((pk[k2] & kIdMask) == id) ++m;
-                    pk[k] = id | (m << kIdBits);
-                    if (m != 1u) my_plain = 0u;
+                if constexpr (NREG) {
+#pragma unroll
+                    for (int k = 0; k < KC - 1; ++k) {
+                        nid[k] = kIdMask + 1u + (uint32_t)k;
+                        if (KEXACT || (uint32_t)k < N) nid[k] = (uint32_t)A.table[negative_slot(base, (uint32_t)k, A.table_size)];
+                    }
+#pragma unroll
+                    for (int k = 0; k < KC - 1; ++k) {
+                        bool first = nid[k] != (uint32_t)my_w;
+                        uint32_t m = 1u;
+#pragma unroll
+                        for (int k1 = 0; k1 < k; ++k1) first = first && nid[k1] != nid[k];
+#pragma unroll
+                        for (int k2 = k + 1; k2 < KC - 1; ++k2) m += (nid[k2] == nid[k]) ? 1u : 0u;
+                        nmult[k] = first ? m : 0u;
+                        if (KEXACT || (uint32_t)k < N) {
+                            pk[k] = nid[k] | (nmult[k] << kIdBits);
+                            if (nmult[k] != 1u) my_plain = 0u;
+                        }
+                    }
+                } else {
+                    for (uint32_t k = 0; k < N; ++k) pk[k] = (uint32_t)A.table[negative_slot(base, k, A.table_size)];
+                    for (uint32_t k = 0; k < N; ++k) {
+                        const uint32_t id = pk[k] & kIdMask;
+                        uint32_t m = (id == (uint32_t)my_w) ? 0u : 1u;
+                        for (uint32_t k1 = 0; k1 < k && m; ++k1) if ((pk[k1] & kIdMask) == id) m = 0u;
+                        if (m) for (uint32_t k2 = k + 1; k2 < N; ++k2) if ((pk[k2] & kIdMask) == id) ++m;
+                        pk[k] = id | (m << kIdBits);
+                        if (m != 1u) my_plain = 0u;
+                    }
                 }
             }
             __syncthreads();
-            if ((uint32_t)lane < nwin) {
+            if (have) {
                 // which of my first KC output rows does the previous window also write?
                 uint32_t reload = 0;
                 if (lane > 0) {
                     const uint32_t pw = (uint32_t)kw[(i0 + lane - 1) & (FCAP - 1)];
-                    const uint32_t *mine = cb_pack + (size_t)lane * N;
                     const uint32_t *prev = cb_pack + (size_t)(lane - 1) * N;
-                    for (uint32_t kk = 0; kk < (uint32_t)KC && kk <= N; ++kk) {
-                        uint32_t id;
-                        if (kk == 0) id = (uint32_t)my_w;
-                        else { const uint32_t p = mine[kk - 1]; if ((p >> kIdBits) == 0) continue; id = p & kIdMask; }
-                        bool hit = id == pw;
-                        for (uint32_t k = 0; k < N && !hit; ++k) hit = (prev[k] >> kIdBits) != 0 && (prev[k] & kIdMask) == id;
-                        if (hit) reload |= 1u << kk;
+                    if constexpr (NREG) {
+                        uint32_t pid[KC];           // rows the previous window writes (others: an id no word has)
+                        pid[0] = pw;
+#pragma unroll
+                        for (int k = 0; k < KC - 1; ++k) {
+                            uint32_t pv = 0u;
+                            if (KEXACT || (uint32_t)k < N) pv = prev[k];
+                            pid[k + 1] = (pv >> kIdBits) ? (pv & kIdMask) : 0xFFFFFFFFu;
+                        }
+#pragma unroll
+                        for (int kk = 0; kk < KC; ++kk) {
+                            const uint32_t id = kk ? nid[kk - 1] : (uint32_t)my_w;
+                            bool hit = false;
+#pragma unroll
+                            for (int k = 0; k < KC; ++k) hit = hit || pid[k] == id;
+                            if (kk && nmult[kk - 1] == 0u) hit = false;
+                            if (hit) reload |= 1u << kk;
+                        }
+                    } else {
+                        const uint32_t *mine = cb_pack + (size_t)lane * N;
+                        for (uint32_t kk = 0; kk < (uint32_t)KC && kk <= N; ++kk) {
+                            uint32_t id;
+                            if (kk == 0) id = (uint32_t)my_w;
+                            else { const uint32_t p = mine[kk - 1]; if ((p >> kIdBits) == 0) continue; id = p & kIdMask; }
+                            bool hit = id == pw;
+                            for (uint32_t k = 0; k < N && !hit; ++k) hit = (prev[k] >> kIdBits) != 0 && (prev[k] & kIdMask) == id;
+                            if (hit) reload |= 1u << kk;
+                        }
                     }
                 }
                 // Context slots of my window (slot c <-> distance (c>>1)+1, right side if c is odd) get a 4-bit
                 // weight: 0 for a slot whose position does not exist, 0 for a slot whose word comes again in a
                 // later slot (dupmask), and for the last slot of a word the number of slots that hold it.  Slots
                 // of one word share one ring row and one set of dot products, so the last one stands for all.
-                uint32_t dupmask = 0, special = 0, overflow = 0;
-                {
-                    const uint32_t me = i0 + lane;
-                    uint32_t *cm = cb_cm + 4 * lane;
-                    cm[0] = cm[1] = cm[2] = cm[3] = 0u;
-                    auto slot_pos = [&](uint32_t c, uint32_t &p) -> bool {     // position of slot c, false if absent
-                        const uint32_t a = (c >> 1) + 1u;
-                        if (c & 1u) { p = me + a; return p < n_prod; }
-                        p = me - a;
-                        return me >= a;
-                    };
-                    for (uint32_t c = 0; c < 2u * my_b; ++c) {
-                        uint32_t p, p2;
-                        if (!slot_pos(c, p)) { special = 1u; continue; }
-                        const int32_t w1 = kw[p & (FCAP - 1)];
-                        bool later = false;
-                        for (uint32_t c2 = c + 1; c2 < 2u * my_b && !later; ++c2)
-                            later = slot_pos(c2, p2) && kw[p2 & (FCAP - 1)] == w1;
-                        if (later) { dupmask |= 1u << c; special = 1u; continue; }
-                        uint32_t m = 1u;
-                        for (uint32_t c2 = 0; c2 < c; ++c2)
-                            if (slot_pos(c2, p2) && kw[p2 & (FCAP - 1)] == w1) ++m;
-                        if (m > 1u) special = 1u;
-                        if (m > 15u) overflow = 1u;
-                        cm[c >> 3] |= (m & 15u) << (4u * (c & 7u));
-                    }
-                    if (overflow) dupmask = 0u;      // pathological repetition: every slot stays on, rows are added to atomically
+                // The words of all slots are fetched once; a slot outside the width or the sentence gets a
+                // value of its own that no word has, so the unrolled comparisons need no further tests.
+                const uint32_t me = i0 + lane;
+                int32_t sw[NCTX];
+                uint32_t exist = 0;
+#pragma unroll
+                for (int c = 0; c < NCTX; ++c) {
+                    const uint32_t a = (uint32_t)(c >> 1) + 1u;
+                    const uint32_t p = (c & 1) ? me + a : me - a;
+                    const bool ok = a <= my_b && ((c & 1) ? p < n_prod : me >= a);
+                    sw[c] = -2 - c;
+                    if (ok) { sw[c] = kw[p & (FCAP - 1)]; exist |= 1u << c; }
                 }
+                uint32_t dupmask = 0, overflow = 0;
+                uint32_t cm[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int c = 0; c < NCTX; ++c) {
+                    bool later = false;
+                    uint32_t m = 1u;
+#pragma unroll
+                    for (int c2 = c + 1; c2 < NCTX; ++c2) later = later || sw[c2] == sw[c];
+#pragma unroll
+                    for (int c2 = 0; c2 < c; ++c2) m += (sw[c2] == sw[c]) ? 1u : 0u;
+                    if ((exist >> c) & 1u) {
+                        if (later) dupmask |= 1u << c;
+                        else {
+                            if (m > 15u) overflow = 1u;
+                            cm[c >> 3] |= (m & 15u) << (4 * (c & 7));
+                        }
+                    }
+                }
+                // special: some slot inside the width is absent, or two slots hold one word
+                const uint32_t inside = (my_b >= 16u) ? 0xFFFFFFFFu : ((1u << (2u * my_b)) - 1u);
+                const uint32_t special = (exist != inside || dupmask != 0u) ? 1u : 0u;
+                if (overflow) dupmask = 0u;      // pathological repetition: every slot stays on, rows are added to atomically
+                reinterpret_cast<uint4 *>(cb_cm)[lane] = make_uint4(cm[0], cm[1], cm[2], cm[3]);
                 cb_meta[lane] = make_uint4(my_b | (reload << 8) | (overflow << 16) | (my_plain << 17) | (special << 18),
                                            (uint32_t)my_w, my_enter, dupmask);
             }
