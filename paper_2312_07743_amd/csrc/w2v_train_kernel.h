@@ -17,6 +17,7 @@
 #include "w2v_rng.h"
 
 #include <type_traits>
+#include <utility>
 
 namespace w2v {
 namespace {
@@ -48,6 +49,51 @@ __device__ __forceinline__ float dpp_move(float v)
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
 }
 constexpr int kDppRowRor8 = 0x128, kDppHalfMirror = 0x141, kDppQuadXor2 = 0x4E, kDppQuadXor1 = 0xB1;
+
+// Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>).
+template <class F, int... Is>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, Is...>)
+{
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f) { static_for_impl(f, std::make_integer_sequence<int, N>{}); }
+
+// Broadcast of per-lane results to every lane without going through scalar registers.
+// rows_to_all: G[r] gets lanes 16r .. 16r+15 of g in each of its four rows of 16 lanes (r < ROWS).
+// mul_row_lane<S>(G, o) = o * G[lane S of the caller's row], fma_row_lane adds that product to acc: the
+// multiplier comes through the row-broadcast DPP operand, so it costs no instruction of its own.
+// The compiler does not see that these instructions read G across lanes, so rows_to_all ends with the two
+// wait states a DPP read of a freshly written register needs.  All 64 lanes must be active.
+template <int ROWS>
+__device__ __forceinline__ void rows_to_all(float g, float (&G)[4])
+{
+    static_assert(ROWS >= 1 && ROWS <= 4, "a wavefront has four rows");
+    const uint32_t u = __float_as_uint(g);
+    const auto h = __builtin_amdgcn_permlane32_swap(u, u, false, false);      // [r0 r1 r0 r1], [r2 r3 r2 r3]
+    const auto lo = __builtin_amdgcn_permlane16_swap(h[0], h[0], false, false);
+    G[0] = __uint_as_float(lo[0]);
+    G[1] = __uint_as_float(lo[1]);
+    G[2] = G[3] = 0.0f;
+    if constexpr (ROWS > 2) {
+        const auto hi = __builtin_amdgcn_permlane16_swap(h[1], h[1], false, false);
+        G[2] = __uint_as_float(hi[0]);
+        G[3] = __uint_as_float(hi[1]);
+    }
+    asm volatile("s_nop 1" : "+v"(G[0]), "+v"(G[1]), "+v"(G[2]), "+v"(G[3]));
+}
+template <int S>
+__device__ __forceinline__ float mul_row_lane(float G, float o)
+{
+    float r;
+    asm("v_mul_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(G), "v"(o), "n"(S));
+    return r;
+}
+template <int S>
+__device__ __forceinline__ void fma_row_lane(float &acc, float G, float o)
+{
+    asm("v_fmac_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(G), "v"(o), "n"(S));
+}
 
 // Transposing reduction: sums each of M per-lane values over the 64 lanes; lane v (v < M) returns
 // the total of value v.  Stage B (32, 16, .., 1) pairs register i with register i+B: lanes with bit B
@@ -583,12 +629,12 @@ train_kernel(KernelArgs A)
 #pragma unroll
                             for (int x = 0; x < E; ++x) dO[kk][x] = 0.0f;
 
-#pragma unroll
-                        for (int q = 0; q < NQW; ++q) {
+                        static_for<NQW>([&](auto q_tag) {
                             // NC context rows (slots C0 .. C0+NC-1) against the KC output rows
-                            const int NC = (q < REM) ? BASE + 1 : BASE;
-                            const int C0 = q * BASE + (q < REM ? q : REM);
-                            if (MASKED && !(amask >> C0)) break;
+                            constexpr int q = decltype(q_tag)::value;
+                            constexpr int NC = (q < REM) ? BASE + 1 : BASE;
+                            constexpr int C0 = q * BASE + (q < REM ? q : REM);
+                            if (MASKED && !(amask >> C0)) return;       // no slot from here on takes part
                             float acc[CC * KC];
 #pragma unroll
                             for (int cc = 0; cc < CC; ++cc) {
@@ -625,22 +671,37 @@ train_kernel(KernelArgs A)
                                 const float l1 = __builtin_fmaf(__builtin_amdgcn_logf(u), 0.693147180559945309f, (gk == 0) ? 0.0f : xv);
                                 loss_acc += (double)(GENERAL ? mult_lane * cmult * l1 : cmult * l1);
                             }
-#pragma unroll
-                            for (int cc = 0; cc < CC; ++cc) {
-                                const int c = C0 + cc;
+                            // every lane needs every g: straight-line windows take it through the row-broadcast
+                            // operand of the multiply-adds, the general path through scalar registers
+                            float G[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                            if constexpr (!MASKED) rows_to_all<(NC * KC + 15) / 16>(g, G);
+                            static_for<CC>([&](auto cc_tag) {
+                                constexpr int cc = decltype(cc_tag)::value;
+                                constexpr int c = C0 + cc;
                                 if (cc < NC && (!MASKED || ((amask >> c) & 1u))) {
                                     float dI[E];
 #pragma unroll
                                     for (int x = 0; x < E; ++x) dI[x] = 0.0f;
+                                    static_for<KC>([&](auto kk_tag) {
+                                        constexpr int kk = decltype(kk_tag)::value;
+                                        constexpr int v = cc * KC + kk;         // lane that holds this pairing's g
+                                        if constexpr (!MASKED) {
 #pragma unroll
-                                    for (int kk = 0; kk < KC; ++kk) {
-                                        const float gs = lane_value(g, (uint32_t)(cc * KC + kk));
+                                            for (int x = 0; x < E; ++x) {
+                                                if (kk == 0) dI[x] = mul_row_lane<v % 16>(G[v / 16], O[kk][x]);
+                                                else fma_row_lane<v % 16>(dI[x], G[v / 16], O[kk][x]);
+                                                if (q == 0 && cc == 0) dO[kk][x] = mul_row_lane<v % 16>(G[v / 16], I[c][x]);
+                                                else fma_row_lane<v % 16>(dO[kk][x], G[v / 16], I[c][x]);
+                                            }
+                                        } else {
+                                            const float gs = lane_value(g, (uint32_t)v);
 #pragma unroll
-                                        for (int x = 0; x < E; ++x) {
-                                            dI[x] = __builtin_fmaf(gs, O[kk][x], dI[x]);
-                                            dO[kk][x] = __builtin_fmaf(gs, I[c][x], dO[kk][x]);
+                                            for (int x = 0; x < E; ++x) {
+                                                dI[x] = __builtin_fmaf(gs, O[kk][x], dI[x]);
+                                                dO[kk][x] = __builtin_fmaf(gs, I[c][x], dO[kk][x]);
+                                            }
                                         }
-                                    }
+                                    });
                                     float *dst = ring + (size_t)cslot[c] * ROWF;
                                     if (GENERAL && shared_rows) {
                                         // positions that share a ring row add up (LDS float add)
@@ -671,8 +732,8 @@ train_kernel(KernelArgs A)
                                         }
                                     }
                                 }
-                            }
-                        }
+                            });
+                        });
 
                         // (f) output rows go back (lock-free) once per window
 #pragma unroll
