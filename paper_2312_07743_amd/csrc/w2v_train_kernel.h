@@ -678,7 +678,7 @@ train_kernel(KernelArgs A)
                             static_for<CC>([&](auto cc_tag) {
                                 constexpr int cc = decltype(cc_tag)::value;
                                 constexpr int c = C0 + cc;
-                                if (cc < NC && (!MASKED || ((amask >> c) & 1u))) {
+                                if constexpr (cc < NC) if (!MASKED || ((amask >> c) & 1u)) {
                                     float dI[E];
 #pragma unroll
                                     for (int x = 0; x < E; ++x) dI[x] = 0.0f;
