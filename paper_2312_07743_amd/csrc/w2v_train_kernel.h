@@ -217,10 +217,13 @@ constexpr uint32_t kNoWord = 0xFFFFFFFFu;
 // KMODE: how the N + 1 output rows of a window relate to the KC rows handled at a time:
 //   0: fewer than KC rows, 1: exactly KC rows (every row-exists test folds away), 2: more than KC rows
 // wavefronts per SIMD the register allocator is asked to make room for (512 VGPRs per lane in all)
+#ifndef W2V_OCC_SMALL_WCAP
+#define W2V_OCC_SMALL_WCAP 10
+#endif
 #ifndef W2V_OCC_SMALL
 #define W2V_OCC_SMALL 3
 #endif
-constexpr int occupancy_goal(int e, int wcap) { return (e <= 2 && wcap <= 5) ? W2V_OCC_SMALL : ((e * wcap <= 25) ? 2 : 1); }
+constexpr int occupancy_goal(int e, int wcap) { return (e <= 2 && wcap <= W2V_OCC_SMALL_WCAP) ? W2V_OCC_SMALL : ((e * wcap <= 25) ? 2 : 1); }
 
 template <int VW, int R, int WCAP, bool FULL, int KMODE>
 __global__ void __launch_bounds__(kLanes) __attribute__((amdgpu_waves_per_eu(occupancy_goal(VW * R, WCAP))))
@@ -590,10 +593,16 @@ train_kernel(KernelArgs A)
                     // the NCW slots are handled in NQW blocks of nearly equal size (BASE or BASE+1 slots)
                     constexpr int NQW = (NCW + CC - 1) / CC;
                     constexpr int BASE = NCW / NQW, REM = NCW % NQW;
+                    // Straight-line windows whose output rows are handled in one pass take the context rows out of
+                    // the ring block by block (fewer rows live at a time): no two slots that take part share a row,
+                    // so a block never sees an earlier block's update.  Otherwise (several passes, or rows that
+                    // are added to by several slots) every dot product needs the rows as they were when the
+                    // window began, and all of them are fetched first.
+                    constexpr bool LOAD_PER_BLOCK = !MULTI && !MASKED && NQW > 1;
                     float I[NCW][E];
                     uint32_t cslot[NCW];
-#pragma unroll
-                    for (int c = 0; c < NCW; ++c) {
+                    auto fetch_slot = [&](auto c_tag) {
+                        constexpr int c = decltype(c_tag)::value;
                         cslot[c] = 0;
 #pragma unroll
                         for (int x = 0; x < E; ++x) I[c][x] = 0.0f;
@@ -606,7 +615,8 @@ train_kernel(KernelArgs A)
 #pragma unroll
                             for (int r = 0; r < R; ++r) load_vec<VW>(src + eoff[r], &I[c][r * VW]);
                         }
-                    }
+                    };
+                    if constexpr (!LOAD_PER_BLOCK) static_for<NCW>(fetch_slot);
                     for (uint32_t kb = 0; kb <= (MULTI ? N : 0u); kb += KC) {
                         const uint32_t gk = kb + lane_k;
                         uint32_t pv = packv;
@@ -635,6 +645,8 @@ train_kernel(KernelArgs A)
                             constexpr int NC = (q < REM) ? BASE + 1 : BASE;
                             constexpr int C0 = q * BASE + (q < REM ? q : REM);
                             if (MASKED && !(amask >> C0)) return;       // no slot from here on takes part
+                            if constexpr (LOAD_PER_BLOCK)
+                                static_for<NC>([&](auto cc_tag) { fetch_slot(std::integral_constant<int, C0 + decltype(cc_tag)::value>{}); });
                             float acc[CC * KC];
 #pragma unroll
                             for (int cc = 0; cc < CC; ++cc) {
