@@ -109,6 +109,19 @@ def main():
             if line.startswith("hbm_bytes_per_launch:"):
                 traffic = float(line.split(":")[1])
 
+    # what a plain streaming copy reaches on this machine (1 GiB read + 1 GiB written per pass), for scale
+    a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+    b = torch.empty_like(a)
+    b.copy_(a)
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(5):
+        b.copy_(a)
+    c1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2 * a.numel() * 4 / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    del a, b
+
     out = {
         "metric": "trained words/sec on 1 MI355X; achieved HBM GB/s vs peak",
         "value": words / wall, "unit": "words/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -122,7 +135,8 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "kernel": "naive_kernel" if args.naive else "train_kernel", "avg_launch_ms": avg_kernel_s * 1e3,
-                     "algorithmic_bytes_per_launch": algo_bytes_per_launch},
+                     "algorithmic_bytes_per_launch": algo_bytes_per_launch,
+                     "streaming_copy_GBs_same_box": copy_gbs},
     }
 
     if not args.no_cpu_baseline:
