@@ -38,6 +38,8 @@ def main():
     ap.add_argument("--workload", default="mid", choices=sorted(WORKLOADS))
     ap.add_argument("--dim", type=int, default=None, help="override d (dimension sweep)")
     ap.add_argument("--in-flight", type=int, default=0, help="sentences_in_flight (0 = fill the GPU)")
+    ap.add_argument("--fixed-width", action="store_true",
+                    help="window_mode 1: every window has width ceil(W/2) (the paper's own variant, Section 3.2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--naive", action="store_true",
                     help="time the no-reuse comparator kernel instead of the window kernel (traffic comparison only)")
@@ -75,7 +77,7 @@ def main():
     E = args.warmup + args.steps
     tr = Trainer(vocab=corpus.vocab, dim=dim, window=window, negatives=negatives, counts=corpus.counts,
                  tokens_per_epoch=corpus.n_tokens, seed=2024, table_size=table_size, subsample_t=t_sub,
-                 total_epochs=E, sentences_in_flight=args.in_flight)
+                 total_epochs=E, sentences_in_flight=args.in_flight, window_mode=1 if args.fixed_width else 0)
     tr.set_corpus(corpus.tokens, corpus.sent_off)
     for e in range(args.warmup):
         tr.train_epoch(e, naive=args.naive)
@@ -129,7 +131,8 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}: vocab {corpus.vocab} {what}, "
                                f"{corpus.n_tokens} tokens in {corpus.n_sent} sentences, d={dim}, W={window}, "
-                               f"N={negatives}, subsample t={t_sub}, lr 0.025 linear decay",
+                               f"N={negatives}, subsample t={t_sub}, lr 0.025 linear decay"
+                               + (", fixed width ceil(W/2)" if args.fixed_width else ""),
                    "kept_words_per_s": kept / wall, "kept_fraction": kept / words,
                    "mean_loss": loss_sum / max(pairs, 1), "sentences_in_flight": args.in_flight},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -146,7 +149,8 @@ def main():
         syn0, syn1 = orc.init_weights(2024, corpus.vocab, dim)
         c0 = time.perf_counter()
         orc.train_epoch(syn0, syn1, corpus.counts, corpus.tokens, corpus.sent_off, window=window, negatives=negatives,
-                        seed=2024, epoch=0, total_epochs=E, table_size=table_size, subsample_t=t_sub, s_end=ns)
+                        seed=2024, epoch=0, total_epochs=E, table_size=table_size, subsample_t=t_sub, s_end=ns,
+                        window_mode=1 if args.fixed_width else 0)
         cdt = time.perf_counter() - c0
         out["cpu_baseline"] = {"value": int(corpus.sent_off[ns]) / cdt, "unit": "words/s", "cores": 1,
                                "kind": "oracle",

@@ -70,7 +70,8 @@ std::string check_config(const w2v_config *c)
     if (((uintptr_t)c->workspace & 255u) != 0) return "cfg.workspace must be 256-byte aligned";
     w2v::RowShape s;
     if (!w2v::pick_row_shape(c->dim, c->ld, &s)) return "cfg.dim: no lane layout for this dimension";
-    if ((uint32_t)(64 * s.vw * s.r) * c->window > 512u * 10u)
+    const uint32_t span = c->window_mode ? (c->window + 1u) / 2u : c->window;      // widest window that occurs
+    if ((uint32_t)(64 * s.vw * s.r) * span > 512u * 10u)
         return "cfg.dim * cfg.window too large (rows of more than 320 floats need window <= 10)";
     return std::string();
 }
@@ -99,9 +100,10 @@ w2v::KernelArgs kernel_args(const w2v_ctx *ctx, const int32_t *tokens, const uin
     a.vocab = c.vocab;
     a.dim = c.dim;
     a.ld = c.ld;
-    a.window = c.window;
+    // fixed width ceil(W/2): the kernels see that width as their window, so the ring holds 2*ceil(W/2)+2 rows
+    a.window = c.window_mode ? (c.window + 1u) / 2u : c.window;
     a.negatives = c.negatives;
-    a.window_mode = c.window_mode;
+    a.window_mode = c.window_mode ? 2u : 0u;
     a.table_size = ctx->table_size;
     a.subsample = c.subsample_t > 0.0 ? 1u : 0u;
     return a;

@@ -41,10 +41,11 @@ W2V_HD bool keep_decision(uint64_t base, uint32_t threshold)
     return threshold == 0xFFFFFFFFu || draw_u32(base, 0) < threshold;
 }
 
-// window width: uniform on 1..W (mode 0) or ceil(W/2) (mode 1)
+// window width: uniform on 1..W (mode 0), ceil(W/2) (mode 1), or W itself (mode 2: the caller has already
+// replaced W by the fixed width)
 W2V_HD uint32_t window_width(uint64_t base, uint32_t W, uint32_t mode)
 {
-    return mode ? (W + 1u) / 2u : 1u + mul_hi_u32(draw_u32(base, 1), W);
+    return mode == 2u ? W : (mode == 1u ? (W + 1u) / 2u : 1u + mul_hi_u32(draw_u32(base, 1), W));
 }
 
 // slot of the sampling table that negative k of this position reads

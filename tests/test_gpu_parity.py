@@ -95,6 +95,28 @@ def test_window_and_negative_ranges(orc32, window, negatives, mode):
     _parity(orc32, c, dim=128, window=window, negatives=negatives, seed=8, window_mode=mode, table_size=50021)
 
 
+def test_large_like_hyperparameters(orc32):
+    """configs[3] in small: Zipf(1.1), d=300 (rows padded to 320 floats), W=5, N=10 (two batches of output rows
+    per window), heavy subsampling."""
+    c = synth.zipf_corpus(5000, 1.1, 60, 1000, seed=31)
+    _parity(orc32, c, dim=300, window=5, negatives=10, seed=17, subsample_t=1e-5, table_size=1 << 20)
+    _parity(orc32, c, dim=300, window=5, negatives=10, seed=17, subsample_t=1e-3, table_size=1 << 20)
+
+
+def test_graph_like_hyperparameters(orc32):
+    """configs[4] in small: uniform walks of 80 on a Barabasi-Albert graph (ids not sorted by frequency, walks
+    revisit nodes), d=128, W=10, N=5, no subsampling."""
+    c = synth.barabasi_albert_walks(n_nodes=3000, m=5, walks_per_node=1, walk_len=80, seed=4)
+    _parity(orc32, c, dim=128, window=10, negatives=5, seed=23, table_size=1 << 18)
+    _parity(orc32, c, dim=128, window=10, negatives=5, seed=23, table_size=1 << 18, window_mode=1)
+
+
+def test_fixed_width_sizes_the_ring_by_the_fixed_width(orc32):
+    # W=16 with rows of 512 floats is only possible because the widest window is ceil(16/2) = 8
+    c = synth.zipf_corpus(300, 1.0, 5, 200, seed=12)
+    _parity(orc32, c, dim=512, window=16, negatives=4, seed=5, window_mode=1, table_size=50021)
+
+
 def test_degenerate_sentences(orc32):
     # empty sentences, one-word sentences, sentences of invalid ids only, a long sentence (> one FIFO refill)
     rng = np.random.default_rng(3)
