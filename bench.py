@@ -40,6 +40,9 @@ def main():
     ap.add_argument("--in-flight", type=int, default=0, help="sentences_in_flight (0 = fill the GPU)")
     ap.add_argument("--fixed-width", action="store_true",
                     help="window_mode 1: every window has width ceil(W/2) (the paper's own variant, Section 3.2)")
+    ap.add_argument("--from-host", action="store_true",
+                    help="feed the corpus from pinned host memory through w2v_train_epoch_host (PCIe-inclusive rate)")
+    ap.add_argument("--staging-mb", type=int, default=32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--naive", action="store_true",
                     help="time the no-reuse comparator kernel instead of the window kernel (traffic comparison only)")
@@ -79,8 +82,17 @@ def main():
                  tokens_per_epoch=corpus.n_tokens, seed=2024, table_size=table_size, subsample_t=t_sub,
                  total_epochs=E, sentences_in_flight=args.in_flight, window_mode=1 if args.fixed_width else 0)
     tr.set_corpus(corpus.tokens, corpus.sent_off)
+    if args.from_host:
+        t_pin = torch.as_tensor(corpus.tokens).pin_memory()
+        o_pin = torch.as_tensor(corpus.sent_off.view(np.int64)).pin_memory()
+
+        def run_epoch(e):
+            tr.train_epoch_from_host(t_pin, o_pin, epoch=e, staging_bytes=args.staging_mb << 20)
+    else:
+        def run_epoch(e):
+            tr.train_epoch(e, naive=args.naive)
     for e in range(args.warmup):
-        tr.train_epoch(e, naive=args.naive)
+        run_epoch(e)
     torch.cuda.synchronize()
     tr.loss(reset=True)
 
@@ -90,7 +102,7 @@ def main():
     t0 = time.perf_counter()
     for k in range(args.steps):
         starts[k].record()                       # torch's current stream is the one the library launches on
-        tr.train_epoch(args.warmup + k, naive=args.naive)
+        run_epoch(args.warmup + k)
         stops[k].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -132,7 +144,9 @@ def main():
         "config": {"workload": f"{args.workload}: vocab {corpus.vocab} {what}, "
                                f"{corpus.n_tokens} tokens in {corpus.n_sent} sentences, d={dim}, W={window}, "
                                f"N={negatives}, subsample t={t_sub}, lr 0.025 linear decay"
-                               + (", fixed width ceil(W/2)" if args.fixed_width else ""),
+                               + (", fixed width ceil(W/2)" if args.fixed_width else "")
+                               + (f", corpus fed from pinned host memory in batches of {args.staging_mb // 2} MiB"
+                                  if args.from_host else ""),
                    "kept_words_per_s": kept / wall, "kept_fraction": kept / words,
                    "mean_loss": loss_sum / max(pairs, 1), "sentences_in_flight": args.in_flight},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -99,6 +99,21 @@ int w2v_build_unigram_table(w2v_ctx *ctx, const uint64_t *counts_host, uint32_t 
 int w2v_train_epoch(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_t *sent_off_dev,
                     uint64_t n_sent, uint64_t first_token_global_pos, uint32_t epoch);
 
+/* The same pass for a corpus that lives in host memory (the batching pipeline of Sec. 4.1 without
+ * the CPU-side sampling: only word ids cross the bus).  tokens_host / sent_off_host: host arrays
+ * laid out as for w2v_train_epoch.  The sentences are cut into batches that fit one half of
+ * staging_dev (caller-owned device memory, staging_bytes >= 2 * (room for the longest sentence),
+ * 256-byte aligned); while one half is trained on, the other is filled over a copy stream the
+ * context owns, so transfers hide behind the kernel.  Every random draw and the learning rate are
+ * keyed by global token positions, so the result equals that of w2v_train_epoch on a resident copy
+ * (bit for bit with sentences_in_flight = 1).  Returns when the last batch has been queued on the
+ * context's stream: the host arrays must stay valid until that stream has been synchronised (pinned
+ * host memory gives truly asynchronous copies, pageable memory works and blocks this call while
+ * each batch is staged).  W2V_EINVAL if a sentence does not fit half of the staging buffer. */
+int w2v_train_epoch_host(w2v_ctx *ctx, const int32_t *tokens_host, const uint64_t *sent_off_host,
+                         uint64_t n_sent, uint64_t first_token_global_pos, uint32_t epoch,
+                         void *staging_dev, uint64_t staging_bytes);
+
 /* Same arithmetic without any on-chip reuse: every (target, context) pairing re-reads and
  * re-writes its context row, and the window's N+1 output rows go through global memory per
  * context word.  Exists only as the memory-traffic comparator for w2v_train_epoch (the role
@@ -127,6 +142,13 @@ int w2v_counters(w2v_ctx *ctx, uint64_t *kept_tokens, uint64_t *invalid_tokens, 
 int w2v_debug_draws(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_t *sent_off_dev,
                     uint64_t n_sent, uint64_t first_token_global_pos, uint32_t epoch,
                     uint8_t *keep_dev, uint8_t *width_dev, int32_t *neg_dev);
+
+/* Test surface: fixes the granularity of the work queue.  w2v_train_epoch hands a sentence out as
+ * 2^unit_shift stretches of its tokens (each reads the W kept tokens on either side as context
+ * only, so the windows are those of the whole sentence); by default the library picks the
+ * exponent from the sizes of the call (0 when one wavefront runs alone).  unit_shift in [0, 6]
+ * fixes it, -1 restores the default. */
+int w2v_debug_set_units(w2v_ctx *ctx, int unit_shift);
 
 /* Test surface: runs the window kernel's cross-lane reduction on its own.  in_dev: device
  * float[60*64], value m of lane l at in_dev[m*64 + l]; out_dev: device float[64], out_dev[l] =

@@ -14,8 +14,8 @@ W2V_OK, W2V_EINVAL, W2V_ESTATE, W2V_ENOMEM, W2V_EHIP = 0, -1, -2, -3, -4
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libw2v.so")
 EXPORTS = ["w2v_query_ld", "w2v_query_workspace", "w2v_create", "w2v_destroy", "w2v_build_unigram_table",
-           "w2v_train_epoch", "w2v_train_epoch_naive", "w2v_get_embeddings", "w2v_loss", "w2v_counters", "w2v_debug_draws",
-           "w2v_debug_reduce", "w2v_last_error"]
+           "w2v_train_epoch", "w2v_train_epoch_host", "w2v_train_epoch_naive", "w2v_get_embeddings", "w2v_loss", "w2v_counters", "w2v_debug_draws",
+           "w2v_debug_set_units", "w2v_debug_reduce", "w2v_last_error"]
 
 
 class W2VConfig(C.Structure):
@@ -52,11 +52,13 @@ def lib():
         L.w2v_build_unigram_table.argtypes = [vp, vp, u32]
         L.w2v_train_epoch.argtypes = [vp, vp, vp, u64, u64, u32]
         L.w2v_train_epoch_naive.argtypes = [vp, vp, vp, u64, u64, u32]
+        L.w2v_train_epoch_host.argtypes = [vp, vp, vp, u64, u64, u32, vp, u64]
         L.w2v_get_embeddings.argtypes = [vp, i32, vp, u64, i32]
         L.w2v_loss.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(u64), i32]
         L.w2v_counters.argtypes = [vp, C.POINTER(u64), C.POINTER(u64), i32]
         L.w2v_debug_draws.argtypes = [vp, vp, vp, u64, u64, u32, vp, vp, vp]
         L.w2v_debug_reduce.argtypes = [vp, vp, vp]
+        L.w2v_debug_set_units.argtypes = [vp, i32]
         L.w2v_last_error.argtypes = [vp]
         L.w2v_last_error.restype = C.c_char_p
         for n in EXPORTS:
@@ -128,9 +130,19 @@ def w2v_train_epoch(ctx, tokens_dev, sent_off_dev, n_sent, first_token_global_po
     _check(lib().w2v_train_epoch(ctx, _ptr(tokens_dev), _ptr(sent_off_dev), n_sent, first_token_global_pos, epoch), ctx)
 
 
+def w2v_train_epoch_host(ctx, tokens_host, sent_off_host, n_sent, first_token_global_pos, epoch, staging_dev,
+                         staging_bytes):
+    _check(lib().w2v_train_epoch_host(ctx, _ptr(tokens_host), _ptr(sent_off_host), n_sent, first_token_global_pos,
+                                      epoch, _ptr(staging_dev), staging_bytes), ctx)
+
+
 def w2v_train_epoch_naive(ctx, tokens_dev, sent_off_dev, n_sent, first_token_global_pos=0, epoch=0):
     _check(lib().w2v_train_epoch_naive(ctx, _ptr(tokens_dev), _ptr(sent_off_dev), n_sent, first_token_global_pos,
                                        epoch), ctx)
+
+
+def w2v_debug_set_units(ctx, unit_shift):
+    _check(lib().w2v_debug_set_units(ctx, int(unit_shift)), ctx)
 
 
 def w2v_get_embeddings(ctx, which, dst, dst_floats, dst_is_device):

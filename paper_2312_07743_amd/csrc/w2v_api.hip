@@ -1,6 +1,6 @@
 // Host side of the C ABI declared in include/w2v.h: argument validation, the host-built sampling
-// table and subsampling thresholds, kernel launches.  No device memory is allocated here: tables and
-// accumulators live in the caller's workspace.
+// table and subsampling thresholds, kernel launches, the host-fed batch loop.  No device memory is
+// allocated here: tables and accumulators live in the caller's workspace, staging in the caller's buffer.
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -106,6 +106,7 @@ w2v::KernelArgs kernel_args(const w2v_ctx *ctx, const int32_t *tokens, const uin
     a.window_mode = c.window_mode ? 2u : 0u;
     a.table_size = ctx->table_size;
     a.subsample = c.subsample_t > 0.0 ? 1u : 0u;
+    a.unit_shift = 0;
     return a;
 }
 
@@ -121,6 +122,19 @@ int check_train_call(w2v_ctx *ctx, const int32_t *tokens, const uint64_t *sent_o
 }
 
 hipStream_t stream_of(const w2v_ctx *ctx) { return static_cast<hipStream_t>(ctx->cfg.stream); }
+
+// Into how many units (a power of two, as its exponent) each sentence is cut for the work queue: enough units
+// that the wavefronts finish within a small fraction of the launch of one another (a wavefront holds a unit
+// until it is done), but units of at least 128 tokens on average, since every unit re-reads the few tokens
+// of context on either side.  One wavefront (strict order) gains nothing from a finer queue.
+uint32_t pick_unit_shift(const w2v_ctx *ctx, uint64_t n_sent, uint64_t n_tokens, uint64_t waves)
+{
+    uint32_t shift = 0;
+    if (ctx->forced_unit_shift >= 0) return (uint32_t)ctx->forced_unit_shift;
+    if (waves <= 1 || n_sent == 0) return 0;
+    while (shift < 3 && (n_sent << shift) < 16u * waves && (n_tokens / n_sent) >> (shift + 1) >= 128u) ++shift;
+    return shift;
+}
 
 }  // namespace
 
@@ -173,6 +187,14 @@ int w2v_destroy(w2v_ctx *ctx)
     if (!ctx) return W2V_EINVAL;
     int rc = W2V_OK;
     if (hipSetDevice(ctx->cfg.device) != hipSuccess || hipStreamSynchronize(stream_of(ctx)) != hipSuccess) rc = W2V_EHIP;
+    if (ctx->copy_stream) {
+        if (hipStreamSynchronize(ctx->copy_stream) != hipSuccess) rc = W2V_EHIP;
+        for (int h = 0; h < 2; ++h) {
+            if (ctx->filled[h]) (void)hipEventDestroy(ctx->filled[h]);
+            if (ctx->drained[h]) (void)hipEventDestroy(ctx->drained[h]);
+        }
+        (void)hipStreamDestroy(ctx->copy_stream);
+    }
     delete ctx;
     return rc;
 }
@@ -240,15 +262,78 @@ int w2v_train_epoch(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_t *sen
     if (rc != W2V_OK) return rc;
     if (n_sent == 0) return W2V_OK;
     HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
-    const w2v::KernelArgs a = kernel_args(ctx, tokens_dev, sent_off_dev, n_sent, first_token_global_pos, epoch);
+    w2v::KernelArgs a = kernel_args(ctx, tokens_dev, sent_off_dev, n_sent, first_token_global_pos, epoch);
     uint64_t waves = ctx->cfg.sentences_in_flight;
     if (waves == 0) {
         waves = w2v::train_resident_waves(a, ctx->cfg.device);
         if (waves == 0) return fail(ctx, W2V_EHIP, "could not query kernel occupancy");
     }
-    if (waves > n_sent) waves = n_sent;
+    // the token count of this call is on the device; the epoch's count stands in for it (a call that feeds
+    // part of an epoch gets units that are shorter than intended, never wrong)
+    a.unit_shift = pick_unit_shift(ctx, n_sent, ctx->cfg.tokens_per_epoch, waves);
+    if (waves > (n_sent << a.unit_shift)) waves = n_sent << a.unit_shift;
     HIP_TRY(ctx, w2v::launch_reset_accum(a.accum, 1, stream_of(ctx)));
     HIP_TRY(ctx, w2v::launch_train(a, (uint32_t)waves, stream_of(ctx)));
+    return W2V_OK;
+}
+
+int w2v_train_epoch_host(w2v_ctx *ctx, const int32_t *tokens_host, const uint64_t *sent_off_host, uint64_t n_sent,
+                         uint64_t first_token_global_pos, uint32_t epoch, void *staging_dev, uint64_t staging_bytes)
+{
+    const int rc = check_train_call(ctx, tokens_host, sent_off_host, n_sent, first_token_global_pos, epoch);
+    if (rc != W2V_OK) return rc;
+    if (!staging_dev || ((uintptr_t)staging_dev & 255u) != 0)
+        return fail(ctx, W2V_EINVAL, "staging_dev is NULL or not 256-byte aligned");
+    const uint64_t half = (staging_bytes / 2u) & ~(uint64_t)255u;
+    // a batch of n tokens in k sentences takes 4n bytes of ids, padding to 8, and 8(k+1) bytes of offsets
+    auto batch_bytes = [](uint64_t ntok, uint64_t nsent) { return ((4u * ntok + 7u) & ~(uint64_t)7u) + 8u * (nsent + 1u); };
+    for (uint64_t s = 0; s < n_sent; ++s) {
+        if (sent_off_host[s + 1] < sent_off_host[s]) return fail(ctx, W2V_EINVAL, "sent_off_host is not non-decreasing");
+        if (batch_bytes(sent_off_host[s + 1] - sent_off_host[s], 1) > half)
+            return fail(ctx, W2V_EINVAL, "a sentence does not fit half of the staging buffer");
+    }
+    if (n_sent == 0) return W2V_OK;
+    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    if (!ctx->copy_stream) {
+        HIP_TRY(ctx, hipStreamCreateWithFlags(&ctx->copy_stream, hipStreamNonBlocking));
+        for (int h = 0; h < 2; ++h) {
+            HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->filled[h], hipEventDisableTiming));
+            HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->drained[h], hipEventDisableTiming));
+        }
+    }
+    uint64_t s0 = 0;
+    for (uint64_t batch = 0; s0 < n_sent; ++batch) {
+        uint64_t s1 = s0 + 1;
+        while (s1 < n_sent && batch_bytes(sent_off_host[s1 + 1] - sent_off_host[s0], s1 + 1 - s0) <= half) ++s1;
+        const int h = (int)(batch & 1u);
+        const uint64_t t_begin = sent_off_host[s0], ntok = sent_off_host[s1] - t_begin, nsent = s1 - s0;
+        unsigned char *base = static_cast<unsigned char *>(staging_dev) + (uint64_t)h * half;
+        int32_t *tok_dev = reinterpret_cast<int32_t *>(base);
+        uint64_t *off_dev = reinterpret_cast<uint64_t *>(base + ((4u * ntok + 7u) & ~(uint64_t)7u));
+        // refill this half only after the batch that used it last (two steps ago, or in an earlier call) has
+        // been trained
+        if (ctx->drained_recorded[h]) HIP_TRY(ctx, hipStreamWaitEvent(ctx->copy_stream, ctx->drained[h], 0));
+        if (ntok) HIP_TRY(ctx, hipMemcpyAsync(tok_dev, tokens_host + t_begin, 4u * ntok, hipMemcpyHostToDevice, ctx->copy_stream));
+        HIP_TRY(ctx, hipMemcpyAsync(off_dev, sent_off_host + s0, 8u * (nsent + 1u), hipMemcpyHostToDevice, ctx->copy_stream));
+        HIP_TRY(ctx, hipEventRecord(ctx->filled[h], ctx->copy_stream));
+        HIP_TRY(ctx, hipStreamWaitEvent(stream_of(ctx), ctx->filled[h], 0));
+        // The offsets keep their values from the whole corpus; the token pointer is moved back by the
+        // batch's first offset instead, so positions (random keys, learning rate) are those of the corpus.
+        const int32_t *tok_moved = reinterpret_cast<const int32_t *>(reinterpret_cast<uintptr_t>(tok_dev) - 4u * t_begin);
+        w2v::KernelArgs a = kernel_args(ctx, tok_moved, off_dev, nsent, first_token_global_pos, epoch);
+        uint64_t waves = ctx->cfg.sentences_in_flight;
+        if (waves == 0) {
+            waves = w2v::train_resident_waves(a, ctx->cfg.device);
+            if (waves == 0) return fail(ctx, W2V_EHIP, "could not query kernel occupancy");
+        }
+        a.unit_shift = pick_unit_shift(ctx, nsent, ntok, waves);
+        if (waves > (nsent << a.unit_shift)) waves = nsent << a.unit_shift;
+        HIP_TRY(ctx, w2v::launch_reset_accum(a.accum, 1, stream_of(ctx)));
+        HIP_TRY(ctx, w2v::launch_train(a, (uint32_t)waves, stream_of(ctx)));
+        HIP_TRY(ctx, hipEventRecord(ctx->drained[h], stream_of(ctx)));
+        ctx->drained_recorded[h] = true;
+        s0 = s1;
+    }
     return W2V_OK;
 }
 
@@ -329,6 +414,14 @@ int w2v_debug_draws(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_t *sen
     HIP_TRY(ctx, hipStreamSynchronize(stream_of(ctx)));
     const w2v::KernelArgs a = kernel_args(ctx, tokens_dev, sent_off_dev, n_sent, first_token_global_pos, epoch);
     HIP_TRY(ctx, w2v::launch_draws(a, n_tokens, keep_dev, width_dev, neg_dev, stream_of(ctx)));
+    return W2V_OK;
+}
+
+int w2v_debug_set_units(w2v_ctx *ctx, int unit_shift)
+{
+    if (!ctx) return fail(nullptr, W2V_EINVAL, "ctx is NULL");
+    if (unit_shift < -1 || unit_shift > 6) return fail(ctx, W2V_EINVAL, "unit_shift must be -1 (automatic) or 0..6");
+    ctx->forced_unit_shift = unit_shift;
     return W2V_OK;
 }
 

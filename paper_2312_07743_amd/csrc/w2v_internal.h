@@ -38,6 +38,7 @@ struct KernelArgs {
     double             lr0, lr_min_frac;
     uint32_t           vocab, dim, ld, window, negatives, window_mode, table_size;
     uint32_t           subsample;      // 0: every threshold is "always keep", thr is not read
+    uint32_t           unit_shift;     // a sentence is handed out as 2^unit_shift units of work (window kernel only)
 };
 
 using TrainFn = void (*)(KernelArgs);
@@ -70,5 +71,12 @@ struct w2v_ctx {
     w2v::WorkspaceLayout ws;
     uint32_t             table_size = 0;
     bool                 table_built = false;
+    int                  forced_unit_shift = -1;   // test override of the work-queue granularity (-1: automatic)
     std::string          err;
+    // host-fed training (created on first use): copy stream, and per staging half an event for "filled"
+    // (recorded on the copy stream) and one for "trained, may be refilled" (recorded on the caller's stream)
+    hipStream_t          copy_stream = nullptr;
+    hipEvent_t           filled[2] = {nullptr, nullptr};
+    hipEvent_t           drained[2] = {nullptr, nullptr};
+    bool                 drained_recorded[2] = {false, false};
 };

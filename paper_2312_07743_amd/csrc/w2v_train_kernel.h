@@ -211,6 +211,7 @@ __device__ __forceinline__ float sentence_lr(const KernelArgs &A, uint64_t start
 //       atomic: a word fills more than 15 slots, weights are not used and ring rows are added to;
 //       plain: every negative distinct and different from the target;
 //       special: some context slot of the window is absent or repeats a word (slot weights differ from 1)
+//       idle (bit 19): a lead-in token of the unit; it has no window of its own and needs no output rows
 //   y = target word, z = word of the kept position that enters the ring at this window (or none)
 constexpr uint32_t kNoWord = 0xFFFFFFFFu;
 
@@ -281,22 +282,65 @@ train_kernel(KernelArgs A)
     };
 
     for (;;) {
-        // ---- next sentence from the work queue -------------------------------------------------
-        unsigned long long s_raw = 0;
-        if (lane == 0) s_raw = atomicAdd(&A.accum->next_sentence, 1ull);
-        const uint64_t s = uni64(s_raw);
-        if (s >= A.n_sent) break;
+        // ---- next unit of work from the queue ---------------------------------------------------
+        // A unit is one of 2^unit_shift equal stretches of a sentence's tokens.  Its windows are those of the
+        // kept tokens inside the stretch; the W kept tokens before it and after it are read as context only,
+        // so the windows are exactly those the whole sentence has (units of one sentence that run at the same
+        // time race like any two sentences do; one wavefront taking all units in order reproduces strict order).
+        unsigned long long q_raw = 0;
+        if (lane == 0) q_raw = atomicAdd(&A.accum->next_sentence, 1ull);
+        const uint64_t q = uni64(q_raw);
+        if (q >= (A.n_sent << A.unit_shift)) break;
+        const uint64_t s = q >> A.unit_shift;
         const uint64_t t0 = uni64(A.sent_off[s]);
         const uint64_t t1 = uni64(A.sent_off[s + 1]);
         const uint32_t len = (t1 > t0) ? (uint32_t)(t1 - t0) : 0u;
         const float alpha = sentence_lr(A, A.first_pos + t0);
+        const uint32_t unit_len = (uint32_t)(((uint64_t)len + (1u << A.unit_shift) - 1u) >> A.unit_shift);
+        const uint64_t u0_64 = (q & ((1ull << A.unit_shift) - 1ull)) * unit_len;
+        const uint32_t u0 = u0_64 < len ? (uint32_t)u0_64 : len;                  // the unit's tokens: [u0, u1)
+        const uint32_t u1 = (len - u0 > unit_len) ? u0 + unit_len : len;
+        if (u0 >= u1) continue;
+
+        // is the token at offset `off` of the sentence kept?  (w: its word; bad: id outside the vocabulary)
+        auto keep_token = [&](uint32_t off, int32_t &w, bool &bad) -> bool {
+            w = A.tokens[t0 + off];
+            bool k = w >= 0 && (uint32_t)w < A.vocab;
+            bad = !k;
+            if (k && A.subsample) {
+                const uint32_t th = A.thr[w];
+                if (th != 0xFFFFFFFFu) k = keep_decision(position_base(A.key, A.first_pos + t0 + off), th);
+            }
+            return k;
+        };
+        // the scan starts at the W-th kept token before the unit (or at the sentence start): n_lead of them
+        uint32_t n_lead = 0, raw_first = u0;
+        for (uint32_t hi = u0; n_lead < W && hi > 0;) {
+            const uint32_t lo = hi >= (uint32_t)kLanes ? hi - kLanes : 0u;
+            const uint32_t off = lo + lane;
+            int32_t w;
+            bool bad;
+            const bool k = off < hi && keep_token(off, w, bad);
+            uint64_t km = __ballot(k);
+            const uint32_t cnt = (uint32_t)__popcll(km);
+            raw_first = lo;
+            if (n_lead + cnt >= W) {
+                for (uint32_t drop = W - n_lead; drop > 1; --drop) km &= ~(1ull << (63 - __builtin_clzll(km)));
+                raw_first = lo + (63u - (uint32_t)__builtin_clzll(km));     // the (W - n_lead)-th kept token from the top
+                n_lead = W;
+            } else {
+                n_lead += cnt;
+            }
+            hi = lo;
+        }
 
         int32_t meta_word = -1;       // lane p&63: word of resident kept position p (-1: none)
         uint32_t meta_slot = 0;       // lane p&63: its ring slot
         uint32_t free_slots = (nslots >= 32) ? 0xFFFFFFFFu : ((1u << nslots) - 1u);
         uint32_t free_hi = (nslots > 32) ? ((1u << (nslots - 32)) - 1u) : 0u;   // slots 32..33 (W = 16)
-        uint32_t n_prod = 0;          // kept tokens found so far
-        uint32_t raw_next = 0;        // next token offset to look at
+        uint32_t n_prod = 0;          // kept tokens found so far (counted from the scan's start)
+        uint32_t n_own = 0;           // ... of them before the unit's end: windows exist for [n_lead, n_own)
+        uint32_t raw_next = raw_first;   // next token offset to look at
         uint32_t n_ins = 0;           // kept positions [0, n_ins) have entered the ring
         uint32_t i0 = 0;              // first window of the current chunk
 
@@ -342,29 +386,23 @@ train_kernel(KernelArgs A)
             // ---- look at more tokens until this chunk's windows know all their context ----------
             while (n_prod < i0 + kLanes + W + 1 && raw_next < len) {
                 const uint32_t off = raw_next + lane;
-                bool k = false;
+                bool k = false, bad = false;
                 int32_t w = -1;
-                if (off < len) {
-                    w = A.tokens[t0 + off];
-                    k = w >= 0 && (uint32_t)w < A.vocab;
-                    if (!k) ++dropped_acc;
-                    if (k && A.subsample) {
-                        const uint32_t th = A.thr[w];
-                        if (th != 0xFFFFFFFFu) k = keep_decision(position_base(A.key, A.first_pos + t0 + off), th);
-                    }
-                }
+                if (off < len) k = keep_token(off, w, bad);
+                if (bad && off >= u0 && off < u1) ++dropped_acc;
                 const uint64_t km = __ballot(k);
                 if (k) {
                     const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(km >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)km, 0u));
                     kw[(n_prod + rank) & (FCAP - 1)] = w;
                     kp[(n_prod + rank) & (FCAP - 1)] = off;
                 }
+                n_own += (uint32_t)__popcll(__ballot(k && off < u1));
                 n_prod += (uint32_t)__popcll(km);
                 raw_next += kLanes;
             }
             __syncthreads();
-            if (i0 >= n_prod) break;
-            const uint32_t nwin = (n_prod - i0 < (uint32_t)kLanes) ? n_prod - i0 : (uint32_t)kLanes;
+            if (i0 >= n_own) break;
+            const uint32_t nwin = (n_own - i0 < (uint32_t)kLanes) ? n_own - i0 : (uint32_t)kLanes;
 
             // ---- width and negatives of the chunk's windows, one window per lane ----------------
             // Negative k of a window carries a multiplicity: 0 if it equals the target or an earlier negative,
@@ -379,7 +417,7 @@ train_kernel(KernelArgs A)
                 const uint32_t idx = (i0 + lane) & (FCAP - 1);
                 my_w = kw[idx];
                 const uint64_t base = position_base(A.key, A.first_pos + t0 + kp[idx]);
-                my_b = window_width(base, W, A.window_mode);
+                my_b = (i0 + lane < n_lead) ? 0u : window_width(base, W, A.window_mode);   // lead-in tokens: context only
                 const uint32_t pe = i0 + lane + W + 1;
                 if (pe < n_prod) my_enter = (uint32_t)kw[pe & (FCAP - 1)];
                 uint32_t *pk = cb_pack + (size_t)lane * N;
@@ -493,7 +531,8 @@ train_kernel(KernelArgs A)
                 const uint32_t special = (exist != inside || dupmask != 0u) ? 1u : 0u;
                 if (overflow) dupmask = 0u;      // pathological repetition: every slot stays on, rows are added to atomically
                 reinterpret_cast<uint4 *>(cb_cm)[lane] = make_uint4(cm[0], cm[1], cm[2], cm[3]);
-                cb_meta[lane] = make_uint4(my_b | (reload << 8) | (overflow << 16) | (my_plain << 17) | (special << 18),
+                cb_meta[lane] = make_uint4(my_b | (reload << 8) | (overflow << 16) | (my_plain << 17) | (special << 18) |
+                                               ((my_b == 0u ? 1u : 0u) << 19),
                                            (uint32_t)my_w, my_enter, dupmask);
             }
             __syncthreads();
@@ -522,12 +561,13 @@ train_kernel(KernelArgs A)
             if (lane_k >= 1 && (KFULL || (uint32_t)lane_k <= N)) packv = cb_pack[lane_k - 1];
             if (lane_k == 0) packv = mraw.y | (1u << kIdBits);
             float O[KC][E];
+            const bool first_idle = (uni(mraw.x) >> 19) & 1u;
 #pragma unroll
             for (int kk = 0; kk < KC; ++kk) {
                 const uint32_t pk = lane_value(packv, (uint32_t)kk);
 #pragma unroll
                 for (int x = 0; x < E; ++x) O[kk][x] = 0.0f;
-                if (KFULL || (uint32_t)kk <= N) load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, O[kk]);
+                if (!first_idle && (KFULL || (uint32_t)kk <= N)) load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, O[kk]);
             }
 
             for (uint32_t j = 0; j < nwin; ++j) {
@@ -570,7 +610,7 @@ train_kernel(KernelArgs A)
                 // (d) the next window's output rows start their trip from memory
                 uint32_t packv_next = pack_next;
                 float On[KC][E];
-                if (has_next) {
+                if (has_next && !((uni(mraw_next.x) >> 19) & 1u)) {
                     if (lane_k == 0) packv_next = mraw_next.y | (1u << kIdBits);
 #pragma unroll
                     for (int kk = 0; kk < KC; ++kk) {
@@ -799,7 +839,7 @@ train_kernel(KernelArgs A)
                 // (g) rows of the next window that this window has just rewritten are fetched again
                 //     (a load issued after a store of the same wavefront sees the stored data)
                 if (has_next) {
-                    const uint32_t reload = nact ? (uni(mraw_next.x) >> 8) : 0u;
+                    const uint32_t reload = nact ? ((uni(mraw_next.x) >> 8) & 0x3Fu) : 0u;
                     if (reload) {
 #pragma unroll
                         for (int kk = 0; kk < KC; ++kk)
@@ -831,11 +871,11 @@ train_kernel(KernelArgs A)
             }
             i0 += nwin;
         }
-        kept_acc += n_prod;
+        kept_acc += n_own - n_lead;
 
         // ---- sentence done: the rows still in the ring go back -------------------------------------
         {
-            const uint32_t first = (n_prod > W) ? n_prod - W : 0u;   // positions < first left already
+            const uint32_t first = (n_own > W) ? n_own - W : 0u;     // positions < first left already
             for (uint32_t p = first; p < n_ins; ++p) ring_leave(p);
         }
         __syncthreads();

@@ -48,6 +48,15 @@ class Trainer:
         f = B.w2v_train_epoch_naive if naive else B.w2v_train_epoch
         f(self.ctx, self.tokens, self.sent_off, self.n_sent, first_token_global_pos, epoch)
 
+    def train_epoch_from_host(self, tokens, sent_off, epoch=0, first_token_global_pos=0, staging_bytes=32 << 20):
+        """tokens / sent_off: host arrays (numpy int32 / uint64, or pinned torch tensors of the same bytes); they
+        are cut into batches that are copied into a device staging buffer while the previous batch trains."""
+        if getattr(self, "staging", None) is None or self.staging.numel() != staging_bytes:
+            self.staging = torch.empty(staging_bytes, dtype=torch.uint8, device=self.dev)
+            assert self.staging.data_ptr() % 256 == 0
+        B.w2v_train_epoch_host(self.ctx, tokens, sent_off, len(sent_off) - 1, first_token_global_pos, epoch,
+                               self.staging, staging_bytes)
+
     def loss(self, reset=False):
         return B.w2v_loss(self.ctx, reset)
 

@@ -64,8 +64,8 @@ def test_integer_decisions_bit_exact(orc32, case):
         assert 0.2 < keep.mean() < 0.98
 
 
-def _parity(orc32, corpus, tol=1e-4, **kw):
-    g0, g1, gl, gp = run_gpu(corpus, sentences_in_flight=1, **kw)
+def _parity(orc32, corpus, tol=1e-4, unit_shift=None, **kw):
+    g0, g1, gl, gp = run_gpu(corpus, sentences_in_flight=1, unit_shift=unit_shift, **kw)
     r0, r1, rl, rp = run_oracle(orc32, corpus, **kw)
     assert gp == rp, (gp, rp)
     assert abs(gl - rl) <= 2e-5 * abs(rl) + 1e-9, (gl, rl)
@@ -115,6 +115,40 @@ def test_fixed_width_sizes_the_ring_by_the_fixed_width(orc32):
     # W=16 with rows of 512 floats is only possible because the widest window is ceil(16/2) = 8
     c = synth.zipf_corpus(300, 1.0, 5, 200, seed=12)
     _parity(orc32, c, dim=512, window=16, negatives=4, seed=5, window_mode=1, table_size=50021)
+
+
+@pytest.mark.parametrize("unit_shift", [1, 2, 3, 6])
+def test_sentences_cut_into_units_of_work(orc32, unit_shift):
+    """A sentence handed out as 2^k stretches (each with its lead-in and lead-out context) must train exactly
+    the windows of the whole sentence: one wavefront taking the units in order reproduces the oracle."""
+    rng = np.random.default_rng(4)
+    lens = [1000, 0, 1, 2, 7, 63, 64, 65, 129, 700, 5, 999]          # stretches shorter than a window too
+    tok = rng.zipf(1.3, size=sum(lens)).astype(np.int64)
+    tok = np.where(tok > 300, rng.integers(0, 300, size=tok.size), tok - 1).astype(np.int32)
+    tok[17] = -5                                                     # an invalid id is counted once, not per unit
+    off = np.cumsum([0] + lens).astype(np.uint64)
+    c = synth.Corpus(tok, off, np.bincount(tok[tok >= 0], minlength=300).astype(np.uint64))
+    for t, window in ((0.0, 5), (3e-2, 5), (3e-2, 10), (0.3, 2)):
+        _parity(orc32, c, dim=128, window=window, negatives=5, seed=9, subsample_t=t, table_size=50021,
+                unit_shift=unit_shift)
+
+
+def test_units_do_not_change_counters():
+    from paper_2312_07743_amd.trainer import Trainer
+    c = synth.planted_corpus(vocab=3000, n_sent=40, sent_len=777, seed=5, band_start=200, n_clusters=4,
+                             cluster_size=20, min_count=2)
+    tok = c.tokens.copy()
+    tok[::501] = -1
+    seen = []
+    for shift in (0, 2, 5):
+        tr = Trainer(vocab=c.vocab, dim=64, window=5, negatives=3, counts=c.counts, tokens_per_epoch=c.n_tokens, seed=3,
+                     table_size=1 << 14, subsample_t=1e-3)
+        tr.set_corpus(tok, c.sent_off)
+        B.w2v_debug_set_units(tr.ctx, shift)
+        tr.train_epoch(0)
+        seen.append((tr.counters(), tr.loss()[1]))
+        tr.close()
+    assert seen[0] == seen[1] == seen[2] and seen[0][0][1] == len(tok[::501])
 
 
 def test_degenerate_sentences(orc32):

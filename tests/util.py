@@ -23,13 +23,16 @@ def run_oracle(orc, corpus, *, dim, window, negatives, seed, epochs=1, table_siz
 
 def run_gpu(corpus, *, dim, window, negatives, seed, epochs=1, table_size=1 << 16, subsample_t=0.0, window_mode=0,
             lr0=0.025, sentences_in_flight=0, syn0=None, syn1neg=None, first_token_global_pos=0,
-            tokens_per_epoch=None, total_epochs=None, start_epoch=0, naive=False):
+            tokens_per_epoch=None, total_epochs=None, start_epoch=0, naive=False, unit_shift=None):
+    from paper_2312_07743_amd import binding
     from paper_2312_07743_amd.trainer import Trainer
     tr = Trainer(vocab=corpus.vocab, dim=dim, window=window, negatives=negatives, counts=corpus.counts,
                  tokens_per_epoch=tokens_per_epoch or corpus.n_tokens, seed=seed, table_size=table_size,
                  subsample_t=subsample_t, total_epochs=total_epochs or epochs, sentences_in_flight=sentences_in_flight,
                  window_mode=window_mode, lr0=lr0, syn0=syn0, syn1neg=syn1neg)
     tr.set_corpus(corpus.tokens, corpus.sent_off)
+    if unit_shift is not None:
+        binding.w2v_debug_set_units(tr.ctx, unit_shift)
     for e in range(start_epoch, start_epoch + epochs):
         tr.train_epoch(e, first_token_global_pos, naive=naive)
     loss, pairs = tr.loss()
