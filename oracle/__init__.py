@@ -21,7 +21,8 @@ class Params(C.Structure):
                 ("total_epochs", C.c_uint32), ("epoch", C.c_uint32),
                 ("tokens_per_epoch", C.c_uint64), ("first_token_global_pos", C.c_uint64),
                 ("seed", C.c_uint64), ("table_size", C.c_uint64),
-                ("lr0", C.c_double), ("lr_min_frac", C.c_double)]
+                ("lr0", C.c_double), ("lr_min_frac", C.c_double),
+                ("negative_block", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 class Oracle:
@@ -125,7 +126,8 @@ class Oracle:
     def train_epoch(self, syn0, syn1neg, counts, tokens, sent_off, *, window, negatives,
                     seed, epoch=0, total_epochs=1, tokens_per_epoch=None, first_token_global_pos=0,
                     table_size=1 << 24, lr0=0.025, lr_min_frac=1e-4, subsample_t=0.0,
-                    window_mode=0, update_mode=0, dump=False, s_begin=0, s_end=None, s_stride=1):
+                    window_mode=0, update_mode=0, dump=False, s_begin=0, s_end=None, s_stride=1,
+                    negative_block=0):
         """Serial SGNS over sentences [s_begin, s_end) with the given stride, in place.
         Returns dict(loss_sum, pairs[, keep, width, neg])."""
         assert syn0.dtype == self.real and syn1neg.dtype == self.real
@@ -138,7 +140,7 @@ class Oracle:
         T = len(tokens)
         P = Params(V, d, window, negatives, window_mode, update_mode, total_epochs, epoch,
                    T if tokens_per_epoch is None else tokens_per_epoch, first_token_global_pos,
-                   seed, table_size, lr0, lr_min_frac)
+                   seed, table_size, lr0, lr_min_frac, negative_block, 0)
         end = self.table_ends(counts, table_size)
         thr = self.thresholds(counts, subsample_t)
         loss = C.c_double(0.0)

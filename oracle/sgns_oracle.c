@@ -21,6 +21,10 @@
  *   - traditional window width: random in [1, W]    Section 3.2
  *   - the paper's own variant: fixed width ceil(W/2) Section 3.2
  *   - sentences are independent units (Hogwild)     Section 2.2 / 2.3
+ *   - optional extension named as future work: one set of negatives for the
+ *     windows of several consecutive tokens .......... Section 3.1 (temporal
+ *                                                    locality and reuse),
+ *                                                    Section 7 (future work)
  *   - words with >= 5 occurrences, <= 1000 words per sentence: corpus
  *     preparation, done by the caller ............... Table 3 caption
  * Where the paper is silent (sampling distribution exponent, subsampling
@@ -311,6 +315,11 @@ typedef struct orc_params {
     uint32_t total_epochs, epoch;
     uint64_t tokens_per_epoch, first_token_global_pos, seed, table_size;
     double lr0, lr_min_frac;
+    /* Negative reuse over more than one window (0 or 1: off, the paper's method).  With a block of B > 1 the
+     * tokens of a sentence are taken in stretches of B consecutive tokens (by offset in the sentence, before
+     * subsampling), and every window centred in a stretch uses the N negatives drawn at the stretch's first
+     * token position.  A negative equal to a window's own target is still skipped for that window only. */
+    uint32_t negative_block, reserved;
 } orc_params;
 
 /* Optional dumps (any may be NULL), indexed by token offset in `tokens`:
@@ -349,8 +358,13 @@ int orc_train_range(const orc_params *P, real_t *syn0, real_t *syn1neg,
             uint32_t bw = orc_width(W, P->window_mode, P->seed, P->epoch, pos);
             int32_t out[ORC_MAX_NEG + 1];
             out[0] = kw[i];
+            uint64_t neg_pos = pos;
+            if (P->negative_block > 1) {
+                const uint64_t off = kp[i] - a;              /* offset of the centre in its sentence */
+                neg_pos = P->first_token_global_pos + a + (off / P->negative_block) * P->negative_block;
+            }
             for (uint32_t k = 0; k < N; ++k)
-                out[1 + k] = orc_negative(table_end, V, P->table_size, P->seed, P->epoch, pos, k);
+                out[1 + k] = orc_negative(table_end, V, P->table_size, P->seed, P->epoch, neg_pos, k);
             if (width_out) width_out[kp[i]] = (uint8_t)bw;
             if (neg_out) for (uint32_t k = 0; k < N; ++k) neg_out[kp[i] * N + k] = out[1 + k];
             int32_t ctx[ORC_MAX_CTX]; uint32_t nctx = 0;

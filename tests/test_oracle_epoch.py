@@ -218,3 +218,65 @@ def test_both_readings_of_the_update_order_reach_the_same_quality(orc32):
                                   epoch=e, total_epochs=3, table_size=1 << 18, update_mode=mode)
         res.append(r["loss_sum"] / r["pairs"])
     assert abs(res[0] - res[1]) / res[0] < 0.02, res
+
+
+def test_negative_block_shares_the_stretch_start_draws(orc32):
+    """Negative reuse over several windows (Section 7 names it as future work): with a block of B tokens every
+    window centred in the same stretch of B consecutive tokens of a sentence uses the draws of the stretch's
+    first position.  Checked against the scalar draw function at positions computed here, not by the oracle."""
+    rng = np.random.default_rng(5)
+    lens = [37, 1, 0, 64, 9]
+    tok = rng.integers(0, 60, size=sum(lens)).astype(np.int32)
+    off = np.cumsum([0] + lens).astype(np.uint64)
+    counts = np.bincount(tok, minlength=60).astype(np.uint64)
+    V, d, N, tsz, seed, first = 60, 4, 3, 4099, 21, 1000
+    end = orc32.table_ends(counts, tsz)
+    base = None
+    for B in (0, 1, 4, 16):
+        syn0, syn1 = orc32.init_weights(3, V, d)
+        r = orc32.train_epoch(syn0, syn1, counts, tok, off, window=2, negatives=N, seed=seed, epoch=1, total_epochs=2,
+                              first_token_global_pos=first, tokens_per_epoch=5000, table_size=tsz, subsample_t=5e-3,
+                              dump=True, negative_block=B)
+        if B <= 1:
+            if base is None:
+                base = (syn0.copy(), syn1.copy(), r["neg"].copy())
+            else:                                   # a block of one token is the paper's method, bit for bit
+                assert np.array_equal(syn0, base[0]) and np.array_equal(syn1, base[1]) and np.array_equal(r["neg"], base[2])
+        assert 0 < r["keep"].sum() < len(tok)
+        for s in range(len(lens)):
+            for t in range(int(off[s]), int(off[s + 1])):
+                if not r["keep"][t]:
+                    assert np.all(r["neg"][t] == -1)
+                    continue
+                o = t - int(off[s])
+                start = t if B <= 1 else int(off[s]) + (o // B) * B
+                want = [orc32.negative(end, tsz, seed, 1, first + start, k) for k in range(N)]
+                assert list(r["neg"][t]) == want
+        # keep decisions and widths do not depend on the block
+        assert r["width"].max() <= 2
+
+
+def test_negative_block_hand_case(orc64):
+    # Two windows share one negative set: with syn1neg = 0 every dot product of the first window is 0, so the
+    # negatives' rows move by -alpha/2 * (sum of its context rows); the second window then sees those rows.
+    V, d = 6, 2
+    rng = np.random.default_rng(2)
+    syn0 = rng.normal(size=(V, d))
+    s0 = syn0.copy()
+    counts = np.array([0, 0, 0, 0, 5, 7], np.uint64)          # negatives can only be words 4 or 5
+    tok, off = _one_sentence([0, 1])
+    end = orc64.table_ends(counts, 64)
+    syn1 = np.zeros((V, d))
+    r = orc64.train_epoch(syn0, syn1, counts, tok, off, window=1, negatives=1, seed=9, lr0=0.5, lr_min_frac=1.0,
+                          table_size=64, negative_block=2, dump=True)
+    n = orc64.negative(end, 64, 9, 0, 0, 0)                    # the draw of position 0 serves both windows
+    assert list(r["neg"][:, 0]) == [n, n]
+    a = 0.5
+    # window 0: centre 0, context {1}; window 1: centre 1, context {0}
+    o_n = -0.5 * a * s0[1]                                     # negative row after window 0
+    o_t0 = 0.5 * a * s0[1]
+    x = float(s0[0] @ o_n)                                     # window 1 pairs context 0 with the moved negative row
+    g = a * (0.0 - _sigmoid(x))
+    assert np.allclose(syn1[n], o_n + g * s0[0], rtol=0, atol=1e-15)
+    assert np.allclose(syn1[0], o_t0, rtol=0, atol=1e-15)
+    assert np.allclose(syn0[0], s0[0] + g * o_n, rtol=0, atol=1e-15)      # context of window 1 moves by g * (old negative row)
