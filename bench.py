@@ -43,6 +43,9 @@ def main():
     ap.add_argument("--from-host", action="store_true",
                     help="feed the corpus from pinned host memory through w2v_train_epoch_host (PCIe-inclusive rate)")
     ap.add_argument("--staging-mb", type=int, default=32)
+    ap.add_argument("--negative-block", type=int, default=0,
+                    help="reuse of negatives over the windows centred in one stretch of this many tokens (an extension "
+                         "the paper names as future work; 0 = the paper's fresh negatives per window)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--naive", action="store_true",
                     help="time the no-reuse comparator kernel instead of the window kernel (traffic comparison only)")
@@ -80,7 +83,7 @@ def main():
     E = args.warmup + args.steps
     tr = Trainer(vocab=corpus.vocab, dim=dim, window=window, negatives=negatives, counts=corpus.counts,
                  tokens_per_epoch=corpus.n_tokens, seed=2024, table_size=table_size, subsample_t=t_sub,
-                 total_epochs=E, sentences_in_flight=args.in_flight, window_mode=1 if args.fixed_width else 0)
+                 total_epochs=E, sentences_in_flight=args.in_flight, window_mode=1 if args.fixed_width else 0, negative_block=args.negative_block)
     tr.set_corpus(corpus.tokens, corpus.sent_off)
     if args.from_host:
         t_pin = torch.as_tensor(corpus.tokens).pin_memory()
@@ -112,13 +115,21 @@ def main():
 
     words = corpus.n_tokens * args.steps
     row_bytes = 4 * dim
-    algo_bytes_per_launch = (2 * negatives + 4) * row_bytes * (kept / args.steps)
+    rows_per_kept = 2 * negatives + 4
+    if args.negative_block > 1:
+        # the negatives' rows move once per stretch that has a kept token (first timed epoch taken as typical)
+        keep, _, _ = tr.draws(epoch=args.warmup)
+        sent = np.repeat(np.arange(corpus.n_sent), np.diff(corpus.sent_off.astype(np.int64)))
+        stretch = (np.arange(corpus.n_tokens) - corpus.sent_off.astype(np.int64)[sent]) // args.negative_block
+        key = (sent.astype(np.int64) << 32) | stretch
+        rows_per_kept = 4 + 2 * negatives * len(np.unique(key[keep != 0])) / max(int(keep.sum()), 1)
+    algo_bytes_per_launch = rows_per_kept * row_bytes * (kept / args.steps)
     avg_kernel_s = float(np.mean(kernel_ms)) / 1e3
     achieved = algo_bytes_per_launch / avg_kernel_s / 1e9
     traffic = None
     # measured L2<->memory bytes per launch, from the committed rocprofv3 counter summary of this workload
     tpath = os.path.join(ROOT, "profiles", f"window_kernel_{args.workload}_d{dim}_counters.txt")
-    if os.path.exists(tpath) and not args.naive:
+    if os.path.exists(tpath) and not (args.naive or args.fixed_width or args.from_host or args.negative_block > 1):
         for line in open(tpath):
             if line.startswith("hbm_bytes_per_launch:"):
                 traffic = float(line.split(":")[1])
@@ -145,6 +156,8 @@ def main():
                                f"{corpus.n_tokens} tokens in {corpus.n_sent} sentences, d={dim}, W={window}, "
                                f"N={negatives}, subsample t={t_sub}, lr 0.025 linear decay"
                                + (", fixed width ceil(W/2)" if args.fixed_width else "")
+                               + (f", negatives shared by stretches of {args.negative_block} tokens "
+                                  f"({rows_per_kept:.2f} rows per kept word)" if args.negative_block > 1 else "")
                                + (f", corpus fed from pinned host memory in batches of {args.staging_mb // 2} MiB"
                                   if args.from_host else ""),
                    "kept_words_per_s": kept / wall, "kept_fraction": kept / words,
@@ -164,7 +177,7 @@ def main():
         c0 = time.perf_counter()
         orc.train_epoch(syn0, syn1, corpus.counts, corpus.tokens, corpus.sent_off, window=window, negatives=negatives,
                         seed=2024, epoch=0, total_epochs=E, table_size=table_size, subsample_t=t_sub, s_end=ns,
-                        window_mode=1 if args.fixed_width else 0)
+                        window_mode=1 if args.fixed_width else 0, negative_block=args.negative_block)
         cdt = time.perf_counter() - c0
         out["cpu_baseline"] = {"value": int(corpus.sent_off[ns]) / cdt, "unit": "words/s", "cores": 1,
                                "kind": "oracle",

@@ -68,6 +68,13 @@ typedef struct w2v_config {
     void    *stream;              /* hipStream_t owned by the caller (NULL = the default stream)        */
     void    *workspace;           /* device scratch, 256-byte aligned, owned by the caller              */
     uint64_t workspace_bytes;     /* >= w2v_query_workspace()                                           */
+    uint32_t negative_block;      /* 0 or 1: N fresh negatives for every window (Sec. 3.1, the paper's
+                                     method).  B in {2,4,8,16,32,64}: reuse over more than one window
+                                     (Sec. 7, future work): the windows centred in one stretch of B
+                                     consecutive tokens of a sentence (offsets before subsampling) share
+                                     the N negatives drawn at the stretch's first position; a negative
+                                     equal to a window's own target is skipped for that window only      */
+    uint32_t reserved;            /* 0                                                                  */
 } w2v_config;
 
 /* Row stride (in floats) that keeps every row aligned to 128-byte memory lines. */

@@ -57,6 +57,9 @@ std::string check_config(const w2v_config *c)
     if (c->window < 1 || c->window > W2V_MAX_WINDOW) return "cfg.window out of range [1, 16]";
     if (c->negatives > W2V_MAX_NEGATIVES) return "cfg.negatives out of range [0, 20]";
     if (c->window_mode > 1) return "cfg.window_mode must be 0 or 1";
+    if (c->negative_block > 64u || (c->negative_block & (c->negative_block - 1u)) != 0)
+        return "cfg.negative_block must be 0 or a power of two up to 64";
+    if (c->reserved != 0) return "cfg.reserved must be 0";
     if (c->total_epochs < 1) return "cfg.total_epochs must be >= 1";
     if (c->tokens_per_epoch < 1) return "cfg.tokens_per_epoch must be >= 1";
     if (c->tokens_per_epoch > (1ull << 52) / c->total_epochs) return "total_epochs * tokens_per_epoch exceeds 2^52";
@@ -107,6 +110,8 @@ w2v::KernelArgs kernel_args(const w2v_ctx *ctx, const int32_t *tokens, const uin
     a.table_size = ctx->table_size;
     a.subsample = c.subsample_t > 0.0 ? 1u : 0u;
     a.unit_shift = 0;
+    a.neg_shift = 0;
+    for (uint32_t b = c.negative_block; b > 1u; b >>= 1) ++a.neg_shift;
     return a;
 }
 
@@ -342,6 +347,8 @@ int w2v_train_epoch_naive(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_
 {
     const int rc = check_train_call(ctx, tokens_dev, sent_off_dev, n_sent, first_token_global_pos, epoch);
     if (rc != W2V_OK) return rc;
+    if (ctx->cfg.negative_block > 1u)
+        return fail(ctx, W2V_EINVAL, "the no-reuse comparator draws fresh negatives per window (cfg.negative_block must be 0 or 1)");
     if (n_sent == 0) return W2V_OK;
     HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
     const w2v::KernelArgs a = kernel_args(ctx, tokens_dev, sent_off_dev, n_sent, first_token_global_pos, epoch);

@@ -39,6 +39,8 @@ struct KernelArgs {
     uint32_t           vocab, dim, ld, window, negatives, window_mode, table_size;
     uint32_t           subsample;      // 0: every threshold is "always keep", thr is not read
     uint32_t           unit_shift;     // a sentence is handed out as 2^unit_shift units of work (window kernel only)
+    uint32_t           neg_shift;      // 0: negatives drawn at each window's own position; s: at the first position
+                                       // of the stretch of 2^s tokens (offsets in the sentence) the centre lies in
 };
 
 using TrainFn = void (*)(KernelArgs);

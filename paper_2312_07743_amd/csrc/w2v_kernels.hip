@@ -44,8 +44,20 @@ __global__ void draws_kernel(KernelArgs A, uint64_t n_tokens, uint8_t *keep, uin
         if (k) k = keep_decision(base, A.subsample ? A.thr[w] : 0xFFFFFFFFu);
         keep[t] = k ? 1 : 0;
         width[t] = k ? (uint8_t)window_width(base, A.window, A.window_mode) : 0;
+        uint64_t nbase = base;
+        if (k && A.neg_shift) {
+            // sentence of token t: the last s with sent_off[s] <= t; its negatives come from the first position
+            // of the stretch of 2^neg_shift tokens (counted from the sentence start) that t lies in
+            uint64_t lo = 0, hi = A.n_sent;
+            while (hi - lo > 1) {
+                const uint64_t mid = lo + (hi - lo) / 2;
+                if (A.sent_off[mid] <= t) lo = mid; else hi = mid;
+            }
+            const uint64_t start = A.sent_off[lo];
+            nbase = position_base(A.key, A.first_pos + start + (((t - start) >> A.neg_shift) << A.neg_shift));
+        }
         for (uint32_t j = 0; j < A.negatives; ++j)
-            neg[t * A.negatives + j] = k ? A.table[negative_slot(base, j, A.table_size)] : -1;
+            neg[t * A.negatives + j] = k ? A.table[negative_slot(nbase, j, A.table_size)] : -1;
     }
 }
 

@@ -212,6 +212,7 @@ __device__ __forceinline__ float sentence_lr(const KernelArgs &A, uint64_t start
 //       plain: every negative distinct and different from the target;
 //       special: some context slot of the window is absent or repeats a word (slot weights differ from 1)
 //       idle (bit 19): a lead-in token of the unit; it has no window of its own and needs no output rows
+//       hand-over (bit 20): the next window uses the same negatives; their rows stay in registers for it
 //   y = target word, z = word of the kept position that enters the ring at this window (or none)
 constexpr uint32_t kNoWord = 0xFFFFFFFFu;
 
@@ -410,14 +411,18 @@ train_kernel(KernelArgs A)
             // multiplicities stay in registers and every comparison is unrolled; otherwise they are worked on
             // in LDS.  Negatives that do not exist (k >= N) get ids no word has, so they match nothing.
             int32_t my_w = -1;
-            uint32_t my_b = 0, my_enter = kNoWord, my_plain = 0;
+            uint32_t my_b = 0, my_enter = kNoWord, my_plain = 0, my_stretch = 0;
             uint32_t nid[NREG ? KC - 1 : 1] = {}, nmult[NREG ? KC - 1 : 1] = {};
             const bool have = (uint32_t)lane < nwin;
             if (have) {
                 const uint32_t idx = (i0 + lane) & (FCAP - 1);
                 my_w = kw[idx];
-                const uint64_t base = position_base(A.key, A.first_pos + t0 + kp[idx]);
+                const uint32_t my_off = kp[idx];
+                const uint64_t base = position_base(A.key, A.first_pos + t0 + my_off);
                 my_b = (i0 + lane < n_lead) ? 0u : window_width(base, W, A.window_mode);   // lead-in tokens: context only
+                // negatives: drawn at my own position, or at the first position of my stretch of 2^neg_shift tokens
+                my_stretch = my_off >> A.neg_shift;
+                const uint64_t nbase = A.neg_shift ? position_base(A.key, A.first_pos + t0 + (my_stretch << A.neg_shift)) : base;
                 const uint32_t pe = i0 + lane + W + 1;
                 if (pe < n_prod) my_enter = (uint32_t)kw[pe & (FCAP - 1)];
                 uint32_t *pk = cb_pack + (size_t)lane * N;
@@ -426,7 +431,7 @@ train_kernel(KernelArgs A)
 #pragma unroll
                     for (int k = 0; k < KC - 1; ++k) {
                         nid[k] = kIdMask + 1u + (uint32_t)k;
-                        if (KEXACT || (uint32_t)k < N) nid[k] = (uint32_t)A.table[negative_slot(base, (uint32_t)k, A.table_size)];
+                        if (KEXACT || (uint32_t)k < N) nid[k] = (uint32_t)A.table[negative_slot(nbase, (uint32_t)k, A.table_size)];
                     }
 #pragma unroll
                     for (int k = 0; k < KC - 1; ++k) {
@@ -443,7 +448,7 @@ train_kernel(KernelArgs A)
                         }
                     }
                 } else {
-                    for (uint32_t k = 0; k < N; ++k) pk[k] = (uint32_t)A.table[negative_slot(base, k, A.table_size)];
+                    for (uint32_t k = 0; k < N; ++k) pk[k] = (uint32_t)A.table[negative_slot(nbase, k, A.table_size)];
                     for (uint32_t k = 0; k < N; ++k) {
                         const uint32_t id = pk[k] & kIdMask;
                         uint32_t m = (id == (uint32_t)my_w) ? 0u : 1u;
@@ -455,9 +460,9 @@ train_kernel(KernelArgs A)
                 }
             }
             __syncthreads();
+            uint32_t reload = 0, dupmask = 0, overflow = 0, special = 0;
             if (have) {
                 // which of my first KC output rows does the previous window also write?
-                uint32_t reload = 0;
                 if (lane > 0) {
                     const uint32_t pw = (uint32_t)kw[(i0 + lane - 1) & (FCAP - 1)];
                     const uint32_t *prev = cb_pack + (size_t)(lane - 1) * N;
@@ -508,7 +513,6 @@ train_kernel(KernelArgs A)
                     sw[c] = -2 - c;
                     if (ok) { sw[c] = kw[p & (FCAP - 1)]; exist |= 1u << c; }
                 }
-                uint32_t dupmask = 0, overflow = 0;
                 uint32_t cm[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
                 for (int c = 0; c < NCTX; ++c) {
@@ -528,13 +532,28 @@ train_kernel(KernelArgs A)
                 }
                 // special: some slot inside the width is absent, or two slots hold one word
                 const uint32_t inside = (my_b >= 16u) ? 0xFFFFFFFFu : ((1u << (2u * my_b)) - 1u);
-                const uint32_t special = (exist != inside || dupmask != 0u) ? 1u : 0u;
+                special = (exist != inside || dupmask != 0u) ? 1u : 0u;
                 if (overflow) dupmask = 0u;      // pathological repetition: every slot stays on, rows are added to atomically
                 reinterpret_cast<uint4 *>(cb_cm)[lane] = make_uint4(cm[0], cm[1], cm[2], cm[3]);
-                cb_meta[lane] = make_uint4(my_b | (reload << 8) | (overflow << 16) | (my_plain << 17) | (special << 18) |
-                                               ((my_b == 0u ? 1u : 0u) << 19),
-                                           (uint32_t)my_w, my_enter, dupmask);
             }
+            // Negatives shared by a stretch of tokens stay in registers from one window to the next: window j
+            // "hands over" to window j+1 when both are ordinary windows of one stretch (straight-line path, every
+            // negative distinct and different from either target, some context to train on).  The handing window
+            // skips the stores of its negative rows, the receiving one skips their fetch.
+            uint32_t hand_over = 0;
+            if constexpr (!MULTI) {
+                const uint32_t ok = (have && A.neg_shift && my_b != 0u && my_plain && !overflow && n_prod > 1u) ? 1u : 0u;
+                const uint32_t mine = (my_stretch << 1) | ok;
+                const uint32_t next = (uint32_t)__shfl_down((int)mine, 1, kLanes);
+                const uint32_t prev = (uint32_t)__shfl_up((int)mine, 1, kLanes);
+                hand_over = (ok && (uint32_t)lane + 1u < nwin && next == mine) ? 1u : 0u;
+                const bool receive = ok && lane > 0 && prev == mine;
+                if (receive) reload &= 1u;       // only my target row can have been rewritten in memory by the previous window
+            }
+            if (have)
+                cb_meta[lane] = make_uint4(my_b | (reload << 8) | (overflow << 16) | (my_plain << 17) | (special << 18) |
+                                               ((my_b == 0u ? 1u : 0u) << 19) | (hand_over << 20),
+                                           (uint32_t)my_w, my_enter, dupmask);
             __syncthreads();
 
             // ---- first chunk of a sentence: positions 0..W enter the ring before the first window ----
@@ -610,6 +629,8 @@ train_kernel(KernelArgs A)
                 // (d) the next window's output rows start their trip from memory
                 uint32_t packv_next = pack_next;
                 float On[KC][E];
+                //     (negative rows that this window hands over in registers are not fetched)
+                const bool hand_over = !MULTI && ((uni(mraw.x) >> 20) & 1u);
                 if (has_next && !((uni(mraw_next.x) >> 19) & 1u)) {
                     if (lane_k == 0) packv_next = mraw_next.y | (1u << kIdBits);
 #pragma unroll
@@ -617,7 +638,8 @@ train_kernel(KernelArgs A)
                         const uint32_t pk = lane_value(packv_next, (uint32_t)kk);
 #pragma unroll
                         for (int x = 0; x < E; ++x) On[kk][x] = 0.0f;
-                        if (KFULL || (uint32_t)kk <= N) load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, On[kk]);
+                        if ((KFULL || (uint32_t)kk <= N) && (kk == 0 || !hand_over))
+                            load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, On[kk]);
                     }
                 }
 
@@ -795,7 +817,12 @@ train_kernel(KernelArgs A)
                                 float t[E];
 #pragma unroll
                                 for (int x = 0; x < E; ++x) t[x] = O[kk][x] + dO[kk][x];
-                                store_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, t);
+                                if (kk >= 1 && hand_over) {          // stays in registers for the next window
+#pragma unroll
+                                    for (int x = 0; x < E; ++x) O[kk][x] = t[x];
+                                } else {
+                                    store_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, t);
+                                }
                             }
                         }
                     }
@@ -865,8 +892,10 @@ train_kernel(KernelArgs A)
                     packv = packv_next;
 #pragma unroll
                     for (int kk = 0; kk < KC; ++kk)
+                        if (kk == 0 || !hand_over) {
 #pragma unroll
-                        for (int x = 0; x < E; ++x) O[kk][x] = On[kk][x];
+                            for (int x = 0; x < E; ++x) O[kk][x] = On[kk][x];
+                        }
                 }
             }
             i0 += nwin;

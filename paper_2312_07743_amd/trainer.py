@@ -9,7 +9,7 @@ from . import binding as B
 class Trainer:
     def __init__(self, *, vocab, dim, window, negatives, counts, tokens_per_epoch, seed, table_size=1 << 24,
                  subsample_t=0.0, total_epochs=1, sentences_in_flight=0, window_mode=0, lr0=0.025,
-                 lr_min_frac=1e-4, device=0, init_weights=True, syn0=None, syn1neg=None):
+                 lr_min_frac=1e-4, device=0, init_weights=True, syn0=None, syn1neg=None, negative_block=0):
         if not torch.cuda.is_available():
             raise RuntimeError("the SGNS trainer needs a GPU; there is no CPU implementation in this package")
         self.dev = torch.device("cuda", device)
@@ -30,7 +30,7 @@ class Trainer:
                                  ld=self.ld, workspace=self.workspace, workspace_bytes=ws_bytes, device=device,
                                  stream=self.stream.cuda_stream, window_mode=window_mode, total_epochs=total_epochs,
                                  sentences_in_flight=sentences_in_flight, lr0=lr0, lr_min_frac=lr_min_frac,
-                                 subsample_t=subsample_t)
+                                 subsample_t=subsample_t, negative_block=negative_block)
         torch.cuda.synchronize(self.dev)
         self.ctx = B.w2v_create(self.cfg, 1 if init_weights else 0)
         B.w2v_build_unigram_table(self.ctx, counts, table_size)

@@ -151,6 +151,39 @@ def test_units_do_not_change_counters():
     assert seen[0] == seen[1] == seen[2] and seen[0][0][1] == len(tok[::501])
 
 
+@pytest.mark.parametrize("block,window,negatives", [(2, 5, 5), (8, 5, 5), (64, 5, 5), (8, 5, 3), (8, 10, 5), (16, 5, 10),
+                                                    (4, 16, 1)])
+def test_negatives_shared_by_a_stretch_of_tokens(orc32, block, window, negatives):
+    """cfg.negative_block: the windows centred in one stretch of tokens use one set of negatives, whose rows the
+    kernel keeps in registers from window to window.  Frequent words make targets hit the shared negatives, short
+    and empty sentences end stretches early; strict order must reproduce the oracle."""
+    rng = np.random.default_rng(block)
+    lens = [900, 0, 1, 130, 66, 2, 700, 17]
+    tok = rng.zipf(1.25, size=sum(lens)).astype(np.int64)
+    tok = np.where(tok > 400, rng.integers(0, 400, size=tok.size), tok - 1).astype(np.int32)
+    off = np.cumsum([0] + lens).astype(np.uint64)
+    c = synth.Corpus(tok, off, np.bincount(tok, minlength=400).astype(np.uint64))
+    # (without subsampling the few shared rows take so many updates in a row that fp32 rounding alone moves them
+    #  by 1e-4 to 4e-4 at the usual learning rate, fp32 against fp64 oracle; a smaller rate keeps that at 2e-5)
+    for t, shift, lr0 in ((0.0, None, 0.005), (2e-2, None, 0.025), (2e-2, 2, 0.025)):
+        _parity(orc32, c, dim=128, window=window, negatives=negatives, seed=13, subsample_t=t, table_size=50021,
+                negative_block=block, unit_shift=shift, lr0=lr0)
+
+
+def test_negative_block_draws_bit_exact(orc32):
+    from paper_2312_07743_amd.trainer import Trainer
+    c = synth.zipf_corpus(333, 1.2, 17, 301, seed=9)
+    tr = Trainer(vocab=c.vocab, dim=64, window=5, negatives=4, counts=c.counts, tokens_per_epoch=c.n_tokens, seed=99,
+                 table_size=100003, subsample_t=1e-2, total_epochs=2, negative_block=16)
+    tr.set_corpus(c.tokens, c.sent_off)
+    keep, width, neg = tr.draws(epoch=1)
+    tr.close()
+    syn0, syn1 = orc32.init_weights(1, c.vocab, 4)
+    r = orc32.train_epoch(syn0, syn1, c.counts, c.tokens, c.sent_off, window=5, negatives=4, seed=99, epoch=1,
+                          total_epochs=2, table_size=100003, subsample_t=1e-2, dump=True, negative_block=16)
+    assert np.array_equal(keep, r["keep"]) and np.array_equal(width, r["width"]) and np.array_equal(neg, r["neg"])
+
+
 def test_degenerate_sentences(orc32):
     # empty sentences, one-word sentences, sentences of invalid ids only, a long sentence (> one FIFO refill)
     rng = np.random.default_rng(3)

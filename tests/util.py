@@ -4,7 +4,7 @@ import numpy as np
 
 def run_oracle(orc, corpus, *, dim, window, negatives, seed, epochs=1, table_size=1 << 16, subsample_t=0.0,
                window_mode=0, lr0=0.025, syn0=None, syn1neg=None, first_token_global_pos=0, tokens_per_epoch=None,
-               total_epochs=None, start_epoch=0, update_mode=0):
+               total_epochs=None, start_epoch=0, update_mode=0, negative_block=0):
     if syn0 is None:
         syn0, syn1neg = orc.init_weights(seed, corpus.vocab, dim)
     else:
@@ -15,7 +15,8 @@ def run_oracle(orc, corpus, *, dim, window, negatives, seed, epochs=1, table_siz
         r = orc.train_epoch(syn0, syn1neg, corpus.counts, corpus.tokens, corpus.sent_off, window=window,
                             negatives=negatives, seed=seed, epoch=e, total_epochs=total_epochs, table_size=table_size,
                             subsample_t=subsample_t, window_mode=window_mode, lr0=lr0, update_mode=update_mode,
-                            first_token_global_pos=first_token_global_pos, tokens_per_epoch=tokens_per_epoch)
+                            first_token_global_pos=first_token_global_pos, tokens_per_epoch=tokens_per_epoch,
+                            negative_block=negative_block)
         loss += r["loss_sum"]
         pairs += r["pairs"]
     return syn0, syn1neg, loss, pairs
@@ -23,13 +24,13 @@ def run_oracle(orc, corpus, *, dim, window, negatives, seed, epochs=1, table_siz
 
 def run_gpu(corpus, *, dim, window, negatives, seed, epochs=1, table_size=1 << 16, subsample_t=0.0, window_mode=0,
             lr0=0.025, sentences_in_flight=0, syn0=None, syn1neg=None, first_token_global_pos=0,
-            tokens_per_epoch=None, total_epochs=None, start_epoch=0, naive=False, unit_shift=None):
+            tokens_per_epoch=None, total_epochs=None, start_epoch=0, naive=False, unit_shift=None, negative_block=0):
     from paper_2312_07743_amd import binding
     from paper_2312_07743_amd.trainer import Trainer
     tr = Trainer(vocab=corpus.vocab, dim=dim, window=window, negatives=negatives, counts=corpus.counts,
                  tokens_per_epoch=tokens_per_epoch or corpus.n_tokens, seed=seed, table_size=table_size,
                  subsample_t=subsample_t, total_epochs=total_epochs or epochs, sentences_in_flight=sentences_in_flight,
-                 window_mode=window_mode, lr0=lr0, syn0=syn0, syn1neg=syn1neg)
+                 window_mode=window_mode, lr0=lr0, syn0=syn0, syn1neg=syn1neg, negative_block=negative_block)
     tr.set_corpus(corpus.tokens, corpus.sent_off)
     if unit_shift is not None:
         binding.w2v_debug_set_units(tr.ctx, unit_shift)
