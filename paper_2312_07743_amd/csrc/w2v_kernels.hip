@@ -74,27 +74,34 @@ __global__ void __launch_bounds__(kLanes) reduce_selftest_kernel(const float *in
 TrainFn train_fn_v1r1k0(uint32_t window, bool full);
 TrainFn train_fn_v1r1k1(uint32_t window, bool full);
 TrainFn train_fn_v1r1k2(uint32_t window, bool full);
+TrainFn train_fn_v1r1k3(uint32_t window, bool full);
 TrainFn train_fn_v2r1k0(uint32_t window, bool full);
 TrainFn train_fn_v2r1k1(uint32_t window, bool full);
 TrainFn train_fn_v2r1k2(uint32_t window, bool full);
+TrainFn train_fn_v2r1k3(uint32_t window, bool full);
 TrainFn train_fn_v4r1k0(uint32_t window, bool full);
 TrainFn train_fn_v4r1k1(uint32_t window, bool full);
 TrainFn train_fn_v4r1k2(uint32_t window, bool full);
+TrainFn train_fn_v4r1k3(uint32_t window, bool full);
 TrainFn train_fn_v1r5k0(uint32_t window, bool full);
 TrainFn train_fn_v1r5k1(uint32_t window, bool full);
 TrainFn train_fn_v1r5k2(uint32_t window, bool full);
+TrainFn train_fn_v1r5k3(uint32_t window, bool full);
 TrainFn train_fn_v4r2k0(uint32_t window, bool full);
 TrainFn train_fn_v4r2k1(uint32_t window, bool full);
 TrainFn train_fn_v4r2k2(uint32_t window, bool full);
+TrainFn train_fn_v4r2k3(uint32_t window, bool full);
 
 namespace {
 TrainFn train_fn(const KernelArgs &a, RowShape s)
 {
     const bool full = a.dim == (uint32_t)(kLanes * s.vw * s.r);
-    const int kmode = (a.negatives + 1 > (uint32_t)KC) ? 2 : (a.negatives + 1 == (uint32_t)KC) ? 1 : 0;
+    const uint32_t rows = a.negatives + 1;                  // output rows of a window
+    const int kmode = rows > 2u * KC ? 3 : rows > (uint32_t)KC ? 2 : rows == (uint32_t)KC ? 1 : 0;
 #define W2V_PICK(VW, R)                                                                              \
     if (s.vw == VW && s.r == R)                                                                      \
-        return kmode == 2 ? train_fn_v##VW##r##R##k2(a.window, full)                                 \
+        return kmode == 3 ? train_fn_v##VW##r##R##k3(a.window, full)                                 \
+             : kmode == 2 ? train_fn_v##VW##r##R##k2(a.window, full)                                 \
              : kmode == 1 ? train_fn_v##VW##r##R##k1(a.window, full) : train_fn_v##VW##r##R##k0(a.window, full);
     W2V_PICK(1, 1)
     W2V_PICK(2, 1)

@@ -217,7 +217,8 @@ __device__ __forceinline__ float sentence_lr(const KernelArgs &A, uint64_t start
 constexpr uint32_t kNoWord = 0xFFFFFFFFu;
 
 // KMODE: how the N + 1 output rows of a window relate to the KC rows handled at a time:
-//   0: fewer than KC rows, 1: exactly KC rows (every row-exists test folds away), 2: more than KC rows
+//   0: fewer than KC rows, 1: exactly KC rows (every row-exists test folds away), 2: up to 2 KC rows (two passes,
+//   each fetching the rows of the next while it computes), 3: more (further rows fetched when their pass begins)
 // wavefronts per SIMD the register allocator is asked to make room for (512 VGPRs per lane in all)
 #ifndef W2V_OCC_SMALL_WCAP
 #define W2V_OCC_SMALL_WCAP 10
@@ -234,7 +235,8 @@ train_kernel(KernelArgs A)
     constexpr int E = VW * R;            // floats of a row per lane
     constexpr int ROWF = kLanes * E;     // floats of a ring row in LDS
     constexpr int NCTX = 2 * WCAP;       // context positions a window can have
-    constexpr bool MULTI = KMODE == 2;   // output rows beyond the first KC are handled in further passes
+    constexpr bool MULTI = KMODE >= 2;   // output rows beyond the first KC are handled in further passes
+    constexpr bool TWO = KMODE == 2;     // ... in exactly one further pass (KC < N + 1 <= 2 KC)
     constexpr bool KFULL = KMODE >= 1;   // the first KC output rows all exist
     constexpr bool KEXACT = KMODE == 1;  // ... and there are no others
     constexpr bool NREG = KMODE <= 1;    // at most KC - 1 negatives: the sampling stage keeps them in registers
@@ -629,19 +631,24 @@ train_kernel(KernelArgs A)
                 // (d) the next window's output rows start their trip from memory
                 uint32_t packv_next = pack_next;
                 float On[KC][E];
-                //     (negative rows that this window hands over in registers are not fetched)
+                //     (negative rows that this window hands over in registers are not fetched).
+                //     Windows with two passes over their output rows fetch them between the passes instead.
                 const bool hand_over = !MULTI && ((uni(mraw.x) >> 20) & 1u);
-                if (has_next && !((uni(mraw_next.x) >> 19) & 1u)) {
-                    if (lane_k == 0) packv_next = mraw_next.y | (1u << kIdBits);
+                auto fetch_next_window = [&](auto &dst) {
+                    if (has_next && !((uni(mraw_next.x) >> 19) & 1u)) {
+                        if (lane_k == 0) packv_next = mraw_next.y | (1u << kIdBits);
 #pragma unroll
-                    for (int kk = 0; kk < KC; ++kk) {
-                        const uint32_t pk = lane_value(packv_next, (uint32_t)kk);
+                        for (int kk = 0; kk < KC; ++kk) {
+                            const uint32_t pk = lane_value(packv_next, (uint32_t)kk);
 #pragma unroll
-                        for (int x = 0; x < E; ++x) On[kk][x] = 0.0f;
-                        if ((KFULL || (uint32_t)kk <= N) && (kk == 0 || !hand_over))
-                            load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, On[kk]);
+                            for (int x = 0; x < E; ++x) dst[kk][x] = 0.0f;
+                            if ((KFULL || (uint32_t)kk <= N) && (kk == 0 || !hand_over))
+                                load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, dst[kk]);
+                        }
                     }
-                }
+                };
+                if constexpr (!TWO) fetch_next_window(On);
+                else if (nact == 0) fetch_next_window(O);
 
                 // (e) the window's arithmetic over context slots 0..NCW-1.
                 //     GENERAL = false: straight-line code for the common window: all NCW slots exist, no two
@@ -679,19 +686,10 @@ train_kernel(KernelArgs A)
                         }
                     };
                     if constexpr (!LOAD_PER_BLOCK) static_for<NCW>(fetch_slot);
-                    for (uint32_t kb = 0; kb <= (MULTI ? N : 0u); kb += KC) {
+                    // One pass: the KC output rows held in OB (ids in pv, rows kb .. kb+KC-1 of the window) against
+                    // all context slots.
+                    auto run_pass = [&](uint32_t kb, auto &OB, uint32_t pv) {
                         const uint32_t gk = kb + lane_k;
-                        uint32_t pv = packv;
-                        if (MULTI && kb) {                          // further output rows: fetched here
-                            pv = (gk <= N) ? cb_pack[(size_t)j * N + (gk - 1)] : 0u;
-#pragma unroll
-                            for (int kk = 0; kk < KC; ++kk) {
-                                const uint32_t pk = lane_value(pv, (uint32_t)kk);
-#pragma unroll
-                                for (int x = 0; x < E; ++x) O[kk][x] = 0.0f;
-                                if (kb + kk <= N) load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, O[kk]);
-                            }
-                        }
                         const float mult_lane = (KEXACT || gk <= N) ? (GENERAL ? (float)(pv >> kIdBits) : 1.0f) : 0.0f;
                         const float label = (gk == 0) ? 1.0f : 0.0f;
                         const float gscale = GENERAL ? alpha * mult_lane : alpha;
@@ -718,7 +716,7 @@ train_kernel(KernelArgs A)
                                     float p = 0.0f;
                                     if (cc < NC && (!MASKED || ((amask >> c) & 1u))) {
 #pragma unroll
-                                        for (int x = 0; x < E; ++x) p = __builtin_fmaf(I[c][x], O[kk][x], p);
+                                        for (int x = 0; x < E; ++x) p = __builtin_fmaf(I[c][x], OB[kk][x], p);
                                     }
                                     acc[cc * KC + kk] = p;
                                 }
@@ -762,8 +760,8 @@ train_kernel(KernelArgs A)
                                         if constexpr (!MASKED) {
 #pragma unroll
                                             for (int x = 0; x < E; ++x) {
-                                                if (kk == 0) dI[x] = mul_row_lane<v % 16>(G[v / 16], O[kk][x]);
-                                                else fma_row_lane<v % 16>(dI[x], G[v / 16], O[kk][x]);
+                                                if (kk == 0) dI[x] = mul_row_lane<v % 16>(G[v / 16], OB[kk][x]);
+                                                else fma_row_lane<v % 16>(dI[x], G[v / 16], OB[kk][x]);
                                                 if (q == 0 && cc == 0) dO[kk][x] = mul_row_lane<v % 16>(G[v / 16], I[c][x]);
                                                 else fma_row_lane<v % 16>(dO[kk][x], G[v / 16], I[c][x]);
                                             }
@@ -771,7 +769,7 @@ train_kernel(KernelArgs A)
                                             const float gs = lane_value(g, (uint32_t)v);
 #pragma unroll
                                             for (int x = 0; x < E; ++x) {
-                                                dI[x] = __builtin_fmaf(gs, O[kk][x], dI[x]);
+                                                dI[x] = __builtin_fmaf(gs, OB[kk][x], dI[x]);
                                                 dO[kk][x] = __builtin_fmaf(gs, I[c][x], dO[kk][x]);
                                             }
                                         }
@@ -816,14 +814,48 @@ train_kernel(KernelArgs A)
                             if ((KEXACT || kb + kk <= N) && (!GENERAL || (pk >> kIdBits))) {
                                 float t[E];
 #pragma unroll
-                                for (int x = 0; x < E; ++x) t[x] = O[kk][x] + dO[kk][x];
+                                for (int x = 0; x < E; ++x) t[x] = OB[kk][x] + dO[kk][x];
                                 if (kk >= 1 && hand_over) {          // stays in registers for the next window
 #pragma unroll
-                                    for (int x = 0; x < E; ++x) O[kk][x] = t[x];
+                                    for (int x = 0; x < E; ++x) OB[kk][x] = t[x];
                                 } else {
                                     store_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, t);
                                 }
                             }
+                        }
+                    };
+                    if constexpr (!MULTI) {
+                        run_pass(0u, O, packv);
+                    } else if constexpr (TWO) {
+                        // two passes: the second batch of rows travels into On while the first batch is worked on,
+                        // and the next window's first batch travels into O while the second is worked on
+                        const uint32_t gk2 = (uint32_t)KC + lane_k;
+                        const uint32_t pv2 = (gk2 <= N) ? cb_pack[(size_t)j * N + (gk2 - 1)] : 0u;
+#pragma unroll
+                        for (int kk = 0; kk < KC; ++kk) {
+                            const uint32_t pk = lane_value(pv2, (uint32_t)kk);
+#pragma unroll
+                            for (int x = 0; x < E; ++x) On[kk][x] = 0.0f;
+                            if ((uint32_t)KC + kk <= N) load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, On[kk]);
+                        }
+                        run_pass(0u, O, packv);
+                        fetch_next_window(O);
+                        run_pass((uint32_t)KC, On, pv2);
+                    } else {
+                        for (uint32_t kb = 0; kb <= N; kb += KC) {
+                            uint32_t pv = packv;
+                            if (kb) {                               // further output rows: fetched here
+                                const uint32_t gk = kb + lane_k;
+                                pv = (gk <= N) ? cb_pack[(size_t)j * N + (gk - 1)] : 0u;
+#pragma unroll
+                                for (int kk = 0; kk < KC; ++kk) {
+                                    const uint32_t pk = lane_value(pv, (uint32_t)kk);
+#pragma unroll
+                                    for (int x = 0; x < E; ++x) O[kk][x] = 0.0f;
+                                    if (kb + kk <= N) load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, O[kk]);
+                                }
+                            }
+                            run_pass(kb, O, pv);
                         }
                     }
                 };
@@ -872,7 +904,7 @@ train_kernel(KernelArgs A)
                         for (int kk = 0; kk < KC; ++kk)
                             if ((reload >> kk) & 1u) {
                                 const uint32_t pk = lane_value(packv_next, (uint32_t)kk);
-                                load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, On[kk]);
+                                load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, TWO ? O[kk] : On[kk]);
                             }
                     }
                 }
@@ -892,7 +924,7 @@ train_kernel(KernelArgs A)
                     packv = packv_next;
 #pragma unroll
                     for (int kk = 0; kk < KC; ++kk)
-                        if (kk == 0 || !hand_over) {
+                        if (!TWO && (kk == 0 || !hand_over)) {
 #pragma unroll
                             for (int x = 0; x < E; ++x) O[kk][x] = On[kk][x];
                         }

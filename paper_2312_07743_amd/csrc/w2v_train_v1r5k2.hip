@@ -1,4 +1,4 @@
-// window kernel, rows of 1 x 5 floats per lane, more than 6 output rows per window
+// window kernel, rows of 1 x 5 floats per lane, 7 to 12 output rows per window (two passes)
 #define W2V_VW 1
 #define W2V_R 5
 #define W2V_KMODE 2

@@ -1,0 +1,7 @@
+// window kernel, rows of 1 x 5 floats per lane, more than 12 output rows per window
+#define W2V_VW 1
+#define W2V_R 5
+#define W2V_KMODE 3
+#define W2V_GUARDED_ONLY 1
+#define W2V_ENTRY train_fn_v1r5k3
+#include "w2v_train_inst.inc"

@@ -1,4 +1,4 @@
-// window kernel, rows of 2 x 1 floats per lane, more than 6 output rows per window
+// window kernel, rows of 2 x 1 floats per lane, 7 to 12 output rows per window (two passes)
 #define W2V_VW 2
 #define W2V_R 1
 #define W2V_KMODE 2
