@@ -24,10 +24,7 @@ namespace {
 
 constexpr int kLanes = 64;
 constexpr int KC = 6;              // output rows held in registers at once
-#ifndef W2V_CC
-#define W2V_CC 10
-#endif
-constexpr int CC = W2V_CC;         // most context rows whose pairings are reduced together (CC*KC <= 64)
+constexpr int CC = 10;             // most context rows whose pairings are reduced together (CC*KC <= 64)
 constexpr int FCAP = 256;          // kept-token FIFO entries per wavefront (power of two)
 constexpr uint32_t kIdBits = 27;
 constexpr uint32_t kIdMask = (1u << kIdBits) - 1u;
@@ -219,14 +216,11 @@ constexpr uint32_t kNoWord = 0xFFFFFFFFu;
 // KMODE: how the N + 1 output rows of a window relate to the KC rows handled at a time:
 //   0: fewer than KC rows, 1: exactly KC rows (every row-exists test folds away), 2: up to 2 KC rows (two passes,
 //   each fetching the rows of the next while it computes), 3: more (further rows fetched when their pass begins)
+
 // wavefronts per SIMD the register allocator is asked to make room for (512 VGPRs per lane in all)
-#ifndef W2V_OCC_SMALL_WCAP
-#define W2V_OCC_SMALL_WCAP 10
-#endif
-#ifndef W2V_OCC_SMALL
-#define W2V_OCC_SMALL 3
-#endif
-constexpr int occupancy_goal(int e, int wcap) { return (e <= 2 && wcap <= W2V_OCC_SMALL_WCAP) ? W2V_OCC_SMALL : ((e * wcap <= 25) ? 2 : 1); }
+// (e: floats of a row per lane, wcap: widest window of the instantiation; measured: 4 per SIMD is no faster
+// than 3 for short rows because LDS then limits the CU, and 3 for rows of 4 floats per lane spills)
+constexpr int occupancy_goal(int e, int wcap) { return (e <= 2 && wcap <= 10) ? 3 : ((e * wcap <= 25) ? 2 : 1); }
 
 template <int VW, int R, int WCAP, bool FULL, int KMODE>
 __global__ void __launch_bounds__(kLanes) __attribute__((amdgpu_waves_per_eu(occupancy_goal(VW * R, WCAP))))
