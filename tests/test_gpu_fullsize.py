@@ -87,3 +87,53 @@ def test_lock_free_run_matches_serial_oracle_statistically(mid, reference):
         score = planted_score(emb, mid.labels)
         assert abs(score - ref_last["planted_score"]) <= 0.01, (score, ref_last)
         torch.cuda.synchronize()
+
+
+def _pairs_from_draws(keep, width, sent_off):
+    """(context, target) pairs of an epoch from the per-token decisions alone: the kept tokens of a sentence form a
+    sequence; the window of its i-th member with width b has min(b, i) + min(b, n-1-i) context words."""
+    lens = np.diff(sent_off.astype(np.int64))
+    sent = np.repeat(np.arange(len(lens)), lens)
+    k = keep.astype(bool)
+    ks, kb = sent[k], width[k].astype(np.int64)
+    n_kept = np.bincount(ks, minlength=len(lens))
+    first = np.concatenate([[0], np.cumsum(n_kept)[:-1]])
+    i = np.arange(len(ks)) - first[ks]
+    n = n_kept[ks]
+    return int((np.minimum(kb, i) + np.minimum(kb, n - 1 - i)).sum())
+
+
+@pytest.mark.parametrize("shape", ["large", "graph"])
+def test_counts_and_sampled_decisions_on_the_big_shapes(orc32, shape):
+    """Prefixes of configs[3] (d=300, N=10, t=1e-5, two passes over the output rows) and configs[4] (walks of 80,
+    W=10, no subsampling) placed late in an 800M-token epoch, every sentence lock-free at once: the counters must
+    equal what the integer decisions imply, and the decisions must be the oracle's at sampled positions."""
+    from paper_2312_07743_amd.trainer import Trainer
+    if shape == "large":
+        c = synth.planted_corpus(vocab=550000, s=1.1, n_sent=6000, sent_len=1000, seed=1)
+        P = dict(dim=300, window=5, negatives=10, subsample_t=1e-5)
+    else:
+        c = synth.barabasi_albert_walks(n_nodes=150000, m=5, walks_per_node=1, walk_len=80, seed=1)
+        P = dict(dim=128, window=10, negatives=5, subsample_t=0.0)
+    first, T, seed, tsz = 700_000_000, 800_000_000, 77, 1 << 24
+    tr = Trainer(vocab=c.vocab, counts=c.counts, tokens_per_epoch=T, seed=seed, table_size=tsz, total_epochs=1, **P)
+    tr.set_corpus(c.tokens, c.sent_off)
+    keep, width, neg = tr.draws(epoch=0, first_token_global_pos=first)
+    tr.train_epoch(0, first_token_global_pos=first)
+    kept, invalid = tr.counters()
+    loss, pairs = tr.loss()
+    emb = tr.embeddings(1)
+    tr.close()
+    assert invalid == 0 and kept == int(keep.sum())
+    assert pairs == _pairs_from_draws(keep, width, c.sent_off)
+    assert np.isfinite(emb).all() and 0.0 < loss / pairs < (P["negatives"] + 1) * np.log(2.0) * 1.05
+    thr = orc32.thresholds(c.counts, P["subsample_t"])
+    end = orc32.table_ends(c.counts, tsz)
+    rng = np.random.default_rng(1)
+    for t in rng.integers(0, c.n_tokens, size=1500):
+        t = int(t)
+        k = orc32.keep(thr, int(c.tokens[t]), seed, 0, first + t)
+        assert keep[t] == k
+        if k:
+            assert width[t] == orc32.width(P["window"], 0, seed, 0, first + t)
+            assert list(neg[t]) == [orc32.negative(end, tsz, seed, 0, first + t, j) for j in range(P["negatives"])]
