@@ -83,6 +83,10 @@ TrainFn train_fn_v4r1k0(uint32_t window, bool full);
 TrainFn train_fn_v4r1k1(uint32_t window, bool full);
 TrainFn train_fn_v4r1k2(uint32_t window, bool full);
 TrainFn train_fn_v4r1k3(uint32_t window, bool full);
+TrainFn train_fn_v4r1t1k0(uint32_t window, bool full);
+TrainFn train_fn_v4r1t1k1(uint32_t window, bool full);
+TrainFn train_fn_v4r1t1k2(uint32_t window, bool full);
+TrainFn train_fn_v4r1t1k3(uint32_t window, bool full);
 TrainFn train_fn_v1r5k0(uint32_t window, bool full);
 TrainFn train_fn_v1r5k1(uint32_t window, bool full);
 TrainFn train_fn_v1r5k2(uint32_t window, bool full);
@@ -95,14 +99,17 @@ TrainFn train_fn_v4r2k3(uint32_t window, bool full);
 namespace {
 TrainFn train_fn(const KernelArgs &a, RowShape s)
 {
-    const bool full = a.dim == (uint32_t)(kLanes * s.vw * s.r);
+    const bool full = a.dim == (uint32_t)(kLanes * floats_per_lane(s));
     const uint32_t rows = a.negatives + 1;                  // output rows of a window
     const int kmode = rows > 2u * KC ? 3 : rows > (uint32_t)KC ? 2 : rows == (uint32_t)KC ? 1 : 0;
 #define W2V_PICK(VW, R)                                                                              \
-    if (s.vw == VW && s.r == R)                                                                      \
+    if (s.vw == VW && s.r == R && s.tail == 0)                                                       \
         return kmode == 3 ? train_fn_v##VW##r##R##k3(a.window, full)                                 \
              : kmode == 2 ? train_fn_v##VW##r##R##k2(a.window, full)                                 \
              : kmode == 1 ? train_fn_v##VW##r##R##k1(a.window, full) : train_fn_v##VW##r##R##k0(a.window, full);
+    if (s.vw == 4 && s.r == 1 && s.tail == 1)
+        return kmode == 3 ? train_fn_v4r1t1k3(a.window, full) : kmode == 2 ? train_fn_v4r1t1k2(a.window, full)
+             : kmode == 1 ? train_fn_v4r1t1k1(a.window, full) : train_fn_v4r1t1k0(a.window, full);
     W2V_PICK(1, 1)
     W2V_PICK(2, 1)
     W2V_PICK(4, 1)
@@ -116,11 +123,16 @@ TrainFn train_fn(const KernelArgs &a, RowShape s)
 // ---------------------------------------------------------------------------------------------
 // host side of the kernels
 // ---------------------------------------------------------------------------------------------
-bool pick_row_shape(uint32_t dim, uint32_t ld, RowShape *out)
+bool pick_row_shape(uint32_t dim, uint32_t ld, uint32_t negatives, RowShape *out)
 {
-    static const RowShape shapes[] = {{1, 1}, {2, 1}, {4, 1}, {1, 5}, {4, 2}};   // by floats per lane
+    // by floats per lane; a row of 260..320 floats is one 16-byte chunk plus one float per lane when its length
+    // allows (a quarter of the memory instructions of five single floats)
+    static const RowShape shapes[] = {{1, 1, 0}, {2, 1, 0}, {4, 1, 0}, {4, 1, 1}, {1, 5, 0}, {4, 2, 0}};
     for (const RowShape &s : shapes) {
-        if ((uint32_t)(kLanes * s.vw * s.r) < dim) continue;
+        if ((uint32_t)(kLanes * floats_per_lane(s)) < dim) continue;
+        // 16-byte chunks need aligned groups of four registers; with two passes over the output rows (N > 5) the
+        // kernel has none to spare and single floats measured faster (Large prefix: 78 against 83 ms)
+        if (s.tail && negatives + 1u > (uint32_t)KC) continue;
         if (dim % s.vw || ld % s.vw) continue;
         *out = s;
         return true;
@@ -130,7 +142,7 @@ bool pick_row_shape(uint32_t dim, uint32_t ld, RowShape *out)
 
 uint32_t train_lds_bytes(const KernelArgs &a, RowShape s)
 {
-    const uint32_t rowf = kLanes * s.vw * s.r;
+    const uint32_t rowf = kLanes * floats_per_lane(s);
     return (2 * a.window + 3) * rowf * 4u + FCAP * 8u + kLanes * 32u + kLanes * a.negatives * 4u;
 }
 
@@ -153,7 +165,7 @@ hipError_t launch_reset_accum(Accum *accum, int what, hipStream_t stream)
 uint32_t train_resident_waves(const KernelArgs &a, int device)
 {
     RowShape s;
-    if (!pick_row_shape(a.dim, a.ld, &s)) return 0;
+    if (!pick_row_shape(a.dim, a.ld, a.negatives, &s)) return 0;
     TrainFn fn = train_fn(a, s);
     if (!fn) return 0;
     int per_cu = 0, cus = 0;
@@ -165,7 +177,7 @@ uint32_t train_resident_waves(const KernelArgs &a, int device)
 hipError_t launch_train(const KernelArgs &a, uint32_t waves, hipStream_t stream)
 {
     RowShape s;
-    if (!pick_row_shape(a.dim, a.ld, &s)) return hipErrorInvalidValue;
+    if (!pick_row_shape(a.dim, a.ld, a.negatives, &s)) return hipErrorInvalidValue;
     TrainFn fn = train_fn(a, s);
     if (!fn) return hipErrorInvalidValue;
     hipLaunchKernelGGL(fn, dim3(waves), dim3(kLanes), train_lds_bytes(a, s), stream, a);

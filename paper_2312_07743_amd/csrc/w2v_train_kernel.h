@@ -222,11 +222,12 @@ constexpr uint32_t kNoWord = 0xFFFFFFFFu;
 // than 3 for short rows because LDS then limits the CU, and 3 for rows of 4 floats per lane spills)
 constexpr int occupancy_goal(int e, int wcap) { return (e <= 2 && wcap <= 10) ? 3 : ((e * wcap <= 25) ? 2 : 1); }
 
-template <int VW, int R, int WCAP, bool FULL, int KMODE>
-__global__ void __launch_bounds__(kLanes) __attribute__((amdgpu_waves_per_eu(occupancy_goal(VW * R, WCAP))))
+template <int VW, int R, int TAIL, int WCAP, bool FULL, int KMODE>
+__global__ void __launch_bounds__(kLanes) __attribute__((amdgpu_waves_per_eu(occupancy_goal(VW * R + TAIL, WCAP))))
 train_kernel(KernelArgs A)
 {
-    constexpr int E = VW * R;            // floats of a row per lane
+    constexpr int E = VW * R + TAIL;     // floats of a row per lane
+    constexpr int NCH = R + TAIL;        // chunks of a row per lane: R of VW floats, then TAIL single floats
     constexpr int ROWF = kLanes * E;     // floats of a ring row in LDS
     constexpr int NCTX = 2 * WCAP;       // context positions a window can have
     constexpr bool MULTI = KMODE >= 2;   // output rows beyond the first KC are handled in further passes
@@ -247,36 +248,60 @@ train_kernel(KernelArgs A)
     uint32_t *cb_cm = reinterpret_cast<uint32_t *>(cb_meta + kLanes);        // [64][4] context multiplicities, 4 bits per slot
     uint32_t *cb_pack = cb_cm + 4 * kLanes;                                  // [64][N] negative id | multiplicity<<27
 
+    // A lane's share of a row: chunk r < R is VW consecutive floats at (r*64 + lane)*VW, chunk R + t is the
+    // single float at 64*VW*R + t*64 + lane.  `chunks` calls f(chunk index, its width, its place in a register row).
+    auto chunks = [&](auto &&f) {
+        static_for<NCH>([&](auto r_tag) {
+            constexpr int r = decltype(r_tag)::value;
+            f(r_tag, std::integral_constant<int, (r < R ? VW : 1)>{},
+              std::integral_constant<int, (r < R ? r * VW : R * VW + (r - R))>{});
+        });
+    };
     // element offsets of this lane inside a row, and whether they exist (dim may not fill 64*E)
-    int eoff[R];
-    bool evalid[R];
+    int eoff[NCH];
+    bool evalid[NCH];
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        eoff[r] = (r * kLanes + lane) * VW;
+    for (int r = 0; r < NCH; ++r) {
+        eoff[r] = r < R ? (r * kLanes + lane) * VW : kLanes * VW * R + (r - R) * kLanes + lane;
         evalid[r] = FULL || (uint32_t)eoff[r] < A.dim;
     }
     const int lane_c = lane / KC, lane_k = lane % KC;   // pairing handled by this lane after the reduction
+
+    auto load_row = [&](const float *row, float *dst) {           // global row -> registers (zeros beyond dim)
+        chunks([&](auto r_, auto w_, auto o_) {
+            constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
 #pragma unroll
-    for (int r = 0; r < R; ++r)
+            for (int x = 0; x < CW; ++x) dst[RO + x] = 0.0f;
+            if (evalid[r]) load_vec<CW>(row + eoff[r], dst + RO);
+        });
+    };
+    auto store_row = [&](float *row, const float *src) {          // registers -> global row
+        chunks([&](auto r_, auto w_, auto o_) {
+            constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
+            if (evalid[r]) store_vec<CW>(row + eoff[r], src + RO);
+        });
+    };
+    auto ring_to_regs = [&](const float *lrow, float *dst) {      // LDS ring row -> registers
+        chunks([&](auto r_, auto w_, auto o_) {
+            constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
+            load_vec<CW>(lrow + eoff[r], dst + RO);
+        });
+    };
+    auto regs_to_ring = [&](float *lrow, const float *src) {      // registers -> LDS ring row
+        chunks([&](auto r_, auto w_, auto o_) {
+            constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
+            store_vec<CW>(lrow + eoff[r], src + RO);
+        });
+    };
+    {
+        float zero[E];
 #pragma unroll
-        for (int x = 0; x < VW; ++x) ring[(size_t)nslots * ROWF + eoff[r] + x] = 0.0f;
+        for (int x = 0; x < E; ++x) zero[x] = 0.0f;
+        regs_to_ring(ring + (size_t)nslots * ROWF, zero);
+    }
 
     double loss_acc = 0.0;
     unsigned long long pairs_acc = 0, dropped_acc = 0, kept_acc = 0;
-
-    auto load_row = [&](const float *row, float *dst) {           // global row -> registers (zeros beyond dim)
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-#pragma unroll
-            for (int x = 0; x < VW; ++x) dst[r * VW + x] = 0.0f;
-            if (evalid[r]) load_vec<VW>(row + eoff[r], dst + r * VW);
-        }
-    };
-    auto store_row = [&](float *row, const float *src) {          // registers -> global row
-#pragma unroll
-        for (int r = 0; r < R; ++r)
-            if (evalid[r]) store_vec<VW>(row + eoff[r], src + r * VW);
-    };
 
     for (;;) {
         // ---- next unit of work from the queue ---------------------------------------------------
@@ -369,12 +394,12 @@ train_kernel(KernelArgs A)
             if (!shared) {
                 const float *src = ring + (size_t)slot * ROWF;
                 float *dst = A.syn0 + (size_t)word * A.ld;
-#pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    float t[VW];
-                    load_vec<VW>(src + eoff[r], t);
-                    if (evalid[r]) store_vec<VW>(dst + eoff[r], t);
-                }
+                chunks([&](auto r_, auto w_, auto) {
+                    constexpr int r = decltype(r_)::value, CW = decltype(w_)::value;
+                    float t[CW];
+                    load_vec<CW>(src + eoff[r], t);
+                    if (evalid[r]) store_vec<CW>(dst + eoff[r], t);
+                });
                 give_slot(slot);
             }
         };
@@ -561,9 +586,7 @@ train_kernel(KernelArgs A)
                     if (ring_enter(n_ins, word, slot)) {
                         float t[E];
                         load_row(A.syn0 + (size_t)word * A.ld, t);
-                        float *dst = ring + (size_t)slot * ROWF;
-#pragma unroll
-                        for (int r = 0; r < R; ++r) store_vec<VW>(dst + eoff[r], t + r * VW);
+                        regs_to_ring(ring + (size_t)slot * ROWF, t);
                     }
                     ++n_ins;
                 }
@@ -631,13 +654,16 @@ train_kernel(KernelArgs A)
                 auto fetch_next_window = [&](auto &dst) {
                     if (has_next && !((uni(mraw_next.x) >> 19) & 1u)) {
                         if (lane_k == 0) packv_next = mraw_next.y | (1u << kIdBits);
+                        if (hand_over) {                            // one branch, two straight-line variants
+                            load_row(A.syn1neg + (size_t)(lane_value(packv_next, 0u) & kIdMask) * A.ld, dst[0]);
+                        } else {
 #pragma unroll
-                        for (int kk = 0; kk < KC; ++kk) {
-                            const uint32_t pk = lane_value(packv_next, (uint32_t)kk);
+                            for (int kk = 0; kk < KC; ++kk) {
+                                const uint32_t pk = lane_value(packv_next, (uint32_t)kk);
 #pragma unroll
-                            for (int x = 0; x < E; ++x) dst[kk][x] = 0.0f;
-                            if ((KFULL || (uint32_t)kk <= N) && (kk == 0 || !hand_over))
-                                load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, dst[kk]);
+                                for (int x = 0; x < E; ++x) dst[kk][x] = 0.0f;
+                                if (KFULL || (uint32_t)kk <= N) load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, dst[kk]);
+                            }
                         }
                     }
                 };
@@ -674,9 +700,7 @@ train_kernel(KernelArgs A)
                             const uint32_t p = (c & 1) ? i + a : i - a;
                             cslot[c] = lane_value(meta_slot, p & 63u);
                             if (!MASKED && !((amask_all >> c) & 1u)) cslot[c] = nslots;    // absent: the zero row
-                            const float *src = ring + (size_t)cslot[c] * ROWF;
-#pragma unroll
-                            for (int r = 0; r < R; ++r) load_vec<VW>(src + eoff[r], &I[c][r * VW]);
+                            ring_to_regs(ring + (size_t)cslot[c] * ROWF, I[c]);
                         }
                     };
                     if constexpr (!LOAD_PER_BLOCK) static_for<NCW>(fetch_slot);
@@ -771,48 +795,57 @@ train_kernel(KernelArgs A)
                                     float *dst = ring + (size_t)cslot[c] * ROWF;
                                     if (GENERAL && shared_rows) {
                                         // positions that share a ring row add up (LDS float add)
+                                        chunks([&](auto r_, auto w_, auto o_) {
+                                            constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
 #pragma unroll
-                                        for (int r = 0; r < R; ++r)
-#pragma unroll
-                                            for (int x = 0; x < VW; ++x)
-                                                __hip_atomic_fetch_add(dst + eoff[r] + x, dI[r * VW + x], __ATOMIC_RELAXED,
+                                            for (int x = 0; x < CW; ++x)
+                                                __hip_atomic_fetch_add(dst + eoff[r] + x, dI[RO + x], __ATOMIC_RELAXED,
                                                                        __HIP_MEMORY_SCOPE_WAVEFRONT);
+                                        });
                                     } else if (MULTI && kb) {
                                         // later output chunks: the row already carries the earlier chunks' deltas
+                                        chunks([&](auto r_, auto w_, auto o_) {
+                                            constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
+                                            float t[CW];
+                                            load_vec<CW>(dst + eoff[r], t);
 #pragma unroll
-                                        for (int r = 0; r < R; ++r) {
-                                            float t[VW];
-                                            load_vec<VW>(dst + eoff[r], t);
-#pragma unroll
-                                            for (int x = 0; x < VW; ++x) t[x] += dI[r * VW + x];
-                                            store_vec<VW>(dst + eoff[r], t);
-                                        }
+                                            for (int x = 0; x < CW; ++x) t[x] += dI[RO + x];
+                                            store_vec<CW>(dst + eoff[r], t);
+                                        });
                                     } else {
                                         // the row still equals the copy in registers: plain write of copy + delta
+                                        chunks([&](auto r_, auto w_, auto o_) {
+                                            constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
+                                            float t[CW];
 #pragma unroll
-                                        for (int r = 0; r < R; ++r) {
-                                            float t[VW];
-#pragma unroll
-                                            for (int x = 0; x < VW; ++x) t[x] = I[c][r * VW + x] + dI[r * VW + x];
-                                            store_vec<VW>(dst + eoff[r], t);
-                                        }
+                                            for (int x = 0; x < CW; ++x) t[x] = I[c][RO + x] + dI[RO + x];
+                                            store_vec<CW>(dst + eoff[r], t);
+                                        });
                                     }
                                 }
                             });
                         });
 
                         // (f) output rows go back (lock-free) once per window
+                        if (hand_over) {
+                            // the negatives' rows stay in registers for the next window (every row exists and
+                            // counts once in a window that hands over)
+                            float t[E];
 #pragma unroll
-                        for (int kk = 0; kk < KC; ++kk) {
-                            const uint32_t pk = lane_value(pv, (uint32_t)kk);
-                            if ((KEXACT || kb + kk <= N) && (!GENERAL || (pk >> kIdBits))) {
-                                float t[E];
+                            for (int x = 0; x < E; ++x) t[x] = OB[0][x] + dO[0][x];
+                            store_row(A.syn1neg + (size_t)(lane_value(pv, 0u) & kIdMask) * A.ld, t);
 #pragma unroll
-                                for (int x = 0; x < E; ++x) t[x] = OB[kk][x] + dO[kk][x];
-                                if (kk >= 1 && hand_over) {          // stays in registers for the next window
+                            for (int kk = 1; kk < KC; ++kk)
 #pragma unroll
-                                    for (int x = 0; x < E; ++x) OB[kk][x] = t[x];
-                                } else {
+                                for (int x = 0; x < E; ++x) OB[kk][x] += dO[kk][x];
+                        } else {
+#pragma unroll
+                            for (int kk = 0; kk < KC; ++kk) {
+                                const uint32_t pk = lane_value(pv, (uint32_t)kk);
+                                if ((KEXACT || kb + kk <= N) && (!GENERAL || (pk >> kIdBits))) {
+                                    float t[E];
+#pragma unroll
+                                    for (int x = 0; x < E; ++x) t[x] = OB[kk][x] + dO[kk][x];
                                     store_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, t);
                                 }
                             }
@@ -906,9 +939,7 @@ train_kernel(KernelArgs A)
                 // (h) the fetched context row enters the ring, the oldest position leaves it
                 //     (every lane only touches its own elements of a ring row: no barrier needed)
                 if (pend) {
-                    float *dst = ring + (size_t)pend_slot * ROWF;
-#pragma unroll
-                    for (int r = 0; r < R; ++r) store_vec<VW>(dst + eoff[r], pend_row + r * VW);
+                    regs_to_ring(ring + (size_t)pend_slot * ROWF, pend_row);
                 }
                 if (i >= W) ring_leave(i - W);
 
@@ -916,12 +947,17 @@ train_kernel(KernelArgs A)
                 if (has_next) {
                     mraw = mraw_next;
                     packv = packv_next;
+                    if constexpr (!TWO) {
+                        if (hand_over) {
 #pragma unroll
-                    for (int kk = 0; kk < KC; ++kk)
-                        if (!TWO && (kk == 0 || !hand_over)) {
+                            for (int x = 0; x < E; ++x) O[0][x] = On[0][x];
+                        } else {
 #pragma unroll
-                            for (int x = 0; x < E; ++x) O[kk][x] = On[kk][x];
+                            for (int kk = 0; kk < KC; ++kk)
+#pragma unroll
+                                for (int x = 0; x < E; ++x) O[kk][x] = On[kk][x];
                         }
+                    }
                 }
             }
             i0 += nwin;

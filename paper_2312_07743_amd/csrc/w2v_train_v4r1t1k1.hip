@@ -1,0 +1,9 @@
+// window kernel, rows of one chunk of 4 floats plus one single float per lane (dimensions 260..320 that are
+// multiples of 4), exactly 6 output rows per window
+#define W2V_VW 4
+#define W2V_R 1
+#define W2V_TAIL 1
+#define W2V_KMODE 1
+#define W2V_GUARDED_ONLY 1
+#define W2V_ENTRY train_fn_v4r1t1k1
+#include "w2v_train_inst.inc"
