@@ -188,6 +188,43 @@ template <int VW> __device__ __forceinline__ void store_vec(float *p, const floa
     else { *reinterpret_cast<float4 *>(p) = make_float4(src[0], src[1], src[2], src[3]); }
 }
 
+// Rows whose length does not fill the lanes' shares (dim < 64 * floats per lane) are reached through a buffer
+// resource per row, dim floats long: a lane whose share lies past the last column loads 0 and its stores are
+// dropped by the hardware's range check, so no lane needs a test of its own, and the lane's constant byte offset
+// is the only vector operand.  Whole rows use plain global accesses (measured faster for them).
+typedef unsigned int vec2u __attribute__((ext_vector_type(2)));
+typedef unsigned int vec4u __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t row_resource(const float *base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(base), 0, (int)bytes, 0x00020000);
+}
+template <int VW>
+__device__ __forceinline__ void row_load_vec(__amdgpu_buffer_rsrc_t rs, int lane_bytes, uint32_t row_bytes_off, float *dst)
+{
+    if constexpr (VW == 1) {
+        dst[0] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, lane_bytes, (int)row_bytes_off, 0));
+    } else if constexpr (VW == 2) {
+        const vec2u t = __builtin_amdgcn_raw_buffer_load_b64(rs, lane_bytes, (int)row_bytes_off, 0);
+        dst[0] = __uint_as_float(t.x); dst[1] = __uint_as_float(t.y);
+    } else {
+        const vec4u t = __builtin_amdgcn_raw_buffer_load_b128(rs, lane_bytes, (int)row_bytes_off, 0);
+        dst[0] = __uint_as_float(t.x); dst[1] = __uint_as_float(t.y); dst[2] = __uint_as_float(t.z); dst[3] = __uint_as_float(t.w);
+    }
+}
+template <int VW>
+__device__ __forceinline__ void row_store_vec(__amdgpu_buffer_rsrc_t rs, int lane_bytes, uint32_t row_bytes_off, const float *src)
+{
+    if constexpr (VW == 1) {
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(src[0]), rs, lane_bytes, (int)row_bytes_off, 0);
+    } else if constexpr (VW == 2) {
+        vec2u t; t.x = __float_as_uint(src[0]); t.y = __float_as_uint(src[1]);
+        __builtin_amdgcn_raw_buffer_store_b64(t, rs, lane_bytes, (int)row_bytes_off, 0);
+    } else {
+        vec4u t; t.x = __float_as_uint(src[0]); t.y = __float_as_uint(src[1]); t.z = __float_as_uint(src[2]); t.w = __float_as_uint(src[3]);
+        __builtin_amdgcn_raw_buffer_store_b128(t, rs, lane_bytes, (int)row_bytes_off, 0);
+    }
+}
+
 // learning rate of the sentence that starts at global token offset `start` of this epoch
 __device__ __forceinline__ float sentence_lr(const KernelArgs &A, uint64_t start)
 {
@@ -257,30 +294,49 @@ train_kernel(KernelArgs A)
               std::integral_constant<int, (r < R ? r * VW : R * VW + (r - R))>{});
         });
     };
-    // element offsets of this lane inside a row, and whether they exist (dim may not fill 64*E)
+    // element offsets of this lane inside a row (they may lie beyond dim: such elements are zero in registers and
+    // in the ring, and the bounds check of the row accesses keeps them out of memory)
     int eoff[NCH];
-    bool evalid[NCH];
 #pragma unroll
-    for (int r = 0; r < NCH; ++r) {
+    for (int r = 0; r < NCH; ++r)
         eoff[r] = r < R ? (r * kLanes + lane) * VW : kLanes * VW * R + (r - R) * kLanes + lane;
-        evalid[r] = FULL || (uint32_t)eoff[r] < A.dim;
-    }
     const int lane_c = lane / KC, lane_k = lane % KC;   // pairing handled by this lane after the reduction
 
-    auto load_row = [&](const float *row, float *dst) {           // global row -> registers (zeros beyond dim)
-        chunks([&](auto r_, auto w_, auto o_) {
-            constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
-#pragma unroll
-            for (int x = 0; x < CW; ++x) dst[RO + x] = 0.0f;
-            if (evalid[r]) load_vec<CW>(row + eoff[r], dst + RO);
-        });
+    const uint32_t row_bytes = A.dim * 4u;
+    // row `word` of a table -> registers (zeros beyond dim) / registers -> the row (nothing beyond dim)
+    auto load_row = [&](const float *table, uint32_t word, float *dst) {
+        const float *row = table + (size_t)word * A.ld;
+        if constexpr (FULL) {
+            chunks([&](auto r_, auto w_, auto o_) {
+                constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
+                load_vec<CW>(row + eoff[r], dst + RO);
+            });
+        } else {
+            const __amdgpu_buffer_rsrc_t rs = row_resource(row, row_bytes);
+            chunks([&](auto r_, auto w_, auto o_) {
+                constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
+                row_load_vec<CW>(rs, eoff[r] * 4, 0u, dst + RO);
+            });
+        }
     };
-    auto store_row = [&](float *row, const float *src) {          // registers -> global row
-        chunks([&](auto r_, auto w_, auto o_) {
-            constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
-            if (evalid[r]) store_vec<CW>(row + eoff[r], src + RO);
-        });
+    auto store_row = [&](float *table, uint32_t word, const float *src) {
+        float *row = table + (size_t)word * A.ld;
+        if constexpr (FULL) {
+            chunks([&](auto r_, auto w_, auto o_) {
+                constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
+                store_vec<CW>(row + eoff[r], src + RO);
+            });
+        } else {
+            const __amdgpu_buffer_rsrc_t rs = row_resource(row, row_bytes);
+            chunks([&](auto r_, auto w_, auto o_) {
+                constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
+                row_store_vec<CW>(rs, eoff[r] * 4, 0u, src + RO);
+            });
+        }
     };
+    auto load_ctx = [&](uint32_t word, float *dst) { load_row(A.syn0, word, dst); };
+    auto load_out = [&](uint32_t word, float *dst) { load_row(A.syn1neg, word, dst); };
+    auto store_out = [&](uint32_t word, const float *src) { store_row(A.syn1neg, word, src); };
     auto ring_to_regs = [&](const float *lrow, float *dst) {      // LDS ring row -> registers
         chunks([&](auto r_, auto w_, auto o_) {
             constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
@@ -392,14 +448,9 @@ train_kernel(KernelArgs A)
             if (lane == (int)l) meta_word = -1;
             const uint64_t shared = __ballot(meta_word >= 0 && meta_slot == slot);
             if (!shared) {
-                const float *src = ring + (size_t)slot * ROWF;
-                float *dst = A.syn0 + (size_t)word * A.ld;
-                chunks([&](auto r_, auto w_, auto) {
-                    constexpr int r = decltype(r_)::value, CW = decltype(w_)::value;
-                    float t[CW];
-                    load_vec<CW>(src + eoff[r], t);
-                    if (evalid[r]) store_vec<CW>(dst + eoff[r], t);
-                });
+                float t[E];
+                ring_to_regs(ring + (size_t)slot * ROWF, t);
+                store_row(A.syn0, (uint32_t)word, t);
                 give_slot(slot);
             }
         };
@@ -585,7 +636,7 @@ train_kernel(KernelArgs A)
                     uint32_t slot;
                     if (ring_enter(n_ins, word, slot)) {
                         float t[E];
-                        load_row(A.syn0 + (size_t)word * A.ld, t);
+                        load_ctx((uint32_t)word, t);
                         regs_to_ring(ring + (size_t)slot * ROWF, t);
                     }
                     ++n_ins;
@@ -605,7 +656,7 @@ train_kernel(KernelArgs A)
                 const uint32_t pk = lane_value(packv, (uint32_t)kk);
 #pragma unroll
                 for (int x = 0; x < E; ++x) O[kk][x] = 0.0f;
-                if (!first_idle && (KFULL || (uint32_t)kk <= N)) load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, O[kk]);
+                if (!first_idle && (KFULL || (uint32_t)kk <= N)) load_out(pk & kIdMask, O[kk]);
             }
 
             for (uint32_t j = 0; j < nwin; ++j) {
@@ -633,7 +684,7 @@ train_kernel(KernelArgs A)
                 float pend_row[E] = {};
                 if (enter_word != kNoWord) {
                     pend = ring_enter(n_ins, (int32_t)enter_word, pend_slot);
-                    if (pend) load_row(A.syn0 + (size_t)enter_word * A.ld, pend_row);
+                    if (pend) load_ctx(enter_word, pend_row);
                     ++n_ins;
                 }
 
@@ -654,15 +705,15 @@ train_kernel(KernelArgs A)
                 auto fetch_next_window = [&](auto &dst) {
                     if (has_next && !((uni(mraw_next.x) >> 19) & 1u)) {
                         if (lane_k == 0) packv_next = mraw_next.y | (1u << kIdBits);
-                        if (hand_over) {                            // one branch, two straight-line variants
-                            load_row(A.syn1neg + (size_t)(lane_value(packv_next, 0u) & kIdMask) * A.ld, dst[0]);
+                        if (hand_over) {                        // one branch, two straight-line variants
+                            load_out(lane_value(packv_next, 0u) & kIdMask, dst[0]);
                         } else {
 #pragma unroll
                             for (int kk = 0; kk < KC; ++kk) {
                                 const uint32_t pk = lane_value(packv_next, (uint32_t)kk);
 #pragma unroll
                                 for (int x = 0; x < E; ++x) dst[kk][x] = 0.0f;
-                                if (KFULL || (uint32_t)kk <= N) load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, dst[kk]);
+                                if (KFULL || (uint32_t)kk <= N) load_out(pk & kIdMask, dst[kk]);
                             }
                         }
                     }
@@ -833,7 +884,7 @@ train_kernel(KernelArgs A)
                             float t[E];
 #pragma unroll
                             for (int x = 0; x < E; ++x) t[x] = OB[0][x] + dO[0][x];
-                            store_row(A.syn1neg + (size_t)(lane_value(pv, 0u) & kIdMask) * A.ld, t);
+                            store_out(lane_value(pv, 0u) & kIdMask, t);
 #pragma unroll
                             for (int kk = 1; kk < KC; ++kk)
 #pragma unroll
@@ -846,7 +897,7 @@ train_kernel(KernelArgs A)
                                     float t[E];
 #pragma unroll
                                     for (int x = 0; x < E; ++x) t[x] = OB[kk][x] + dO[kk][x];
-                                    store_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, t);
+                                    store_out(pk & kIdMask, t);
                                 }
                             }
                         }
@@ -863,7 +914,7 @@ train_kernel(KernelArgs A)
                             const uint32_t pk = lane_value(pv2, (uint32_t)kk);
 #pragma unroll
                             for (int x = 0; x < E; ++x) On[kk][x] = 0.0f;
-                            if ((uint32_t)KC + kk <= N) load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, On[kk]);
+                            if ((uint32_t)KC + kk <= N) load_out(pk & kIdMask, On[kk]);
                         }
                         run_pass(0u, O, packv);
                         fetch_next_window(O);
@@ -879,7 +930,7 @@ train_kernel(KernelArgs A)
                                     const uint32_t pk = lane_value(pv, (uint32_t)kk);
 #pragma unroll
                                     for (int x = 0; x < E; ++x) O[kk][x] = 0.0f;
-                                    if (kb + kk <= N) load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, O[kk]);
+                                    if (kb + kk <= N) load_out(pk & kIdMask, O[kk]);
                                 }
                             }
                             run_pass(kb, O, pv);
@@ -931,7 +982,7 @@ train_kernel(KernelArgs A)
                         for (int kk = 0; kk < KC; ++kk)
                             if ((reload >> kk) & 1u) {
                                 const uint32_t pk = lane_value(packv_next, (uint32_t)kk);
-                                load_row(A.syn1neg + (size_t)(pk & kIdMask) * A.ld, TWO ? O[kk] : On[kk]);
+                                load_out(pk & kIdMask, TWO ? O[kk] : On[kk]);
                             }
                     }
                 }

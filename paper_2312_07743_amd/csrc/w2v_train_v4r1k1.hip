@@ -2,6 +2,6 @@
 #define W2V_VW 4
 #define W2V_R 1
 #define W2V_KMODE 1
-#define W2V_GUARDED_ONLY 0
+#define W2V_WHOLE_ROWS 1
 #define W2V_ENTRY train_fn_v4r1k1
 #include "w2v_train_inst.inc"

@@ -4,6 +4,6 @@
 #define W2V_R 1
 #define W2V_TAIL 1
 #define W2V_KMODE 0
-#define W2V_GUARDED_ONLY 1
+#define W2V_WHOLE_ROWS 0
 #define W2V_ENTRY train_fn_v4r1t1k0
 #include "w2v_train_inst.inc"
