@@ -72,7 +72,7 @@ std::string check_config(const w2v_config *c)
     if (!c->workspace) return "cfg.workspace is NULL";
     if (((uintptr_t)c->workspace & 255u) != 0) return "cfg.workspace must be 256-byte aligned";
     w2v::RowShape s;
-    if (!w2v::pick_row_shape(c->dim, c->ld, c->negatives, &s)) return "cfg.dim: no lane layout for this dimension";
+    if (!w2v::pick_row_shape(c->dim, c->ld, &s)) return "cfg.dim: no lane layout for this dimension";
     const uint32_t span = c->window_mode ? (c->window + 1u) / 2u : c->window;      // widest window that occurs
     if ((uint32_t)(64 * w2v::floats_per_lane(s)) * span > 512u * 10u)
         return "cfg.dim * cfg.window too large (rows of more than 320 floats need window <= 10)";

@@ -50,7 +50,7 @@ using TrainFn = void (*)(KernelArgs);
 // chunks of one float each (chunk t of lane l is float 64*VW*R + t*64 + l).
 struct RowShape { int vw, r, tail; };
 inline int floats_per_lane(RowShape s) { return s.vw * s.r + s.tail; }
-bool pick_row_shape(uint32_t dim, uint32_t ld, uint32_t negatives, RowShape *out);
+bool pick_row_shape(uint32_t dim, uint32_t ld, RowShape *out);
 
 // LDS bytes one wavefront (= one workgroup) of the window kernel needs.
 uint32_t train_lds_bytes(const KernelArgs &a, RowShape s);

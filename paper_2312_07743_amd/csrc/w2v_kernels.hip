@@ -123,16 +123,13 @@ TrainFn train_fn(const KernelArgs &a, RowShape s)
 // ---------------------------------------------------------------------------------------------
 // host side of the kernels
 // ---------------------------------------------------------------------------------------------
-bool pick_row_shape(uint32_t dim, uint32_t ld, uint32_t negatives, RowShape *out)
+bool pick_row_shape(uint32_t dim, uint32_t ld, RowShape *out)
 {
     // by floats per lane; a row of 260..320 floats is one 16-byte chunk plus one float per lane when its length
     // allows (a quarter of the memory instructions of five single floats)
     static const RowShape shapes[] = {{1, 1, 0}, {2, 1, 0}, {4, 1, 0}, {4, 1, 1}, {1, 5, 0}, {4, 2, 0}};
     for (const RowShape &s : shapes) {
         if ((uint32_t)(kLanes * floats_per_lane(s)) < dim) continue;
-        // 16-byte chunks need aligned groups of four registers; with two passes over the output rows (N > 5) the
-        // kernel has none to spare and single floats measured faster (Large prefix: 78 against 83 ms)
-        if (s.tail && negatives + 1u > (uint32_t)KC) continue;
         if (dim % s.vw || ld % s.vw) continue;
         *out = s;
         return true;
@@ -165,7 +162,7 @@ hipError_t launch_reset_accum(Accum *accum, int what, hipStream_t stream)
 uint32_t train_resident_waves(const KernelArgs &a, int device)
 {
     RowShape s;
-    if (!pick_row_shape(a.dim, a.ld, a.negatives, &s)) return 0;
+    if (!pick_row_shape(a.dim, a.ld, &s)) return 0;
     TrainFn fn = train_fn(a, s);
     if (!fn) return 0;
     int per_cu = 0, cus = 0;
@@ -177,7 +174,7 @@ uint32_t train_resident_waves(const KernelArgs &a, int device)
 hipError_t launch_train(const KernelArgs &a, uint32_t waves, hipStream_t stream)
 {
     RowShape s;
-    if (!pick_row_shape(a.dim, a.ld, a.negatives, &s)) return hipErrorInvalidValue;
+    if (!pick_row_shape(a.dim, a.ld, &s)) return hipErrorInvalidValue;
     TrainFn fn = train_fn(a, s);
     if (!fn) return hipErrorInvalidValue;
     hipLaunchKernelGGL(fn, dim3(waves), dim3(kLanes), train_lds_bytes(a, s), stream, a);
