@@ -2,8 +2,8 @@
 // the translation units that instantiate it (one per row shape, see w2v_train_inst.inc).
 //
 // Window kernel in one paragraph (paper Sections 3.1, 3.2, 4.2, re-mapped to CDNA4):
-// one wavefront owns one sentence at a time (work queue over sentences, lock-free between
-// sentences).  The 64 lanes split every embedding row; the N+1 output rows of a window
+// one wavefront owns one sentence, or one stretch of a long sentence, at a time (device work queue,
+// lock-free between wavefronts).  The 64 lanes split every embedding row; the N+1 output rows of a window
 // (target + shared negatives) sit in VGPRs while the window lasts, the context rows sit in an
 // LDS ring from the moment the window span reaches them until it has passed them.  All
 // (context, output) dot products of a window are formed as per-lane partial sums and reduced
@@ -250,6 +250,9 @@ __device__ __forceinline__ float sentence_lr(const KernelArgs &A, uint64_t start
 //   y = target word, z = word of the kept position that enters the ring at this window (or none)
 constexpr uint32_t kNoWord = 0xFFFFFFFFu;
 
+// VW, R, TAIL: a lane's share of a row (R chunks of VW floats, then TAIL single floats); WCAP: widest window of
+// the instantiation; FULL: the rows fill the shares exactly (dim = 64 * floats per lane), so rows are reached
+// with plain global accesses and no bounds check.
 // KMODE: how the N + 1 output rows of a window relate to the KC rows handled at a time:
 //   0: fewer than KC rows, 1: exactly KC rows (every row-exists test folds away), 2: up to 2 KC rows (two passes,
 //   each fetching the rows of the next while it computes), 3: more (further rows fetched when their pass begins)
