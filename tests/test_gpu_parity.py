@@ -184,6 +184,14 @@ def test_negative_block_draws_bit_exact(orc32):
     assert np.array_equal(keep, r["keep"]) and np.array_equal(width, r["width"]) and np.array_equal(neg, r["neg"])
 
 
+@pytest.mark.parametrize("dim,window,negatives", [(320, 16, 20), (299, 16, 7), (512, 10, 20), (1, 3, 2), (7, 16, 12),
+                                                  (260, 5, 11), (64, 16, 6)])
+def test_extreme_shapes(orc32, dim, window, negatives):
+    # largest rings and row counts the limits allow, row lengths at the edges of the lane layouts
+    c = synth.zipf_corpus(500, 1.0, 6, 250, seed=dim + window)
+    _parity(orc32, c, dim=dim, window=window, negatives=negatives, seed=4, table_size=50021, subsample_t=5e-2)
+
+
 def test_degenerate_sentences(orc32):
     # empty sentences, one-word sentences, sentences of invalid ids only, a long sentence (> one FIFO refill)
     rng = np.random.default_rng(3)
