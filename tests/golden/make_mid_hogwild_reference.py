@@ -4,7 +4,10 @@ clusters, 17M tokens, d=128, W=5, N=5, t=1e-4), two epochs, for three training s
 draw).  Calls only oracle/ and the input generator; takes about ten minutes on one core.
 
     python tests/golden/make_mid_hogwild_reference.py
+    python tests/golden/make_mid_hogwild_reference.py --negative-block 16     (one seed, writes
+        mid_hogwild_reference_nb16.json: the same with negatives shared by stretches of 16 tokens)
 """
+import argparse
 import json
 import os
 import sys
@@ -24,9 +27,18 @@ CORPUS = dict(vocab=71000, s=1.05, n_sent=17000, sent_len=1000, seed=1)
 
 
 def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--negative-block", type=int, default=0)
+    args = ap.parse_args()
+    global PARAMS, SEEDS
+    name = "mid_hogwild_reference.json"
+    if args.negative_block > 1:
+        PARAMS = dict(PARAMS, negative_block=args.negative_block)
+        SEEDS = SEEDS[:1]
+        name = f"mid_hogwild_reference_nb{args.negative_block}.json"
     orc = Oracle("float")
     c = synth.planted_corpus(**CORPUS)
-    path = os.path.join(HERE, "mid_hogwild_reference.json")
+    path = os.path.join(HERE, name)
     out = {"params": PARAMS, "corpus": CORPUS, "vocab": c.vocab, "tokens": c.n_tokens, "runs": []}
     if os.path.exists(path):                       # resume: keep the seeds that are already complete
         old = json.load(open(path))
@@ -42,7 +54,7 @@ def main():
             r = orc.train_epoch(syn0, syn1, c.counts, c.tokens, c.sent_off, window=PARAMS["window"],
                                 negatives=PARAMS["negatives"], seed=seed, epoch=e,
                                 total_epochs=PARAMS["epochs"], table_size=PARAMS["table_size"],
-                                subsample_t=PARAMS["subsample_t"])
+                                subsample_t=PARAMS["subsample_t"], negative_block=PARAMS.get("negative_block", 0))
             run["epochs"].append({"mean_loss": r["loss_sum"] / r["pairs"], "pairs": r["pairs"],
                                   "planted_score": planted_score(syn0, c.labels)})
             print(seed, e, run["epochs"][-1], f"{time.time() - t:.0f}s", flush=True)

@@ -60,6 +60,17 @@ def test_lock_free_run_matches_serial_oracle_statistically(mid, reference):
     """Every sentence in flight at once, two epochs, one run per stored training seed: pair counts are
     schedule-independent and must be exact; the final epoch's mean loss must be within 1 % of the serial
     oracle's, and the planted clusters must be recovered as well as the oracle recovers them."""
+    _lock_free_against(mid, reference)
+
+
+def test_lock_free_run_with_shared_negatives_matches_serial_oracle_statistically(mid):
+    """The same with cfg.negative_block = 16 against the oracle run with that option (stored by
+    tests/golden/make_mid_hogwild_reference.py --negative-block 16)."""
+    with open(os.path.join(HERE, "golden", "mid_hogwild_reference_nb16.json")) as f:
+        _lock_free_against(mid, json.load(f))
+
+
+def _lock_free_against(mid, reference):
     import torch
     from paper_2312_07743_amd.trainer import Trainer
     P = reference["params"]
@@ -67,7 +78,8 @@ def test_lock_free_run_matches_serial_oracle_statistically(mid, reference):
     for run in reference["runs"]:
         tr = Trainer(vocab=mid.vocab, dim=P["dim"], window=P["window"], negatives=P["negatives"], counts=mid.counts,
                      tokens_per_epoch=mid.n_tokens, seed=run["seed"], table_size=P["table_size"],
-                     subsample_t=P["subsample_t"], total_epochs=P["epochs"], sentences_in_flight=0)
+                     subsample_t=P["subsample_t"], total_epochs=P["epochs"], sentences_in_flight=0,
+                     negative_block=P.get("negative_block", 0))
         tr.set_corpus(mid.tokens, mid.sent_off)
         losses, kept, invalid = [], 0, 0
         for e in range(P["epochs"]):
