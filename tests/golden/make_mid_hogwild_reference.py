@@ -6,6 +6,8 @@ draw).  Calls only oracle/ and the input generator; takes about ten minutes on o
     python tests/golden/make_mid_hogwild_reference.py
     python tests/golden/make_mid_hogwild_reference.py --negative-block 16     (one seed, writes
         mid_hogwild_reference_nb16.json: the same with negatives shared by stretches of 16 tokens)
+    python tests/golden/make_mid_hogwild_reference.py --fixed-width           (one seed, writes
+        mid_hogwild_reference_fixed_width.json: every window has width ceil(W/2))
 """
 import argparse
 import json
@@ -29,6 +31,7 @@ CORPUS = dict(vocab=71000, s=1.05, n_sent=17000, sent_len=1000, seed=1)
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--negative-block", type=int, default=0)
+    ap.add_argument("--fixed-width", action="store_true")
     args = ap.parse_args()
     global PARAMS, SEEDS
     name = "mid_hogwild_reference.json"
@@ -36,6 +39,10 @@ def main():
         PARAMS = dict(PARAMS, negative_block=args.negative_block)
         SEEDS = SEEDS[:1]
         name = f"mid_hogwild_reference_nb{args.negative_block}.json"
+    elif args.fixed_width:
+        PARAMS = dict(PARAMS, window_mode=1)
+        SEEDS = SEEDS[:1]
+        name = "mid_hogwild_reference_fixed_width.json"
     orc = Oracle("float")
     c = synth.planted_corpus(**CORPUS)
     path = os.path.join(HERE, name)
@@ -54,7 +61,8 @@ def main():
             r = orc.train_epoch(syn0, syn1, c.counts, c.tokens, c.sent_off, window=PARAMS["window"],
                                 negatives=PARAMS["negatives"], seed=seed, epoch=e,
                                 total_epochs=PARAMS["epochs"], table_size=PARAMS["table_size"],
-                                subsample_t=PARAMS["subsample_t"], negative_block=PARAMS.get("negative_block", 0))
+                                subsample_t=PARAMS["subsample_t"], negative_block=PARAMS.get("negative_block", 0),
+                                window_mode=PARAMS.get("window_mode", 0))
             run["epochs"].append({"mean_loss": r["loss_sum"] / r["pairs"], "pairs": r["pairs"],
                                   "planted_score": planted_score(syn0, c.labels)})
             print(seed, e, run["epochs"][-1], f"{time.time() - t:.0f}s", flush=True)

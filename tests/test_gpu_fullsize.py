@@ -70,6 +70,12 @@ def test_lock_free_run_with_shared_negatives_matches_serial_oracle_statistically
         _lock_free_against(mid, json.load(f))
 
 
+def test_lock_free_run_with_fixed_width_matches_serial_oracle_statistically(mid):
+    """The same with window_mode = 1 (width ceil(W/2), the paper's own variant) against the oracle run in that mode."""
+    with open(os.path.join(HERE, "golden", "mid_hogwild_reference_fixed_width.json")) as f:
+        _lock_free_against(mid, json.load(f))
+
+
 def _lock_free_against(mid, reference):
     import torch
     from paper_2312_07743_amd.trainer import Trainer
@@ -79,7 +85,7 @@ def _lock_free_against(mid, reference):
         tr = Trainer(vocab=mid.vocab, dim=P["dim"], window=P["window"], negatives=P["negatives"], counts=mid.counts,
                      tokens_per_epoch=mid.n_tokens, seed=run["seed"], table_size=P["table_size"],
                      subsample_t=P["subsample_t"], total_epochs=P["epochs"], sentences_in_flight=0,
-                     negative_block=P.get("negative_block", 0))
+                     negative_block=P.get("negative_block", 0), window_mode=P.get("window_mode", 0))
         tr.set_corpus(mid.tokens, mid.sent_off)
         losses, kept, invalid = [], 0, 0
         for e in range(P["epochs"]):
