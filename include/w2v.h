@@ -155,7 +155,7 @@ int w2v_debug_draws(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_t *sen
 /* Test surface: fixes the granularity of the work queue.  w2v_train_epoch hands a sentence out as
  * 2^unit_shift stretches of its tokens (each reads the W kept tokens on either side as context
  * only, so the windows are those of the whole sentence); by default the library picks the
- * exponent from the sizes of the call (0 when one wavefront runs alone).  unit_shift in [0, 10]
+ * exponent from the sizes of the call (0 when one wavefront runs alone).  unit_shift in [0, 16]
  * fixes it, -1 restores the default. */
 int w2v_debug_set_units(w2v_ctx *ctx, int unit_shift);
 

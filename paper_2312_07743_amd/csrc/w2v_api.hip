@@ -149,7 +149,7 @@ uint32_t pick_unit_shift(const w2v_ctx *ctx, uint64_t n_sent, uint64_t n_tokens,
     uint32_t shift = 0;
     if (ctx->forced_unit_shift >= 0) return (uint32_t)ctx->forced_unit_shift;
     if (waves <= 1 || n_sent == 0) return 0;
-    while (shift < 10 && (n_sent << shift) < 16u * waves && (n_tokens / n_sent) >> (shift + 1) >= 128u) ++shift;
+    while (shift < 16 && (n_sent << shift) < 16u * waves && (n_tokens / n_sent) >> (shift + 1) >= 128u) ++shift;
     return shift;
 }
 
@@ -441,7 +441,7 @@ int w2v_debug_draws(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_t *sen
 int w2v_debug_set_units(w2v_ctx *ctx, int unit_shift)
 {
     if (!ctx) return fail(nullptr, W2V_EINVAL, "ctx is NULL");
-    if (unit_shift < -1 || unit_shift > 10) return fail(ctx, W2V_EINVAL, "unit_shift must be -1 (automatic) or 0..10");
+    if (unit_shift < -1 || unit_shift > 16) return fail(ctx, W2V_EINVAL, "unit_shift must be -1 (automatic) or 0..16");
     ctx->forced_unit_shift = unit_shift;
     return W2V_OK;
 }

@@ -117,7 +117,7 @@ def test_fixed_width_sizes_the_ring_by_the_fixed_width(orc32):
     _parity(orc32, c, dim=512, window=16, negatives=4, seed=5, window_mode=1, table_size=50021)
 
 
-@pytest.mark.parametrize("unit_shift", [1, 2, 3, 6])
+@pytest.mark.parametrize("unit_shift", [1, 2, 3, 6, 12])
 def test_sentences_cut_into_units_of_work(orc32, unit_shift):
     """A sentence handed out as 2^k stretches (each with its lead-in and lead-out context) must train exactly
     the windows of the whole sentence: one wavefront taking the units in order reproduces the oracle."""
