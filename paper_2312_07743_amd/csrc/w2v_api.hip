@@ -122,16 +122,12 @@ int check_train_call(w2v_ctx *ctx, const int32_t *tokens, const uint64_t *sent_o
     if (!ctx->table_built) return fail(ctx, W2V_ESTATE, "w2v_build_unigram_table must be called first");
     if (epoch >= ctx->cfg.total_epochs) return fail(ctx, W2V_EINVAL, "epoch must be < cfg.total_epochs");
     if (first_pos > ctx->cfg.tokens_per_epoch) return fail(ctx, W2V_EINVAL, "first_token_global_pos exceeds cfg.tokens_per_epoch");
-    if (n_sent && (!tokens || !sent_off)) return fail(ctx, W2V_EINVAL, "tokens_dev / sent_off_dev is NULL");
+    if (n_sent && (!tokens || !sent_off)) return fail(ctx, W2V_EINVAL, "tokens / sent_off is NULL");
     return W2V_OK;
 }
 
 hipStream_t stream_of(const w2v_ctx *ctx) { return static_cast<hipStream_t>(ctx->cfg.stream); }
 
-// Into how many units (a power of two, as its exponent) each sentence is cut for the work queue: enough units
-// that the wavefronts finish within a small fraction of the launch of one another (a wavefront holds a unit
-// until it is done), but units of at least 128 tokens on average, since every unit re-reads the few tokens
-// of context on either side.  One wavefront (strict order) gains nothing from a finer queue.
 // Wavefronts for cfg.sentences_in_flight = 0: all the GPU holds, but no more than one per 4,096 tokens of the
 // epoch.  Every wavefront trains on copies of the rows it touches and the last writer of a row wins, so with
 // too many of them at work on a small corpus most updates of the frequent rows are lost (measured: a 3M-token
@@ -144,6 +140,10 @@ uint64_t lock_free_waves(const w2v_ctx *ctx, uint64_t resident)
     return resident < cap ? resident : cap;
 }
 
+// Into how many units (a power of two, as its exponent) each sentence is cut for the work queue: enough units
+// that the wavefronts finish within a small fraction of the launch of one another (a wavefront holds a unit
+// until it is done), but units of at least 128 tokens on average, since every unit re-reads the few tokens
+// of context on either side.  One wavefront (strict order) gains nothing from a finer queue.
 uint32_t pick_unit_shift(const w2v_ctx *ctx, uint64_t n_sent, uint64_t n_tokens, uint64_t waves)
 {
     uint32_t shift = 0;
