@@ -258,9 +258,10 @@ constexpr uint32_t kNoWord = 0xFFFFFFFFu;
 //   each fetching the rows of the next while it computes), 3: more (further rows fetched when their pass begins)
 
 // wavefronts per SIMD the register allocator is asked to make room for (512 VGPRs per lane in all)
-// (e: floats of a row per lane, wcap: widest window of the instantiation; measured: 4 per SIMD is no faster
-// than 3 for short rows because LDS then limits the CU, and 3 for rows of 4 floats per lane spills)
-constexpr int occupancy_goal(int e, int wcap) { return (e <= 2 && wcap <= 10) ? 3 : ((e * wcap <= 25) ? 2 : 1); }
+// (e: floats of a row per lane, wcap: widest window of the instantiation; measured: rows of one float per lane
+// gain 17 % from 4 per SIMD (128 VGPRs, 16 spilled), 5 spills 56; rows of two floats gain nothing from 4
+// because LDS then limits the CU; 3 for rows of 4 floats per lane spills)
+constexpr int occupancy_goal(int e, int wcap) { return (e == 1 && wcap <= 5) ? 4 : (e <= 2 && wcap <= 10) ? 3 : ((e * wcap <= 25) ? 2 : 1); }
 
 template <int VW, int R, int TAIL, int WCAP, bool FULL, int KMODE>
 __global__ void __launch_bounds__(kLanes) __attribute__((amdgpu_waves_per_eu(occupancy_goal(VW * R + TAIL, WCAP))))
