@@ -192,6 +192,24 @@ def test_extreme_shapes(orc32, dim, window, negatives):
     _parity(orc32, c, dim=dim, window=window, negatives=negatives, seed=4, table_size=50021, subsample_t=5e-2)
 
 
+def test_degenerate_vocabularies_and_schedules(orc32):
+    # one word: every negative equals the target (all masked) and every context word is the target's own word
+    tok = np.zeros(300, np.int32)
+    c1 = synth.Corpus(tok, np.array([0, 100, 300], np.uint64), np.array([300], np.uint64))
+    _parity(orc32, c1, dim=64, window=3, negatives=4, seed=1, table_size=17)
+    # two words, one of them never sampled as a negative (count 0 owns no table slot)
+    tok = np.array([0, 1] * 200, np.int32)
+    c2 = synth.Corpus(tok, np.array([0, 400], np.uint64), np.array([400, 0], np.uint64))
+    _parity(orc32, c2, dim=128, window=5, negatives=5, seed=2, table_size=64)
+    # only invalid ids: nothing is trained, nothing is written
+    c3 = synth.Corpus(np.full(500, -7, np.int32), np.array([0, 250, 500], np.uint64), np.array([1, 1, 1], np.uint64))
+    _parity(orc32, c3, dim=128, window=5, negatives=5, seed=3, table_size=64)
+    # the last epoch of a long schedule: the learning rate sits on its floor for the later sentences
+    c4 = synth.zipf_corpus(300, 1.0, 8, 300, seed=6)
+    _parity(orc32, c4, dim=128, window=5, negatives=5, seed=4, table_size=4099, epochs=1, start_epoch=9, total_epochs=10,
+            lr0=0.05)
+
+
 def test_degenerate_sentences(orc32):
     # empty sentences, one-word sentences, sentences of invalid ids only, a long sentence (> one FIFO refill)
     rng = np.random.default_rng(3)
