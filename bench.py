@@ -147,6 +147,7 @@ def main():
     copy_gbs = 5 * 2 * a.numel() * 4 / (c0.elapsed_time(c1) * 1e-3) / 1e9
     del a, b
 
+    props = torch.cuda.get_device_properties(0)
     out = {
         "metric": "trained words/sec on 1 MI355X; achieved HBM GB/s vs peak",
         "value": words / wall, "unit": "words/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -161,7 +162,9 @@ def main():
                                + (f", corpus fed from pinned host memory in batches of {args.staging_mb // 2} MiB"
                                   if args.from_host else ""),
                    "kept_words_per_s": kept / wall, "kept_fraction": kept / words,
-                   "mean_loss": loss_sum / max(pairs, 1), "sentences_in_flight": args.in_flight},
+                   "mean_loss": loss_sum / max(pairs, 1), "sentences_in_flight": args.in_flight,
+                   "device": f"{props.name}, {props.multi_processor_count} CUs, "
+                             f"{props.total_memory / 2**30:.0f} GiB"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "kernel": "naive_kernel" if args.naive else "train_kernel", "avg_launch_ms": avg_kernel_s * 1e3,
