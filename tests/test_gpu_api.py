@@ -74,3 +74,41 @@ def test_embeddings_to_device_loss_reset_and_counters():
     tr.train_epoch(1)
     assert tr.loss()[1] > 0
     tr.close()
+
+
+def test_two_contexts_on_their_own_streams_do_not_disturb_each_other():
+    """Two trainers with different shapes, each on a stream of its own, epochs issued alternately: each must end
+    exactly where it ends when it runs alone (strict order makes a run deterministic)."""
+    from paper_2312_07743_amd.trainer import Trainer
+    ca = synth.zipf_corpus(300, 1.0, 6, 400, seed=1)
+    cb = synth.zipf_corpus(500, 1.1, 5, 300, seed=2)
+
+    def make(c, dim, window, negatives, stream):
+        with torch.cuda.stream(stream):
+            tr = Trainer(vocab=c.vocab, dim=dim, window=window, negatives=negatives, counts=c.counts,
+                         tokens_per_epoch=c.n_tokens, seed=9, table_size=1 << 14, subsample_t=1e-2, total_epochs=2,
+                         sentences_in_flight=1)
+            tr.set_corpus(c.tokens, c.sent_off)
+        return tr
+
+    def run_alone(c, dim, window, negatives):
+        tr = make(c, dim, window, negatives, torch.cuda.current_stream())
+        for e in range(2):
+            tr.train_epoch(e)
+        out = tr.embeddings(0), tr.embeddings(1), tr.loss()
+        tr.close()
+        return out
+
+    want_a, want_b = run_alone(ca, 128, 5, 5), run_alone(cb, 300, 3, 8)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    ta, tb = make(ca, 128, 5, 5, sa), make(cb, 300, 3, 8, sb)
+    for e in range(2):
+        ta.train_epoch(e)
+        tb.train_epoch(e)
+    got_a = ta.embeddings(0), ta.embeddings(1), ta.loss()
+    got_b = tb.embeddings(0), tb.embeddings(1), tb.loss()
+    ta.close()
+    tb.close()
+    for got, want in ((got_a, want_a), (got_b, want_b)):
+        assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1]) and got[2] == want[2]
+    torch.cuda.synchronize()
