@@ -47,6 +47,9 @@ def main():
     ap.add_argument("--negative-block", type=int, default=0,
                     help="reuse of negatives over the windows centred in one stretch of this many tokens (an extension "
                          "the paper names as future work; 0 = the paper's fresh negatives per window)")
+    ap.add_argument("--full-size", action="store_true",
+                    help="large / graph at their whole size (800M tokens; the corpus alone takes minutes to generate) "
+                         "instead of the prefix")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--naive", action="store_true",
                     help="time the no-reuse comparator kernel instead of the window kernel (traffic comparison only)")
@@ -73,8 +76,15 @@ def main():
     from paper_2312_07743_amd.trainer import Trainer
 
     gen_kw, dim, window, negatives, t_sub, table_size = WORKLOADS[args.workload]
+    gen_kw = dict(gen_kw)
     if args.dim:
         dim = args.dim
+    if args.full_size:
+        if args.workload == "large":
+            gen_kw["n_sent"] = 800000
+        elif args.workload == "graph":
+            gen_kw["walks_per_node"] = 10
+        gen_kw["progress"] = lambda text: print(text, file=sys.stderr, flush=True)
     if args.workload == "graph":
         corpus = synth.barabasi_albert_walks(**gen_kw)
         what = f"Barabasi-Albert graph ({gen_kw['n_nodes']} nodes, m={gen_kw['m']}), uniform walks of {gen_kw['walk_len']}"

@@ -56,7 +56,7 @@ def zipf_corpus(vocab: int, s: float, n_sent: int, sent_len: int, seed: int) -> 
 def planted_corpus(vocab: int = 71000, s: float = 1.05, n_sent: int = 17000, sent_len: int = 1000,
                    seed: int = 1, n_clusters: int = 16, cluster_size: int = 50,
                    band_start: int = 2000, burst_p: float = 0.02, burst_len: int = 8,
-                   min_count: int = 5) -> Corpus:
+                   min_count: int = 5, progress=None) -> Corpus:
     """'Mid': Zipf(s) text with planted co-occurrence clusters.
 
     n_clusters*cluster_size words are taken from the rank band starting at
@@ -65,11 +65,18 @@ def planted_corpus(vocab: int = 71000, s: float = 1.05, n_sent: int = 17000, sen
     burst_len consecutive tokens drawn uniformly from one cluster.  Words with
     fewer than min_count occurrences are then removed and ids re-numbered in
     rank order (the rule of Table 3's caption); sentences keep their boundaries.
+    `progress`, if given, is called with a short text after each stage (large corpora take minutes).
     """
+    say = progress or (lambda text: None)
     rng = np.random.Generator(np.random.PCG64(seed))
     cdf = _zipf_cdf(vocab, s)
     T = n_sent * sent_len
-    tok = np.searchsorted(cdf, rng.random(T), side="right").astype(np.int32)
+    tok = np.empty(T, np.int32)
+    step = 1 << 25                      # the uniform draws are consumed in order, so pieces give the same ids
+    for a in range(0, T, step):
+        b = min(T, a + step)
+        tok[a:b] = np.searchsorted(cdf, rng.random(b - a), side="right")
+        say(f"corpus: {b} of {T} Zipf ids drawn")
     np.minimum(tok, vocab - 1, out=tok)
     n_planted = n_clusters * cluster_size
     assert band_start + n_planted <= vocab
@@ -85,6 +92,7 @@ def planted_corpus(vocab: int = 71000, s: float = 1.05, n_sent: int = 17000, sen
         pos = starts + j
         ok = (pos // sent_len) == (starts // sent_len)            # stay inside the sentence
         tok[pos[ok]] = members[which[ok], picks[ok, j]]
+    say("corpus: bursts planted")
     counts_full = np.bincount(tok, minlength=vocab)
     keep_word = counts_full >= min_count
     remap = np.cumsum(keep_word) - 1
@@ -96,6 +104,7 @@ def planted_corpus(vocab: int = 71000, s: float = 1.05, n_sent: int = 17000, sen
     sent_off[1:] = np.cumsum(lens).astype(np.uint64)
     counts = counts_full[keep_word].astype(np.uint64)
     labels = labels_full[keep_word]
+    say("corpus: rare words removed, ids renumbered")
     return Corpus(new_tok, sent_off, counts, labels)
 
 
@@ -111,10 +120,12 @@ def disjoint_slice_corpus(vocab: int, n_sent: int, sent_len: int, seed: int) -> 
     return Corpus(tok, _uniform_offsets(n_sent, sent_len), counts)
 
 
-def barabasi_albert_walks(n_nodes: int, m: int, walks_per_node: int, walk_len: int, seed: int) -> Corpus:
+def barabasi_albert_walks(n_nodes: int, m: int, walks_per_node: int, walk_len: int, seed: int,
+                          progress=None) -> Corpus:
     """'Graph': uniform random walks on a seeded Barabasi-Albert graph; node id = word id.
     The graph is grown with the repeated-endpoint list (a node is picked with probability
     proportional to its degree by picking a uniform entry of the list of edge endpoints)."""
+    say = progress or (lambda text: None)
     rng = np.random.Generator(np.random.PCG64(seed))
     assert n_nodes > m >= 1
     src = np.empty((n_nodes - m) * m, np.int64)
@@ -135,6 +146,7 @@ def barabasi_albert_walks(n_nodes: int, m: int, walks_per_node: int, walk_len: i
             endpoints[n_end + 1] = t
             n_end += 2
             e += 1
+    say("graph: grown")
     a = np.concatenate([src, dst])
     b = np.concatenate([dst, src])
     order = np.argsort(a, kind="stable")
@@ -151,6 +163,8 @@ def barabasi_albert_walks(n_nodes: int, m: int, walks_per_node: int, walk_len: i
         nxt = b[rowptr[cur] + (r * deg[cur]).astype(np.int64)]
         walks[:, step] = nxt
         cur = nxt
+        if step % 8 == 0:
+            say(f"graph: step {step} of {walk_len} of {n_walks} walks")
     tok = walks.reshape(-1)
     counts = np.bincount(tok, minlength=n_nodes).astype(np.uint64)
     return Corpus(tok, _uniform_offsets(n_walks, walk_len), counts)
