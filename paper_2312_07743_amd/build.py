@@ -9,7 +9,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libw2v.so")
 SOURCES = ["w2v_api.hip", "w2v_kernels.hip", "w2v_naive.hip"] + [
-    f"w2v_train_v{shape}k{k}.hip" for shape in ("2r1", "4r1t1", "1r5", "4r2", "4r1", "1r1") for k in (1, 2, 3, 0)]
+    f"w2v_train_v{shape}k{k}.hip" for shape in ("2r1", "4r1t1", "4r1t4", "1r5", "4r2", "4r1", "1r1") for k in (1, 2, 3, 0)]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -87,6 +87,10 @@ TrainFn train_fn_v4r1t1k0(uint32_t window, bool full);
 TrainFn train_fn_v4r1t1k1(uint32_t window, bool full);
 TrainFn train_fn_v4r1t1k2(uint32_t window, bool full);
 TrainFn train_fn_v4r1t1k3(uint32_t window, bool full);
+TrainFn train_fn_v4r1t4k0(uint32_t window, bool full);
+TrainFn train_fn_v4r1t4k1(uint32_t window, bool full);
+TrainFn train_fn_v4r1t4k2(uint32_t window, bool full);
+TrainFn train_fn_v4r1t4k3(uint32_t window, bool full);
 TrainFn train_fn_v1r5k0(uint32_t window, bool full);
 TrainFn train_fn_v1r5k1(uint32_t window, bool full);
 TrainFn train_fn_v1r5k2(uint32_t window, bool full);
@@ -110,6 +114,9 @@ TrainFn train_fn(const KernelArgs &a, RowShape s)
     if (s.vw == 4 && s.r == 1 && s.tail == 1)
         return kmode == 3 ? train_fn_v4r1t1k3(a.window, full) : kmode == 2 ? train_fn_v4r1t1k2(a.window, full)
              : kmode == 1 ? train_fn_v4r1t1k1(a.window, full) : train_fn_v4r1t1k0(a.window, full);
+    if (s.vw == 4 && s.r == 1 && s.tail == 4)
+        return kmode == 3 ? train_fn_v4r1t4k3(a.window, full) : kmode == 2 ? train_fn_v4r1t4k2(a.window, full)
+             : kmode == 1 ? train_fn_v4r1t4k1(a.window, full) : train_fn_v4r1t4k0(a.window, full);
     W2V_PICK(1, 1)
     W2V_PICK(2, 1)
     W2V_PICK(4, 1)
@@ -126,11 +133,14 @@ TrainFn train_fn(const KernelArgs &a, RowShape s)
 bool pick_row_shape(uint32_t dim, uint32_t ld, RowShape *out)
 {
     // by floats per lane; a row of 260..320 floats is one 16-byte chunk plus one float per lane when its length
-    // allows (a quarter of the memory instructions of five single floats)
-    static const RowShape shapes[] = {{1, 1, 0}, {2, 1, 0}, {4, 1, 0}, {4, 1, 1}, {1, 5, 0}, {4, 2, 0}};
+    // allows (a quarter of the memory instructions of five single floats).  A chunk of several floats is
+    // range-checked as a whole, so it must not straddle the end of a row: the length is a multiple of the
+    // chunk, or (shapes with single floats behind the chunks) the chunks end inside the row.
+    static const RowShape shapes[] = {{1, 1, 0}, {2, 1, 0}, {4, 1, 0}, {4, 1, 1}, {1, 5, 0}, {4, 2, 0}, {4, 1, 4}};
     for (const RowShape &s : shapes) {
         if ((uint32_t)(kLanes * floats_per_lane(s)) < dim) continue;
-        if (dim % s.vw || ld % s.vw) continue;
+        const bool chunks_inside = s.tail > 1 && dim >= (uint32_t)(kLanes * s.vw * s.r);
+        if ((dim % s.vw && !chunks_inside) || ld % s.vw) continue;
         *out = s;
         return true;
     }

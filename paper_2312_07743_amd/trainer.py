@@ -39,6 +39,9 @@ class Trainer:
 
     def set_corpus(self, tokens, sent_off):
         self.tokens = torch.as_tensor(np.ascontiguousarray(tokens, np.int32)).to(self.dev)
+        self.n_tokens = int(self.tokens.numel())
+        if self.n_tokens == 0:                  # only empty sentences: the library still wants a pointer
+            self.tokens = torch.zeros(1, dtype=torch.int32, device=self.dev)
         # torch has no uint64 arithmetic, but the bytes are all the library needs
         self.sent_off = torch.as_tensor(np.ascontiguousarray(sent_off, np.uint64).view(np.int64)).to(self.dev)
         self.n_sent = len(sent_off) - 1
@@ -69,7 +72,7 @@ class Trainer:
         return out
 
     def draws(self, epoch=0, first_token_global_pos=0):
-        T = int(self.tokens.numel())
+        T = self.n_tokens
         keep = torch.zeros(T, dtype=torch.uint8, device=self.dev)
         width = torch.zeros(T, dtype=torch.uint8, device=self.dev)
         neg = torch.zeros((T, max(self.negatives, 1)), dtype=torch.int32, device=self.dev)

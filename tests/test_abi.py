@@ -67,7 +67,7 @@ def _good_cfg(**over):
     dict(total_epochs=0), dict(tokens_per_epoch=0), dict(lr0=0.0),
     dict(lr0=float("nan")), dict(lr_min_frac=1.5), dict(subsample_t=-1.0), dict(syn0=None), dict(syn1neg=None),
     dict(ld=127), dict(ld=64), dict(ld=130), dict(workspace=None), dict(workspace=0x10001), dict(device=-1),
-    dict(dim=512, ld=512, window=11), dict(dim=321, ld=324),
+    dict(dim=512, ld=512, window=11), dict(dim=321, ld=352, window=11),
 ])
 def test_create_rejects_bad_config_without_touching_the_gpu(over):
     ctx = C.c_void_p(None)

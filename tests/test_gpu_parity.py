@@ -185,7 +185,7 @@ def test_negative_block_draws_bit_exact(orc32):
 
 
 @pytest.mark.parametrize("dim,window,negatives", [(320, 16, 20), (299, 16, 7), (512, 10, 20), (1, 3, 2), (7, 16, 12),
-                                                  (260, 5, 11), (64, 16, 6)])
+                                                  (260, 5, 11), (64, 16, 6), (321, 10, 5), (511, 7, 13), (450, 5, 20)])
 def test_extreme_shapes(orc32, dim, window, negatives):
     # largest rings and row counts the limits allow, row lengths at the edges of the lane layouts
     c = synth.zipf_corpus(500, 1.0, 6, 250, seed=dim + window)
