@@ -43,7 +43,7 @@ def main():
                     help="window_mode 1: every window has width ceil(W/2) (the paper's own variant, Section 3.2)")
     ap.add_argument("--from-host", action="store_true",
                     help="feed the corpus from pinned host memory through w2v_train_epoch_host (PCIe-inclusive rate)")
-    ap.add_argument("--staging-mb", type=int, default=32)
+    ap.add_argument("--staging-mb", type=int, default=128)
     ap.add_argument("--negative-block", type=int, default=0,
                     help="reuse of negatives over the windows centred in one stretch of this many tokens (an extension "
                          "the paper names as future work; 0 = the paper's fresh negatives per window)")
@@ -114,9 +114,12 @@ def main():
     stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    host_s = 0.0                                 # time the calls themselves take on the host (they only queue work)
     for k in range(args.steps):
         starts[k].record()                       # torch's current stream is the one the library launches on
+        h0 = time.perf_counter()
         run_epoch(args.warmup + k)
+        host_s += time.perf_counter() - h0
         stops[k].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -174,6 +177,7 @@ def main():
                                   if args.from_host else ""),
                    "kept_words_per_s": kept / wall, "kept_fraction": kept / words,
                    "mean_loss": loss_sum / max(pairs, 1), "sentences_in_flight": args.in_flight,
+                   "host_ms_per_step_inside_the_calls": host_s / args.steps * 1e3,
                    "device": f"{props.name}, {props.multi_processor_count} CUs, "
                              f"{props.total_memory / 2**30:.0f} GiB"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

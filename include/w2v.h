@@ -116,9 +116,14 @@ int w2v_train_epoch(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_t *sen
  * context owns, so transfers hide behind the kernel.  Every random draw and the learning rate are
  * keyed by global token positions, so the result equals that of w2v_train_epoch on a resident copy
  * (bit for bit with sentences_in_flight = 1).  Returns when the last batch has been queued on the
- * context's stream: the host arrays must stay valid until that stream has been synchronised (pinned
+ * context's stream (the call itself waits until all but the last two batches have been trained): the host arrays must stay valid until that stream has been synchronised (pinned
  * host memory gives truly asynchronous copies, pageable memory works and blocks this call while
- * each batch is staged).  W2V_EINVAL if a sentence does not fit half of the staging buffer. */
+ * each batch is staged).  Every batch is a launch of its own, whose last wavefronts leave part of
+ * the GPU idle: large halves keep that loss small (17M tokens per epoch: 9.95 ms with 64 MiB
+ * halves, 10.4 ms with 16 MiB, 13.3 ms with 4 MiB; 9.5 ms resident).  The sentences are spread
+ * over as few batches as fit, of nearly equal size, and the halves alternate across calls, so the
+ * first batch of an epoch is copied while the previous epoch still trains.
+ * W2V_EINVAL if a sentence does not fit half of the staging buffer. */
 int w2v_train_epoch_host(w2v_ctx *ctx, const int32_t *tokens_host, const uint64_t *sent_off_host,
                          uint64_t n_sent, uint64_t first_token_global_pos, uint32_t epoch,
                          void *staging_dev, uint64_t staging_bytes);
@@ -158,6 +163,13 @@ int w2v_debug_draws(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_t *sen
  * exponent from the sizes of the call (0 when one wavefront runs alone).  unit_shift in [0, 16]
  * fixes it, -1 restores the default. */
 int w2v_debug_set_units(w2v_ctx *ctx, int unit_shift);
+
+/* Test surface: fixes how the work queue ends.  By default lock-free launches cut the last eighth of
+ * their sentences into smaller stretches than the rest, so that the wavefronts finish close
+ * together.  fine_shift in [0, 16]: the sentences from index coarse_sentences on (all of them if
+ * it is 0, none if it is >= n_sent) are handed out as 2^fine_shift stretches each, the ones before
+ * as w2v_debug_set_units or the default says; fine_shift = -1 restores the default. */
+int w2v_debug_set_unit_tail(w2v_ctx *ctx, int fine_shift, uint64_t coarse_sentences);
 
 /* Test surface: runs the window kernel's cross-lane reduction on its own.  in_dev: device
  * float[60*64], value m of lane l at in_dev[m*64 + l]; out_dev: device float[64], out_dev[l] =

@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libw2v.so")
 EXPORTS = ["w2v_query_ld", "w2v_query_workspace", "w2v_create", "w2v_destroy", "w2v_build_unigram_table",
            "w2v_train_epoch", "w2v_train_epoch_host", "w2v_train_epoch_naive", "w2v_get_embeddings", "w2v_loss", "w2v_counters", "w2v_debug_draws",
-           "w2v_debug_set_units", "w2v_debug_reduce", "w2v_last_error"]
+           "w2v_debug_set_units", "w2v_debug_set_unit_tail", "w2v_debug_reduce", "w2v_last_error"]
 
 
 class W2VConfig(C.Structure):
@@ -60,6 +60,7 @@ def lib():
         L.w2v_debug_draws.argtypes = [vp, vp, vp, u64, u64, u32, vp, vp, vp]
         L.w2v_debug_reduce.argtypes = [vp, vp, vp]
         L.w2v_debug_set_units.argtypes = [vp, i32]
+        L.w2v_debug_set_unit_tail.argtypes = [vp, i32, u64]
         L.w2v_last_error.argtypes = [vp]
         L.w2v_last_error.restype = C.c_char_p
         for n in EXPORTS:
@@ -145,6 +146,10 @@ def w2v_train_epoch_naive(ctx, tokens_dev, sent_off_dev, n_sent, first_token_glo
 
 def w2v_debug_set_units(ctx, unit_shift):
     _check(lib().w2v_debug_set_units(ctx, int(unit_shift)), ctx)
+
+
+def w2v_debug_set_unit_tail(ctx, fine_shift, coarse_sentences):
+    _check(lib().w2v_debug_set_unit_tail(ctx, int(fine_shift), int(coarse_sentences)), ctx)
 
 
 def w2v_get_embeddings(ctx, which, dst, dst_floats, dst_is_device):

@@ -39,6 +39,8 @@ struct KernelArgs {
     uint32_t           vocab, dim, ld, window, negatives, window_mode, table_size;
     uint32_t           subsample;      // 0: every threshold is "always keep", thr is not read
     uint32_t           unit_shift;     // a sentence is handed out as 2^unit_shift units of work (window kernel only)
+    uint32_t           fine_shift;     // ... the sentences from coarse_sent on as 2^fine_shift units each (the end of
+    uint64_t           coarse_sent;    //     the queue is cut finer, so that the wavefronts finish close together)
     uint32_t           neg_shift;      // 0: negatives drawn at each window's own position; s: at the first position
                                        // of the stretch of 2^s tokens (offsets in the sentence) the centre lies in
 };
@@ -76,6 +78,8 @@ struct w2v_ctx {
     uint32_t             table_size = 0;
     bool                 table_built = false;
     int                  forced_unit_shift = -1;   // test override of the work-queue granularity (-1: automatic)
+    int                  forced_fine_shift = -1;   // test override of the granularity of the queue's end (-1: automatic)
+    uint64_t             forced_coarse_sent = 0;   // ... and of the sentence it begins with
     std::string          err;
     // host-fed training (created on first use): copy stream, and per staging half an event for "filled"
     // (recorded on the copy stream) and one for "trained, may be refilled" (recorded on the caller's stream)
@@ -83,4 +87,6 @@ struct w2v_ctx {
     hipEvent_t           filled[2] = {nullptr, nullptr};
     hipEvent_t           drained[2] = {nullptr, nullptr};
     bool                 drained_recorded[2] = {false, false};
+    uint64_t             resident_waves = 0; // wavefronts of the window kernel the device holds (0: not asked yet)
+    int                  next_half = 0;      // staging half the next batch goes to (alternates across calls too)
 };

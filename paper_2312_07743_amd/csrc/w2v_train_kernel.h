@@ -365,21 +365,26 @@ train_kernel(KernelArgs A)
 
     for (;;) {
         // ---- next unit of work from the queue ---------------------------------------------------
-        // A unit is one of 2^unit_shift equal stretches of a sentence's tokens.  Its windows are those of the
+        // A unit is one of 2^shift equal stretches of a sentence's tokens.  Its windows are those of the
         // kept tokens inside the stretch; the W kept tokens before it and after it are read as context only,
         // so the windows are exactly those the whole sentence has (units of one sentence that run at the same
         // time race like any two sentences do; one wavefront taking all units in order reproduces strict order).
         unsigned long long q_raw = 0;
         if (lane == 0) q_raw = atomicAdd(&A.accum->next_sentence, 1ull);
         const uint64_t q = uni64(q_raw);
-        if (q >= (A.n_sent << A.unit_shift)) break;
-        const uint64_t s = q >> A.unit_shift;
+        // (sentences from A.coarse_sent on are cut into 2^fine_shift stretches instead: the queue ends in small units)
+        const uint64_t n_coarse = A.coarse_sent << A.unit_shift;
+        if (q >= n_coarse + ((A.n_sent - A.coarse_sent) << A.fine_shift)) break;
+        const bool fine = q >= n_coarse;
+        const uint32_t shift = fine ? A.fine_shift : A.unit_shift;
+        const uint64_t qs = fine ? q - n_coarse : q;                 // index among the units of its own kind
+        const uint64_t s = (fine ? A.coarse_sent : 0ull) + (qs >> shift);
         const uint64_t t0 = uni64(A.sent_off[s]);
         const uint64_t t1 = uni64(A.sent_off[s + 1]);
         const uint32_t len = (t1 > t0) ? (uint32_t)(t1 - t0) : 0u;
         const float alpha = sentence_lr(A, A.first_pos + t0);
-        const uint32_t unit_len = (uint32_t)(((uint64_t)len + (1u << A.unit_shift) - 1u) >> A.unit_shift);
-        const uint64_t u0_64 = (q & ((1ull << A.unit_shift) - 1ull)) * unit_len;
+        const uint32_t unit_len = (uint32_t)(((uint64_t)len + (1u << shift) - 1u) >> shift);
+        const uint64_t u0_64 = (qs & ((1ull << shift) - 1ull)) * unit_len;
         const uint32_t u0 = u0_64 < len ? (uint32_t)u0_64 : len;                  // the unit's tokens: [u0, u1)
         const uint32_t u1 = (len - u0 > unit_len) ? u0 + unit_len : len;
         if (u0 >= u1) continue;

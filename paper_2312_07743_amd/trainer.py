@@ -51,7 +51,7 @@ class Trainer:
         f = B.w2v_train_epoch_naive if naive else B.w2v_train_epoch
         f(self.ctx, self.tokens, self.sent_off, self.n_sent, first_token_global_pos, epoch)
 
-    def train_epoch_from_host(self, tokens, sent_off, epoch=0, first_token_global_pos=0, staging_bytes=32 << 20):
+    def train_epoch_from_host(self, tokens, sent_off, epoch=0, first_token_global_pos=0, staging_bytes=128 << 20):
         """tokens / sent_off: host arrays (numpy int32 / uint64, or pinned torch tensors of the same bytes); they
         are cut into batches that are copied into a device staging buffer while the previous batch trains."""
         if getattr(self, "staging", None) is None or self.staging.numel() != staging_bytes:

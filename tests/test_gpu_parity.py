@@ -133,6 +133,28 @@ def test_sentences_cut_into_units_of_work(orc32, unit_shift):
                 unit_shift=unit_shift)
 
 
+@pytest.mark.parametrize("unit_shift,fine_shift,coarse", [(None, 3, 5), (1, 4, 9), (2, 0, 3), (0, 6, 0), (3, 5, 12),
+                                                         (1, 2, 100)])
+def test_queue_that_ends_in_smaller_units(orc32, unit_shift, fine_shift, coarse):
+    """The sentences from index `coarse` on are cut into 2^fine_shift stretches, the ones before into 2^unit_shift
+    (what lock-free launches do with their last sentences so that the wavefronts finish together): in strict
+    order the result is still the oracle's."""
+    rng = np.random.default_rng(14)
+    lens = [300, 0, 1, 700, 2, 64, 65, 129, 0, 500, 5, 999]
+    tok = rng.integers(0, 200, size=sum(lens)).astype(np.int32)
+    tok[[3, 1500]] = 7777
+    off = np.cumsum([0] + lens).astype(np.uint64)
+    c = synth.Corpus(tok, off, np.bincount(tok[tok < 200], minlength=200).astype(np.uint64))
+    for t, window, block in ((0.0, 5, 0), (3e-2, 10, 0), (3e-2, 5, 8)):
+        g = run_gpu(c, sentences_in_flight=1, unit_shift=unit_shift, unit_tail=(fine_shift, coarse), dim=128,
+                    window=window, negatives=5, seed=19, subsample_t=t, table_size=50021, negative_block=block)
+        r = run_oracle(orc32, c, dim=128, window=window, negatives=5, seed=19, subsample_t=t, table_size=50021,
+                       negative_block=block)
+        assert g[3] == r[3] and abs(g[2] - r[2]) <= 2e-5 * abs(r[2])
+        assert_rows_close(g[0], r[0], 1e-4, "syn0")
+        assert_rows_close(g[1], r[1], 1e-4, "syn1neg")
+
+
 def test_units_do_not_change_counters():
     from paper_2312_07743_amd.trainer import Trainer
     c = synth.planted_corpus(vocab=3000, n_sent=40, sent_len=777, seed=5, band_start=200, n_clusters=4,
@@ -258,10 +280,11 @@ def test_second_epoch_and_split_feeding(orc32):
 
 def test_disjoint_vocabulary_slices_run_concurrently_without_conflicts(orc32):
     # every sentence owns its words and N = 0: no two wavefronts touch the same row, so full
-    # concurrency must reproduce the serial oracle
+    # concurrency must reproduce the serial oracle (whole sentences as units of work: stretches of one
+    # sentence share its words)
     c = synth.disjoint_slice_corpus(vocab=6400, n_sent=640, sent_len=150, seed=4)
     kw = dict(dim=128, window=5, negatives=0, seed=6, table_size=1 << 14)
-    g0, g1, gl, gp = run_gpu(c, sentences_in_flight=0, **kw)
+    g0, g1, gl, gp = run_gpu(c, sentences_in_flight=0, unit_shift=0, **kw)
     r0, r1, rl, rp = run_oracle(orc32, c, **kw)
     assert gp == rp and abs(gl - rl) <= 2e-5 * rl
     assert_rows_close(g0, r0, 1e-4, "syn0")

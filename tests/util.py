@@ -24,7 +24,8 @@ def run_oracle(orc, corpus, *, dim, window, negatives, seed, epochs=1, table_siz
 
 def run_gpu(corpus, *, dim, window, negatives, seed, epochs=1, table_size=1 << 16, subsample_t=0.0, window_mode=0,
             lr0=0.025, sentences_in_flight=0, syn0=None, syn1neg=None, first_token_global_pos=0,
-            tokens_per_epoch=None, total_epochs=None, start_epoch=0, naive=False, unit_shift=None, negative_block=0):
+            tokens_per_epoch=None, total_epochs=None, start_epoch=0, naive=False, unit_shift=None, negative_block=0,
+            unit_tail=None):
     from paper_2312_07743_amd import binding
     from paper_2312_07743_amd.trainer import Trainer
     tr = Trainer(vocab=corpus.vocab, dim=dim, window=window, negatives=negatives, counts=corpus.counts,
@@ -34,6 +35,8 @@ def run_gpu(corpus, *, dim, window, negatives, seed, epochs=1, table_size=1 << 1
     tr.set_corpus(corpus.tokens, corpus.sent_off)
     if unit_shift is not None:
         binding.w2v_debug_set_units(tr.ctx, unit_shift)
+    if unit_tail is not None:                      # (fine_shift, first sentence cut that finely)
+        binding.w2v_debug_set_unit_tail(tr.ctx, *unit_tail)
     for e in range(start_epoch, start_epoch + epochs):
         tr.train_epoch(e, first_token_global_pos, naive=naive)
     loss, pairs = tr.loss()
