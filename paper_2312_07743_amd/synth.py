@@ -120,13 +120,11 @@ def disjoint_slice_corpus(vocab: int, n_sent: int, sent_len: int, seed: int) -> 
     return Corpus(tok, _uniform_offsets(n_sent, sent_len), counts)
 
 
-def barabasi_albert_walks(n_nodes: int, m: int, walks_per_node: int, walk_len: int, seed: int,
-                          progress=None) -> Corpus:
-    """'Graph': uniform random walks on a seeded Barabasi-Albert graph; node id = word id.
+def barabasi_albert_graph(n_nodes: int, m: int, rng, progress=None):
+    """Seeded Barabasi-Albert graph in CSR form (rowptr int64[n+1], neighbours int64[2E], degrees int64[n]).
     The graph is grown with the repeated-endpoint list (a node is picked with probability
     proportional to its degree by picking a uniform entry of the list of edge endpoints)."""
     say = progress or (lambda text: None)
-    rng = np.random.Generator(np.random.PCG64(seed))
     assert n_nodes > m >= 1
     src = np.empty((n_nodes - m) * m, np.int64)
     dst = np.empty((n_nodes - m) * m, np.int64)
@@ -154,6 +152,15 @@ def barabasi_albert_walks(n_nodes: int, m: int, walks_per_node: int, walk_len: i
     deg = np.bincount(a, minlength=n_nodes)
     rowptr = np.zeros(n_nodes + 1, np.int64)
     rowptr[1:] = np.cumsum(deg)
+    return rowptr, b, deg
+
+
+def barabasi_albert_walks(n_nodes: int, m: int, walks_per_node: int, walk_len: int, seed: int,
+                          progress=None) -> Corpus:
+    """'Graph': uniform random walks on a seeded Barabasi-Albert graph; node id = word id."""
+    say = progress or (lambda text: None)
+    rng = np.random.Generator(np.random.PCG64(seed))
+    rowptr, b, deg = barabasi_albert_graph(n_nodes, m, rng, progress)
     n_walks = n_nodes * walks_per_node
     cur = np.tile(np.arange(n_nodes, dtype=np.int64), walks_per_node)
     walks = np.empty((n_walks, walk_len), np.int32)

@@ -38,12 +38,18 @@ class Trainer:
         self.n_sent = 0
 
     def set_corpus(self, tokens, sent_off):
-        self.tokens = torch.as_tensor(np.ascontiguousarray(tokens, np.int32)).to(self.dev)
+        """tokens: int32 word ids; sent_off: S+1 offsets (numpy uint64, or int64 tensor of the same bytes).  numpy
+        arrays are copied to the device, device tensors are used where they are."""
+        if isinstance(tokens, torch.Tensor):
+            assert tokens.dtype == torch.int32 and sent_off.dtype == torch.int64 and tokens.is_contiguous()
+            self.tokens, self.sent_off = tokens.to(self.dev), sent_off.to(self.dev)
+        else:
+            self.tokens = torch.as_tensor(np.ascontiguousarray(tokens, np.int32)).to(self.dev)
+            # torch has no uint64 arithmetic, but the bytes are all the library needs
+            self.sent_off = torch.as_tensor(np.ascontiguousarray(sent_off, np.uint64).view(np.int64)).to(self.dev)
         self.n_tokens = int(self.tokens.numel())
         if self.n_tokens == 0:                  # only empty sentences: the library still wants a pointer
             self.tokens = torch.zeros(1, dtype=torch.int32, device=self.dev)
-        # torch has no uint64 arithmetic, but the bytes are all the library needs
-        self.sent_off = torch.as_tensor(np.ascontiguousarray(sent_off, np.uint64).view(np.int64)).to(self.dev)
         self.n_sent = len(sent_off) - 1
         torch.cuda.synchronize(self.dev)
 

@@ -157,6 +157,62 @@ def test_counts_and_sampled_decisions_on_the_big_shapes(orc32, shape):
             assert list(neg[t]) == [orc32.negative(end, tsz, seed, 0, first + t, j) for j in range(P["negatives"])]
 
 
+@pytest.mark.parametrize("shape", ["large", "graph"])
+def test_whole_800m_token_epoch_counts_and_sampled_decisions(orc32, shape):
+    """configs[3] and configs[4] at their whole size (800M tokens; the corpus is generated in device memory), one
+    lock-free epoch in the launch configuration of the benchmark: the counters must equal what the integer
+    decisions of all 800M tokens imply, the decisions must be the oracle's at sampled positions, and the tables
+    must stay finite."""
+    import torch
+    from paper_2312_07743_amd import binding as B
+    from paper_2312_07743_amd import synth_device
+    from paper_2312_07743_amd.trainer import Trainer
+    if shape == "large":
+        V, L, S = 550000, 1000, 800000
+        tok, counts = synth_device.zipf_tokens(V, 1.1, S * L, seed=1)
+        P = dict(dim=300, window=5, negatives=10, subsample_t=1e-5)
+    else:
+        V, L, S = 1000000, 80, 10000000
+        tok, counts = synth_device.barabasi_albert_walk_tokens(V, 5, 10, L, seed=1)
+        P = dict(dim=128, window=10, negatives=5, subsample_t=0.0)
+    T, N, seed, tsz = S * L, P["negatives"], 77, 1 << 24
+    off = torch.arange(S + 1, dtype=torch.int64, device="cuda") * L
+    tr = Trainer(vocab=V, counts=counts, tokens_per_epoch=T, seed=seed, table_size=tsz, total_epochs=1, **P)
+    tr.set_corpus(tok, off)
+    keep = torch.empty(T, dtype=torch.uint8, device="cuda")
+    width = torch.empty(T, dtype=torch.uint8, device="cuda")
+    neg = torch.empty((T, N), dtype=torch.int32, device="cuda")
+    B.w2v_debug_draws(tr.ctx, tok, off, S, 0, 0, keep, width, neg)
+    tr.train_epoch(0)
+    kept, invalid = tr.counters()
+    loss, pairs = tr.loss()
+    assert invalid == 0 and kept == int(keep.sum(dtype=torch.int64))
+    # pairs from the decisions: the window of the i-th of a sentence's n kept tokens, width b, has
+    # min(b, i) + min(b, n-1-i) context words
+    k = keep.view(S, L) != 0
+    rank = torch.cumsum(k, dim=1, dtype=torch.int32) - 1
+    n = rank[:, -1:] + 1
+    b = width.view(S, L).to(torch.int32)
+    contrib = (torch.minimum(b, rank) + torch.minimum(b, n - 1 - rank)) * k
+    assert pairs == int(contrib.sum(dtype=torch.int64))
+    del rank, b, contrib, k
+    assert bool(torch.isfinite(tr.syn0).all()) and bool(torch.isfinite(tr.syn1neg).all())
+    assert 0.0 < loss / pairs < (N + 1) * np.log(2.0) * 1.05
+    thr = orc32.thresholds(counts, P["subsample_t"])
+    end = orc32.table_ends(counts, tsz)
+    at = torch.as_tensor(np.concatenate([np.random.default_rng(1).integers(0, T, size=1500), [0, T - 1]]), device="cuda")
+    words, keeps, widths, negs = tok[at].cpu().numpy(), keep[at].cpu().numpy(), width[at].cpu().numpy(), neg[at].cpu().numpy()
+    tr.close()
+    for t, w, kk, bb, nn in zip(at.cpu().numpy(), words, keeps, widths, negs):
+        t = int(t)
+        want = orc32.keep(thr, int(w), seed, 0, t)
+        assert kk == want
+        if want:
+            assert bb == orc32.width(P["window"], 0, seed, 0, t)
+            assert list(nn) == [orc32.negative(end, tsz, seed, 0, t, j) for j in range(N)]
+    torch.cuda.empty_cache()
+
+
 def test_default_concurrency_learns_on_a_small_corpus():
     """sentences_in_flight = 0 on a 3M-token corpus: the library must not put more wavefronts to work than the
     corpus can feed without losing most updates (measured before the cap: planted score 0.56 after five epochs,
