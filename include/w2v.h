@@ -53,9 +53,10 @@ typedef struct w2v_config {
     uint32_t window_mode;         /* 0: width of each window drawn uniformly from [1,W] (Sec. 3.2,
                                      "traditional"); 1: fixed width ceil(W/2) (Sec. 3.2, the paper's) */
     uint32_t total_epochs;        /* E >= 1, length of the learning-rate decay                          */
-    uint32_t sentences_in_flight; /* 0: as many wavefronts at once as the GPU holds, but at most one per 4,096
-                                     tokens of the epoch and at least 64 (lock-free, Sec. 2.2: too many on a
-                                     small corpus lose most updates of the frequent rows);
+    uint32_t sentences_in_flight; /* 0: as many wavefronts at once as the GPU holds, but at most one per
+                                     2,048 * (N+1)/6 tokens that survive subsampling in an epoch, and at
+                                     least 64 (lock-free, Sec. 2.2: too many on a small corpus lose most
+                                     updates of the frequent rows);
                                      k >= 1: exactly at most k at once; 1 = strict corpus order, deterministic */
     uint64_t tokens_per_epoch;    /* T >= 1, corpus tokens per epoch before subsampling                 */
     uint64_t seed;                /* keys every random decision and the weight initialisation          */

@@ -130,14 +130,18 @@ int check_train_call(w2v_ctx *ctx, const int32_t *tokens, const uint64_t *sent_o
 
 hipStream_t stream_of(const w2v_ctx *ctx) { return static_cast<hipStream_t>(ctx->cfg.stream); }
 
-// Wavefronts for cfg.sentences_in_flight = 0: all the GPU holds, but no more than one per 4,096 tokens of the
-// epoch.  Every wavefront trains on copies of the rows it touches and the last writer of a row wins, so with
-// too many of them at work on a small corpus most updates of the frequent rows are lost (measured: a 3M-token
-// corpus on 3,000 wavefronts reaches planted-cluster score 0.56 in five epochs, on 730 it reaches 1.00; a
-// 0.6M-token corpus on 2,400 wavefronts does not learn at all).  The 17M-token corpus keeps every wavefront.
+// Wavefronts for cfg.sentences_in_flight = 0: all the GPU holds, but no more than one per 2,048 * (N+1)/6 kept
+// tokens of the epoch (one per 2,048 with five negatives).  Every wavefront trains on copies of the rows it touches and the last writer of a row wins:
+// the chance that an update of a row is lost grows with the number of rows in flight, wavefronts x (N+1) output
+// rows, while the updates a row gets per epoch grow with the tokens that survive subsampling.  Measured: a 3M-token
+// corpus (N=5, half the tokens kept) on 3,000 wavefronts reaches planted-cluster score 0.56 in five epochs, on 730
+// it reaches 1.00; a 0.6M-token corpus on 2,400 wavefronts does not learn at all; 9.5M tokens of which 30 % are
+// kept, N=10, on 1,536 wavefronts: score 0.67 after two epochs, on 512: 1.00.  The 17M-token corpus (N=5) keeps
+// every wavefront.
 uint64_t lock_free_waves(const w2v_ctx *ctx, uint64_t resident)
 {
-    uint64_t cap = ctx->cfg.tokens_per_epoch / 4096u;
+    const double kept = (double)ctx->cfg.tokens_per_epoch * ctx->kept_fraction;
+    uint64_t cap = (uint64_t)(kept * 6.0 / (2048.0 * (double)(ctx->cfg.negatives + 1u)));
     if (cap < 64u) cap = 64u;
     return resident < cap ? resident : cap;
 }
@@ -285,6 +289,7 @@ int w2v_build_unigram_table(w2v_ctx *ctx, const uint64_t *counts_host, uint32_t 
     // keep probability min(1, sqrt(t / f)), f = count / total, as a 32-bit threshold
     std::vector<uint32_t> thr(V, 0xFFFFFFFFu);
     const double t = ctx->cfg.subsample_t;
+    double kept_c = total_c;                       // expected count of the tokens that survive subsampling
     if (t > 0.0) {
         for (uint32_t i = 0; i < V; ++i) {
             if (counts_host[i] == 0) continue;
@@ -293,8 +298,10 @@ int w2v_build_unigram_table(w2v_ctx *ctx, const uint64_t *counts_host, uint32_t 
             if (p >= 1.0) continue;
             const double q = std::floor(p * 4294967296.0);
             thr[i] = q >= 4294967295.0 ? 0xFFFFFFFFu : (uint32_t)q;
+            kept_c -= (1.0 - p) * (double)counts_host[i];
         }
     }
+    ctx->kept_fraction = kept_c / total_c;
 
     unsigned char *ws = static_cast<unsigned char *>(ctx->cfg.workspace);
     HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));

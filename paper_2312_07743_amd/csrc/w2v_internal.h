@@ -87,6 +87,7 @@ struct w2v_ctx {
     hipEvent_t           filled[2] = {nullptr, nullptr};
     hipEvent_t           drained[2] = {nullptr, nullptr};
     bool                 drained_recorded[2] = {false, false};
+    double               kept_fraction = 1.0;  // expected share of the tokens that survive subsampling (from the counts)
     uint64_t             resident_waves = 0; // wavefronts of the window kernel the device holds (0: not asked yet)
     int                  next_half = 0;      // staging half the next batch goes to (alternates across calls too)
 };

@@ -8,6 +8,9 @@ draw).  Calls only oracle/ and the input generator; takes about ten minutes on o
         mid_hogwild_reference_nb16.json: the same with negatives shared by stretches of 16 tokens)
     python tests/golden/make_mid_hogwild_reference.py --fixed-width           (one seed, writes
         mid_hogwild_reference_fixed_width.json: every window has width ceil(W/2))
+    python tests/golden/make_mid_hogwild_reference.py --large-shape           (one seed, writes
+        large_shape_hogwild_reference.json: the hyper-parameters of the 'Large' workload, d=300, N=10, t=1e-5, on
+        6,000 sentences of its Zipf(1.1) text with planted clusters, four epochs; about twenty minutes)
 """
 import argparse
 import json
@@ -32,8 +35,9 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--negative-block", type=int, default=0)
     ap.add_argument("--fixed-width", action="store_true")
+    ap.add_argument("--large-shape", action="store_true")
     args = ap.parse_args()
-    global PARAMS, SEEDS
+    global PARAMS, SEEDS, CORPUS
     name = "mid_hogwild_reference.json"
     if args.negative_block > 1:
         PARAMS = dict(PARAMS, negative_block=args.negative_block)
@@ -43,6 +47,11 @@ def main():
         PARAMS = dict(PARAMS, window_mode=1)
         SEEDS = SEEDS[:1]
         name = "mid_hogwild_reference_fixed_width.json"
+    elif args.large_shape:
+        PARAMS = dict(dim=300, window=5, negatives=10, table_size=1 << 24, subsample_t=1e-5, epochs=4)
+        CORPUS = dict(vocab=550000, s=1.1, n_sent=6000, sent_len=1000, seed=1)
+        SEEDS = SEEDS[:1]
+        name = "large_shape_hogwild_reference.json"
     orc = Oracle("float")
     c = synth.planted_corpus(**CORPUS)
     path = os.path.join(HERE, name)

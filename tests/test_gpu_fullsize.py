@@ -76,7 +76,19 @@ def test_lock_free_run_with_fixed_width_matches_serial_oracle_statistically(mid)
         _lock_free_against(mid, json.load(f))
 
 
-def _lock_free_against(mid, reference):
+def test_lock_free_run_with_the_large_shape_matches_serial_oracle_statistically():
+    """d=300, N=10, t=1e-5 (configs[3]'s hyper-parameters; 30 % of the tokens survive subsampling) on a 5.7M-token
+    corpus of its law, four epochs, default concurrency: fewer kept tokens and more output rows per window make
+    lost updates matter more than on the 17M-token corpus, and the library's own limit on the wavefronts at work
+    must keep the run within 1 % of the serial oracle (stored by make_mid_hogwild_reference.py --large-shape)."""
+    with open(os.path.join(HERE, "golden", "large_shape_hogwild_reference.json")) as f:
+        ref = json.load(f)
+    c = synth.planted_corpus(**ref["corpus"])
+    assert c.vocab == ref["vocab"] and c.n_tokens == ref["tokens"]
+    _lock_free_against(c, ref, kept_share=(0.20, 0.40))
+
+
+def _lock_free_against(mid, reference, kept_share=(0.45, 0.56)):
     import torch
     from paper_2312_07743_amd.trainer import Trainer
     P = reference["params"]
@@ -95,7 +107,7 @@ def _lock_free_against(mid, reference):
             loss, pairs = tr.loss(reset=True)
             assert pairs == run["epochs"][e]["pairs"]
             losses.append(loss / pairs)
-        assert invalid == 0 and 0.45 * mid.n_tokens * P["epochs"] < kept < 0.56 * mid.n_tokens * P["epochs"]
+        assert invalid == 0 and kept_share[0] * mid.n_tokens * P["epochs"] < kept < kept_share[1] * mid.n_tokens * P["epochs"]
         emb = tr.embeddings(0)
         tr.close()
         assert np.isfinite(emb).all()
