@@ -50,6 +50,9 @@ def main():
     ap.add_argument("--full-size", action="store_true",
                     help="large / graph at their whole size (800M tokens; the corpus alone takes minutes to generate) "
                          "instead of the prefix")
+    ap.add_argument("--coherent-tables", action="store_true",
+                    help="keep syn0 / syn1neg in uncached device memory (wavefronts on different XCDs see each other's "
+                         "updates at once; for walk corpora)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--naive", action="store_true",
                     help="time the no-reuse comparator kernel instead of the window kernel (traffic comparison only)")
@@ -94,7 +97,8 @@ def main():
     E = args.warmup + args.steps
     tr = Trainer(vocab=corpus.vocab, dim=dim, window=window, negatives=negatives, counts=corpus.counts,
                  tokens_per_epoch=corpus.n_tokens, seed=2024, table_size=table_size, subsample_t=t_sub,
-                 total_epochs=E, sentences_in_flight=args.in_flight, window_mode=1 if args.fixed_width else 0, negative_block=args.negative_block)
+                 total_epochs=E, sentences_in_flight=args.in_flight, window_mode=1 if args.fixed_width else 0, negative_block=args.negative_block,
+                 coherent_tables=args.coherent_tables)
     tr.set_corpus(corpus.tokens, corpus.sent_off)
     if args.from_host:
         t_pin = torch.as_tensor(corpus.tokens).pin_memory()
@@ -143,7 +147,8 @@ def main():
     traffic = None
     # measured L2<->memory bytes per launch, from the committed rocprofv3 counter summary of this workload
     tpath = os.path.join(ROOT, "profiles", f"window_kernel_{args.workload}_d{dim}_counters.txt")
-    if os.path.exists(tpath) and not (args.naive or args.fixed_width or args.from_host or args.negative_block > 1):
+    if os.path.exists(tpath) and not (args.naive or args.fixed_width or args.from_host or args.negative_block > 1
+                                      or args.coherent_tables):
         for line in open(tpath):
             if line.startswith("hbm_bytes_per_launch:"):
                 traffic = float(line.split(":")[1])
@@ -173,6 +178,7 @@ def main():
                                + (", fixed width ceil(W/2)" if args.fixed_width else "")
                                + (f", negatives shared by stretches of {args.negative_block} tokens "
                                   f"({rows_per_kept:.2f} rows per kept word)" if args.negative_block > 1 else "")
+                               + (", tables in uncached device memory" if args.coherent_tables else "")
                                + (f", corpus fed from pinned host memory in batches of {args.staging_mb // 2} MiB"
                                   if args.from_host else ""),
                    "kept_words_per_s": kept / wall, "kept_fraction": kept / words,

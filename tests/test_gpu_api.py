@@ -112,3 +112,27 @@ def test_two_contexts_on_their_own_streams_do_not_disturb_each_other():
     for got, want in ((got_a, want_a), (got_b, want_b)):
         assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1]) and got[2] == want[2]
     torch.cuda.synchronize()
+
+
+def test_tables_in_uncached_memory_train_the_same(orc32):
+    """Trainer(coherent_tables=True) keeps syn0 / syn1neg in uncached device memory (for lock-free runs whose
+    wavefronts must see each other's rows across XCDs): in strict order the result is the oracle's, and equal bit
+    for bit to training on ordinary device memory."""
+    from paper_2312_07743_amd.trainer import Trainer
+    from util import assert_rows_close, run_oracle
+    c = synth.zipf_corpus(500, 1.0, 6, 400, seed=21)
+    kw = dict(dim=100, window=5, negatives=5, seed=13, table_size=1 << 14, subsample_t=1e-2)
+    got = []
+    for coherent in (False, True):
+        tr = Trainer(vocab=c.vocab, counts=c.counts, tokens_per_epoch=c.n_tokens, sentences_in_flight=1,
+                     coherent_tables=coherent, **kw)
+        tr.set_corpus(c.tokens, c.sent_off)
+        tr.train_epoch(0)
+        got.append((tr.embeddings(0), tr.embeddings(1), tr.loss()))
+        assert bool(torch.isfinite(tr.syn0).all()) and float(tr.syn0[:, kw["dim"]:].abs().max()) == 0.0
+        tr.close()
+    assert np.array_equal(got[0][0], got[1][0]) and np.array_equal(got[0][1], got[1][1]) and got[0][2] == got[1][2]
+    r0, r1, rl, rp = run_oracle(orc32, c, **kw)
+    assert got[1][2][1] == rp
+    assert_rows_close(got[1][0], r0, 1e-4, "syn0")
+    assert_rows_close(got[1][1], r1, 1e-4, "syn1neg")
