@@ -50,12 +50,11 @@ class Trainer:
         self.dev = torch.device("cuda", device)
         self.vocab, self.dim, self.window, self.negatives = vocab, dim, window, negatives
         self.ld = B.w2v_query_ld(dim)
-        if coherent_tables:
-            self.syn0 = _uncached_zeros((vocab, self.ld), self.dev)
-            self.syn1neg = _uncached_zeros((vocab, self.ld), self.dev)
-        else:
-            self.syn0 = torch.zeros((vocab, self.ld), dtype=torch.float32, device=self.dev)
-            self.syn1neg = torch.zeros((vocab, self.ld), dtype=torch.float32, device=self.dev)
+        def table(name):       # coherent_tables may also name one table ("syn0" / "syn1neg") for experiments
+            if coherent_tables is True or coherent_tables == name:
+                return _uncached_zeros((vocab, self.ld), self.dev)
+            return torch.zeros((vocab, self.ld), dtype=torch.float32, device=self.dev)
+        self.syn0, self.syn1neg = table("syn0"), table("syn1neg")
         if syn0 is not None:
             self.syn0[:, :dim] = torch.as_tensor(np.asarray(syn0, np.float32)).to(self.dev)
             self.syn1neg[:, :dim] = torch.as_tensor(np.asarray(syn1neg, np.float32)).to(self.dev)
