@@ -44,12 +44,20 @@ class Trainer:
         then read each other's updates instead of what their own L2 last saw.  Worth it where the words of a
         window are spread over a large vocabulary (random walks on graphs: 6 % slower, and the loss of an epoch
         on 128 wavefronts within 0.5 % of strict order instead of 3.3 %); text, whose frequent rows live in L2,
-        trains four times slower with it for a gain of 0.2 % in loss."""
+        trains four times slower with it for a gain of 0.2 % in loss.  "auto" decides from the counts."""
         if not torch.cuda.is_available():
             raise RuntimeError("the SGNS trainer needs a GPU; there is no CPU implementation in this package")
         self.dev = torch.device("cuda", device)
         self.vocab, self.dim, self.window, self.negatives = vocab, dim, window, negatives
         self.ld = B.w2v_query_ld(dim)
+        if coherent_tables == "auto":
+            # uncached when the rows that fit one XCD's L2 (2 MB per table) carry under 30 % of the tokens: those are
+            # the corpora (walks over a large graph) that gain from coherent rows and lose little speed without L2
+            by_count = np.sort(np.asarray(counts, dtype=np.float64))[::-1]
+            rows = max(1, (2 << 20) // (self.ld * 4))
+            coherent_tables = bool(by_count[:rows].sum() < 0.3 * max(by_count.sum(), 1.0))
+        self.coherent_tables = coherent_tables
+
         def table(name):       # coherent_tables may also name one table ("syn0" / "syn1neg") for experiments
             if coherent_tables is True or coherent_tables == name:
                 return _uncached_zeros((vocab, self.ld), self.dev)

@@ -136,3 +136,16 @@ def test_tables_in_uncached_memory_train_the_same(orc32):
     assert got[1][2][1] == rp
     assert_rows_close(got[1][0], r0, 1e-4, "syn0")
     assert_rows_close(got[1][1], r1, 1e-4, "syn1neg")
+
+
+def test_automatic_choice_of_uncached_tables():
+    """coherent_tables="auto": text (a few thousand frequent rows carry most tokens) keeps cached tables, walks over a
+    graph with far more nodes than an L2 holds rows get uncached ones."""
+    from paper_2312_07743_amd.trainer import Trainer
+    text = synth.zipf_corpus(71000, 1.05, 50, 1000, seed=2)
+    walks = synth.barabasi_albert_walks(n_nodes=200000, m=5, walks_per_node=1, walk_len=20, seed=2)
+    for c, want in ((text, False), (walks, True)):
+        tr = Trainer(vocab=c.vocab, dim=128, window=5, negatives=5, counts=c.counts, tokens_per_epoch=c.n_tokens, seed=1,
+                     table_size=1 << 16, coherent_tables="auto")
+        assert tr.coherent_tables is want
+        tr.close()
