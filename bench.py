@@ -25,7 +25,7 @@ WORKLOADS = {
     # name: (generator kwargs, dim, window, negatives, subsample_t, table_size)
     "mid": (dict(vocab=71000, s=1.05, n_sent=17000, sent_len=1000, seed=1), 128, 5, 5, 1e-4, 1 << 24),
     # prefixes of the two big configurations (same vocabulary / row sizes, fewer sentences), for --workload only
-    "large": (dict(vocab=550000, s=1.1, n_sent=40000, sent_len=1000, seed=1), 300, 5, 10, 1e-5, 1 << 24),
+    "large": (dict(vocab=550000, s=1.1, n_sent=44000, sent_len=1000, seed=1), 300, 5, 10, 1e-5, 1 << 24),
     "graph": (dict(n_nodes=1000000, m=5, walks_per_node=1, walk_len=80, seed=1), 128, 10, 5, 0.0, 1 << 24),
     "small": (dict(vocab=8000, s=1.05, n_sent=600, sent_len=1000, seed=1, band_start=400), 128, 5, 5, 1e-4, 1 << 20),
 }

@@ -54,7 +54,7 @@ typedef struct w2v_config {
                                      "traditional"); 1: fixed width ceil(W/2) (Sec. 3.2, the paper's) */
     uint32_t total_epochs;        /* E >= 1, length of the learning-rate decay                          */
     uint32_t sentences_in_flight; /* 0: as many wavefronts at once as the GPU holds, but at most one per
-                                     2,048 * (N+1)/6 tokens that survive subsampling in an epoch, and at
+                                     2,048 * ((N+1)/6)^2 tokens that survive subsampling in an epoch, and at
                                      least 64 (lock-free, Sec. 2.2: too many on a small corpus lose most
                                      updates of the frequent rows);
                                      k >= 1: exactly at most k at once; 1 = strict corpus order, deterministic */

@@ -130,18 +130,20 @@ int check_train_call(w2v_ctx *ctx, const int32_t *tokens, const uint64_t *sent_o
 
 hipStream_t stream_of(const w2v_ctx *ctx) { return static_cast<hipStream_t>(ctx->cfg.stream); }
 
-// Wavefronts for cfg.sentences_in_flight = 0: all the GPU holds, but no more than one per 2,048 * (N+1)/6 kept
-// tokens of the epoch (one per 2,048 with five negatives).  Every wavefront trains on copies of the rows it touches and the last writer of a row wins:
-// the chance that an update of a row is lost grows with the number of rows in flight, wavefronts x (N+1) output
-// rows, while the updates a row gets per epoch grow with the tokens that survive subsampling.  Measured: a 3M-token
-// corpus (N=5, half the tokens kept) on 3,000 wavefronts reaches planted-cluster score 0.56 in five epochs, on 730
-// it reaches 1.00; a 0.6M-token corpus on 2,400 wavefronts does not learn at all; 9.5M tokens of which 30 % are
-// kept, N=10, on 1,536 wavefronts: score 0.67 after two epochs, on 512: 1.00.  The 17M-token corpus (N=5) keeps
-// every wavefront.
+// Wavefronts for cfg.sentences_in_flight = 0: all the GPU holds, but no more than one per 2,048 * ((N+1)/6)^2 kept
+// tokens of the epoch (one per 2,048 with five negatives).  Every wavefront trains on copies of the rows it touches
+// and the last writer of a row wins: the chance that an update of a row is lost grows with the output rows in
+// flight, wavefronts x (N+1), a window is spoilt if any of its N+1 rows is, and the updates a row gets per epoch
+// grow with the tokens that survive subsampling.  Measured: a 3M-token corpus (N=5, half the tokens kept) on 3,000
+// wavefronts reaches planted-cluster score 0.56 in five epochs, on 730 it reaches 1.00; a 0.6M-token corpus on 2,400
+// wavefronts does not learn at all; 9.5M tokens of which 30 % are kept, N=10, on 1,536 wavefronts: score 0.67 after
+// two epochs, on 512: 1.00; 5.6M tokens of that kind, four epochs, loss against the serial oracle: 360 wavefronts
+// +0.9 %, 196 (this rule) +0.6 %.  The 17M-token corpus (N=5) keeps every wavefront.
 uint64_t lock_free_waves(const w2v_ctx *ctx, uint64_t resident)
 {
     const double kept = (double)ctx->cfg.tokens_per_epoch * ctx->kept_fraction;
-    uint64_t cap = (uint64_t)(kept * 6.0 / (2048.0 * (double)(ctx->cfg.negatives + 1u)));
+    const double rows = (double)(ctx->cfg.negatives + 1u);
+    uint64_t cap = (uint64_t)(kept * 36.0 / (2048.0 * rows * rows));
     if (cap < 64u) cap = 64u;
     return resident < cap ? resident : cap;
 }
