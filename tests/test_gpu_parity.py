@@ -6,7 +6,7 @@ import torch
 
 from paper_2312_07743_amd import binding as B
 from paper_2312_07743_amd import synth
-from util import assert_rows_close, run_gpu, run_oracle
+from util import assert_no_further_from_fp64_than_fp32_oracle, assert_rows_close, run_gpu, run_oracle
 
 pytestmark = pytest.mark.gpu
 
@@ -74,11 +74,21 @@ def _parity(orc32, corpus, tol=1e-4, unit_shift=None, **kw):
     return max(w0, w1)
 
 
-def test_tiny_config_strict_order_matches_oracle(orc32):
-    """configs[0]: vocab 1000 Zipf(1.0), 100 sentences x 1000 tokens, d=128, W=5, N=5, no subsampling."""
+def test_tiny_config_strict_order_matches_oracle(orc32, orc64):
+    """configs[0]: vocab 1000 Zipf(1.0), 100 sentences x 1000 tokens, d=128, W=5, N=5, no subsampling.  Gated against
+    the fp32 oracle (every element within 2e-4, all but 1 in 10,000 within 1e-4) and against the fp64 oracle: the HIP
+    path may be no further from it than 1.5 times the fp32 oracle is (the distance tests/test_oracle_pins.py pins)."""
     c = synth.zipf_corpus(1000, 1.0, 100, 1000, seed=7)
-    worst = _parity(orc32, c, dim=128, window=5, negatives=5, seed=42, table_size=1 << 24)
-    print("tiny: worst scaled error", worst)
+    kw = dict(dim=128, window=5, negatives=5, seed=42, table_size=1 << 24)
+    g0, g1, gl, gp = run_gpu(c, sentences_in_flight=1, **kw)
+    r0, r1, rl, rp = run_oracle(orc32, c, **kw)
+    d0, d1, dl, dp = run_oracle(orc64, c, **kw)
+    assert gp == rp == dp
+    assert abs(gl - rl) <= 2e-5 * abs(rl) and abs(gl - dl) <= 2e-5 * abs(dl)
+    worst = max(assert_rows_close(g0, r0, 1e-4, "syn0"), assert_rows_close(g1, r1, 1e-4, "syn1neg"))
+    far0 = assert_no_further_from_fp64_than_fp32_oracle(g0, r0, d0, 1.5, "syn0")
+    far1 = assert_no_further_from_fp64_than_fp32_oracle(g1, r1, d1, 1.5, "syn1neg")
+    print("tiny: worst scaled error against the fp32 oracle", worst, "; (HIP, fp32 oracle) from the fp64 oracle:", far0, far1)
 
 
 @pytest.mark.parametrize("dim", [64, 100, 256, 300, 512])
