@@ -53,6 +53,8 @@ def main():
     ap.add_argument("--coherent-tables", action="store_true",
                     help="keep syn0 / syn1neg in uncached device memory (wavefronts on different XCDs see each other's "
                          "updates at once; for walk corpora)")
+    ap.add_argument("--update-mode", type=int, default=0, choices=(0, 1, 2),
+                    help="cfg.update_mode: 0 the library's choice from the word counts, 1 overwrite, 2 summed lock-free updates")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--naive", action="store_true",
                     help="time the no-reuse comparator kernel instead of the window kernel (traffic comparison only)")
@@ -98,7 +100,7 @@ def main():
     tr = Trainer(vocab=corpus.vocab, dim=dim, window=window, negatives=negatives, counts=corpus.counts,
                  tokens_per_epoch=corpus.n_tokens, seed=2024, table_size=table_size, subsample_t=t_sub,
                  total_epochs=E, sentences_in_flight=args.in_flight, window_mode=1 if args.fixed_width else 0, negative_block=args.negative_block,
-                 coherent_tables=args.coherent_tables)
+                 coherent_tables=args.coherent_tables, update_mode=args.update_mode)
     tr.set_corpus(corpus.tokens, corpus.sent_off)
     if args.from_host:
         t_pin = torch.as_tensor(corpus.tokens).pin_memory()

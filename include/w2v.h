@@ -55,22 +55,15 @@ typedef struct w2v_config {
     uint32_t total_epochs;        /* E >= 1, length of the learning-rate decay                          */
     uint32_t sentences_in_flight; /* 0: as many wavefronts at once as the GPU holds, but at most one per
                                      2,048 * ((N+1)/6)^2 tokens that survive subsampling in an epoch, and at
-                                     least 64 (lock-free, Sec. 2.2: too many on a small corpus lose most
-                                     updates of the frequent rows);
-                                     k >= 1: exactly at most k at once; 1 = strict corpus order, deterministic */
+                                     least 64 (lock-free sentences, Sec. 2.2 / 2.3);
+                                     k >= 1: at most k at once; 1 = strict corpus order, deterministic     */
     uint64_t tokens_per_epoch;    /* T >= 1, corpus tokens per epoch before subsampling                 */
     uint64_t seed;                /* keys every random decision and the weight initialisation          */
     double   lr0;                 /* starting learning rate (0.025)                                     */
     double   lr_min_frac;         /* floor of the decay as a fraction of lr0 (1e-4)                     */
     double   subsample_t;         /* frequent-word subsampling threshold t; 0 switches it off           */
     void    *syn0;                /* device, float[vocab*ld]: input (context-word) embeddings           */
-    void    *syn1neg;             /* device, float[vocab*ld]: output (target / negative) weights.
-                                     Either table may lie in uncached device memory (hipExtMallocWithFlags,
-                                     hipDeviceMallocUncached): lock-free wavefronts on different XCDs then
-                                     see each other's rows at once instead of what their own L2 holds.
-                                     Measured: random walks on a 1M-node graph 1 to 6 % slower, loss of an
-                                     epoch on 128 wavefronts within 0.5 % of strict order instead of 3.3 %;
-                                     text four times slower for 0.2 %                                    */
+    void    *syn1neg;             /* device, float[vocab*ld]: output (target / negative) weights          */
     uint32_t ld;                  /* row stride in floats, >= dim and a multiple of 4; columns
                                      dim..ld-1 are never read or written by training                    */
     int32_t  device;              /* HIP device ordinal                                                 */
@@ -83,13 +76,31 @@ typedef struct w2v_config {
                                      consecutive tokens of a sentence (offsets before subsampling) share
                                      the N negatives drawn at the stretch's first position; a negative
                                      equal to a window's own target is skipped for that window only      */
-    uint32_t reserved;            /* 0                                                                  */
+    uint32_t update_mode;         /* How lock-free wavefronts write rows back (Sec. 2.2 / 2.3 leave the
+                                     conflicts between sentences unresolved):
+                                     1: overwrite -- a row goes back as the wavefront's copy of it (a context
+                                        row's copy lives for up to 2W+1 windows), so of the updates several
+                                        wavefronts make to one row at the same time only the last writer's
+                                        survives;
+                                     2: summed -- a row goes back as (what memory holds now) + (the change the
+                                        wavefront made to its copy), and every table access is made at system
+                                        scope, so wavefronts on different XCDs see each other's rows.  Exists
+                                        for dim <= 256, 5 <= N <= 11 and windows of at most 10 as they occur;
+                                        W2V_EINVAL otherwise.  Needs the snapshot space that
+                                        w2v_query_workspace() then adds;
+                                     0: automatic -- summed where such a kernel exists and the word counts
+                                        say that the rows one L2 can hold carry under 30 % of the tokens
+                                        (walks over a large graph), overwrite otherwise (text).
+                                     Strict order (sentences_in_flight = 1) always overwrites: there is
+                                     nothing to sum                                                      */
 } w2v_config;
 
 /* Row stride (in floats) that keeps every row aligned to 128-byte memory lines. */
 int w2v_query_ld(uint32_t dim, uint32_t *ld_out);
 
-/* Bytes of device workspace needed for cfg->vocab and a sampling table of table_size slots. */
+/* Bytes of device workspace needed for a sampling table of table_size slots.  Reads cfg->vocab, and
+ * cfg->dim, window, window_mode, negatives and update_mode for the snapshot space of summed updates
+ * (none if update_mode is 1 or the configuration has no such kernel; cfg->ld may be 0 = w2v_query_ld()). */
 int w2v_query_workspace(const w2v_config *cfg, uint32_t table_size, uint64_t *bytes_out);
 
 /* Validates cfg, copies it, and (init_weights != 0) fills syn0 with U(-0.5/d, 0.5/d) values
@@ -123,13 +134,13 @@ int w2v_train_epoch(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_t *sen
  * context owns, so transfers hide behind the kernel.  Every random draw and the learning rate are
  * keyed by global token positions, so the result equals that of w2v_train_epoch on a resident copy
  * (bit for bit with sentences_in_flight = 1).  Returns when the last batch has been queued on the
- * context's stream (the call itself waits until all but the last two batches have been trained): the host arrays must stay valid until that stream has been synchronised (pinned
- * host memory gives truly asynchronous copies, pageable memory works and blocks this call while
- * each batch is staged).  Every batch is a launch of its own, whose last wavefronts leave part of
- * the GPU idle: large halves keep that loss small (17M tokens per epoch: 9.95 ms with 64 MiB
- * halves, 10.4 ms with 16 MiB, 13.3 ms with 4 MiB; 9.5 ms resident).  The sentences are spread
- * over as few batches as fit, of nearly equal size, and the halves alternate across calls, so the
- * first batch of an epoch is copied while the previous epoch still trains.
+ * context's stream (the call itself waits until all but the last two batches have been trained):
+ * the host arrays must stay valid until that stream has been synchronised (pinned host memory
+ * gives truly asynchronous copies, pageable memory works and blocks this call while each batch is
+ * staged).  Every batch is a launch of its own, whose last wavefronts leave part of the GPU idle:
+ * large halves (tens of MiB) keep that loss small.  The sentences are spread over as few batches as
+ * fit, of nearly equal size, and the halves alternate across calls, so the first batch of an epoch
+ * is copied while the previous epoch still trains.
  * W2V_EINVAL if a sentence does not fit half of the staging buffer. */
 int w2v_train_epoch_host(w2v_ctx *ctx, const int32_t *tokens_host, const uint64_t *sent_off_host,
                          uint64_t n_sent, uint64_t first_token_global_pos, uint32_t epoch,
@@ -164,10 +175,32 @@ int w2v_debug_draws(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_t *sen
                     uint64_t n_sent, uint64_t first_token_global_pos, uint32_t epoch,
                     uint8_t *keep_dev, uint8_t *width_dev, int32_t *neg_dev);
 
+/* Test surface: w2v_train_epoch with the window kernel itself writing out the integer decisions it
+ * takes (the subsampling, width and negative draws of Sec. 2.1 / 3.1 / 3.2 as the hot path computes
+ * them, not a second implementation): same outputs and layout as w2v_debug_draws, for every token
+ * that gets a context window in this call.  Trains like w2v_train_epoch.  Asynchronous after one
+ * wait for the stream. */
+int w2v_debug_train_draws(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_t *sent_off_dev,
+                          uint64_t n_sent, uint64_t first_token_global_pos, uint32_t epoch,
+                          uint8_t *keep_dev, uint8_t *width_dev, int32_t *neg_dev);
+
+/* Test surface: fixes the update mode of every later launch, strict order included (update = 0
+ * overwrite, 1 summed, -1 back to cfg.update_mode's rules), and the parts of the summed mode that are
+ * switched on: flags bit 0 context rows summed, bit 1 output rows summed, bit 2 table loads at system
+ * scope, bit 3 table stores at system scope (15 = the mode as shipped). */
+int w2v_debug_set_update(w2v_ctx *ctx, int update, uint32_t flags);
+
+/* Test surface: the work plan of the last launch (sentences before coarse_sentences were handed out as
+ * 2^unit_shift units each, the others as 2^fine_shift; units in all), its update mode (0 overwrite,
+ * 1 summed) and the wavefronts it was given.  Any output may be NULL.  Waits for the stream. */
+int w2v_debug_get_plan(w2v_ctx *ctx, uint32_t *unit_shift, uint32_t *fine_shift,
+                       uint64_t *coarse_sentences, uint64_t *units, uint32_t *update,
+                       uint64_t *wavefronts);
+
 /* Test surface: fixes the granularity of the work queue.  w2v_train_epoch hands a sentence out as
  * 2^unit_shift stretches of its tokens (each reads the W kept tokens on either side as context
  * only, so the windows are those of the whole sentence); by default the library picks the
- * exponent from the sizes of the call (0 when one wavefront runs alone).  unit_shift in [0, 16]
+ * exponent on the device from the sizes of the call (0 when one wavefront runs alone).  unit_shift in [0, 16]
  * fixes it, -1 restores the default. */
 int w2v_debug_set_units(w2v_ctx *ctx, int unit_shift);
 

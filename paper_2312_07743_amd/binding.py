@@ -15,6 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libw2v.so")
 EXPORTS = ["w2v_query_ld", "w2v_query_workspace", "w2v_create", "w2v_destroy", "w2v_build_unigram_table",
            "w2v_train_epoch", "w2v_train_epoch_host", "w2v_train_epoch_naive", "w2v_get_embeddings", "w2v_loss", "w2v_counters", "w2v_debug_draws",
+           "w2v_debug_train_draws", "w2v_debug_set_update", "w2v_debug_get_plan",
            "w2v_debug_set_units", "w2v_debug_set_unit_tail", "w2v_debug_reduce", "w2v_last_error"]
 
 
@@ -25,7 +26,7 @@ class W2VConfig(C.Structure):
                 ("lr0", C.c_double), ("lr_min_frac", C.c_double), ("subsample_t", C.c_double),
                 ("syn0", C.c_void_p), ("syn1neg", C.c_void_p), ("ld", C.c_uint32), ("device", C.c_int32),
                 ("stream", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_uint64),
-                ("negative_block", C.c_uint32), ("reserved", C.c_uint32)]
+                ("negative_block", C.c_uint32), ("update_mode", C.c_uint32)]
 
 
 class W2VError(RuntimeError):
@@ -58,6 +59,10 @@ def lib():
         L.w2v_loss.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(u64), i32]
         L.w2v_counters.argtypes = [vp, C.POINTER(u64), C.POINTER(u64), i32]
         L.w2v_debug_draws.argtypes = [vp, vp, vp, u64, u64, u32, vp, vp, vp]
+        L.w2v_debug_train_draws.argtypes = [vp, vp, vp, u64, u64, u32, vp, vp, vp]
+        L.w2v_debug_set_update.argtypes = [vp, i32, u32]
+        L.w2v_debug_get_plan.argtypes = [vp, C.POINTER(u32), C.POINTER(u32), C.POINTER(u64), C.POINTER(u64), C.POINTER(u32),
+                                         C.POINTER(u64)]
         L.w2v_debug_reduce.argtypes = [vp, vp, vp]
         L.w2v_debug_set_units.argtypes = [vp, i32]
         L.w2v_debug_set_unit_tail.argtypes = [vp, i32, u64]
@@ -96,8 +101,10 @@ def w2v_query_ld(dim):
     return out.value
 
 
-def w2v_query_workspace(vocab, table_size):
-    cfg = W2VConfig(struct_size=C.sizeof(W2VConfig), vocab=vocab)
+def w2v_query_workspace(vocab, table_size, dim=0, window=0, negatives=0, window_mode=0, update_mode=1):
+    """update_mode 1 (overwrite) needs no snapshot space and no dim / window / negatives."""
+    cfg = W2VConfig(struct_size=C.sizeof(W2VConfig), vocab=vocab, dim=dim, window=window, negatives=negatives,
+                    window_mode=window_mode, update_mode=update_mode)
     out = C.c_uint64(0)
     _check(lib().w2v_query_workspace(C.byref(cfg), table_size, C.byref(out)))
     return out.value
@@ -105,13 +112,13 @@ def w2v_query_workspace(vocab, table_size):
 
 def make_config(*, vocab, dim, window, negatives, tokens_per_epoch, seed, syn0, syn1neg, ld, workspace,
                 workspace_bytes, device=0, stream=None, window_mode=0, total_epochs=1, sentences_in_flight=0,
-                lr0=0.025, lr_min_frac=1e-4, subsample_t=0.0, negative_block=0):
+                lr0=0.025, lr_min_frac=1e-4, subsample_t=0.0, negative_block=0, update_mode=0):
     return W2VConfig(struct_size=C.sizeof(W2VConfig), vocab=vocab, dim=dim, window=window, negatives=negatives,
                      window_mode=window_mode, total_epochs=total_epochs, sentences_in_flight=sentences_in_flight,
                      tokens_per_epoch=tokens_per_epoch, seed=seed, lr0=lr0, lr_min_frac=lr_min_frac,
                      subsample_t=subsample_t, syn0=_ptr(syn0), syn1neg=_ptr(syn1neg), ld=ld, device=device,
                      stream=_ptr(stream), workspace=_ptr(workspace), workspace_bytes=workspace_bytes,
-                     negative_block=negative_block, reserved=0)
+                     negative_block=negative_block, update_mode=update_mode)
 
 
 def w2v_create(cfg, init_weights=1):
@@ -171,6 +178,24 @@ def w2v_counters(ctx, reset=0):
 def w2v_debug_draws(ctx, tokens_dev, sent_off_dev, n_sent, first_token_global_pos, epoch, keep_dev, width_dev, neg_dev):
     _check(lib().w2v_debug_draws(ctx, _ptr(tokens_dev), _ptr(sent_off_dev), n_sent, first_token_global_pos, epoch,
                                  _ptr(keep_dev), _ptr(width_dev), _ptr(neg_dev)), ctx)
+
+
+def w2v_debug_train_draws(ctx, tokens_dev, sent_off_dev, n_sent, first_token_global_pos, epoch, keep_dev, width_dev,
+                          neg_dev):
+    _check(lib().w2v_debug_train_draws(ctx, _ptr(tokens_dev), _ptr(sent_off_dev), n_sent, first_token_global_pos,
+                                       epoch, _ptr(keep_dev), _ptr(width_dev), _ptr(neg_dev)), ctx)
+
+
+def w2v_debug_set_update(ctx, update, flags=15):
+    _check(lib().w2v_debug_set_update(ctx, int(update), int(flags)), ctx)
+
+
+def w2v_debug_get_plan(ctx):
+    """dict(unit_shift, fine_shift, coarse_sentences, units, update, wavefronts) of the last launch"""
+    us, fs, cs, n, up, wv = C.c_uint32(0), C.c_uint32(0), C.c_uint64(0), C.c_uint64(0), C.c_uint32(0), C.c_uint64(0)
+    _check(lib().w2v_debug_get_plan(ctx, C.byref(us), C.byref(fs), C.byref(cs), C.byref(n), C.byref(up), C.byref(wv)), ctx)
+    return dict(unit_shift=us.value, fine_shift=fs.value, coarse_sentences=cs.value, units=n.value, update=up.value,
+                wavefronts=wv.value)
 
 
 def w2v_debug_reduce(in_dev, out_dev, stream=None):

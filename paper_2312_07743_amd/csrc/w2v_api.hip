@@ -1,9 +1,11 @@
 // Host side of the C ABI declared in include/w2v.h: argument validation, the host-built sampling
 // table and subsampling thresholds, kernel launches, the host-fed batch loop.  No device memory is
 // allocated here: tables and accumulators live in the caller's workspace, staging in the caller's buffer.
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <functional>
 #include <new>
 #include <vector>
 
@@ -14,12 +16,13 @@ namespace w2v {
 
 static uint64_t align256(uint64_t x) { return (x + 255u) & ~(uint64_t)255u; }
 
-WorkspaceLayout workspace_layout(uint32_t vocab, uint32_t table_size)
+WorkspaceLayout workspace_layout(uint32_t vocab, uint32_t table_size, uint64_t snap_bytes)
 {
     WorkspaceLayout l;
     l.accum_off = 0;
     l.thr_off = align256(sizeof(Accum));
-    l.table_off = l.thr_off + align256((uint64_t)vocab * sizeof(uint32_t));
+    l.snap_off = l.thr_off + align256((uint64_t)vocab * sizeof(uint32_t));
+    l.table_off = l.snap_off + align256(snap_bytes);
     l.total = l.table_off + align256((uint64_t)table_size * sizeof(int32_t));
     return l;
 }
@@ -59,7 +62,7 @@ std::string check_config(const w2v_config *c)
     if (c->window_mode > 1) return "cfg.window_mode must be 0 or 1";
     if (c->negative_block > 64u || (c->negative_block & (c->negative_block - 1u)) != 0)
         return "cfg.negative_block must be 0 or a power of two up to 64";
-    if (c->reserved != 0) return "cfg.reserved must be 0";
+    if (c->update_mode > 2) return "cfg.update_mode must be 0 (automatic), 1 (overwrite) or 2 (summed)";
     if (c->total_epochs < 1) return "cfg.total_epochs must be >= 1";
     if (c->tokens_per_epoch < 1) return "cfg.tokens_per_epoch must be >= 1";
     if (c->tokens_per_epoch > (1ull << 52) / c->total_epochs) return "total_epochs * tokens_per_epoch exceeds 2^52";
@@ -109,9 +112,6 @@ w2v::KernelArgs kernel_args(const w2v_ctx *ctx, const int32_t *tokens, const uin
     a.window_mode = c.window_mode ? 2u : 0u;
     a.table_size = ctx->table_size;
     a.subsample = c.subsample_t > 0.0 ? 1u : 0u;
-    a.unit_shift = 0;
-    a.fine_shift = 0;
-    a.coarse_sent = n_sent;
     a.neg_shift = 0;
     for (uint32_t b = c.negative_block; b > 1u; b >>= 1) ++a.neg_shift;
     return a;
@@ -148,50 +148,57 @@ uint64_t lock_free_waves(const w2v_ctx *ctx, uint64_t resident)
     return resident < cap ? resident : cap;
 }
 
-// Into how many units (a power of two, as its exponent) each sentence is cut for the work queue: enough units
-// that the wavefronts finish within a small fraction of the launch of one another (a wavefront holds a unit
-// until it is done), but units of at least 128 tokens on average, since every unit re-reads the few tokens
-// of context on either side.  One wavefront (strict order) gains nothing from a finer queue.
-uint32_t pick_unit_shift(const w2v_ctx *ctx, uint64_t n_sent, uint64_t n_tokens, uint64_t waves)
+// Bytes of snapshot space in the workspace: the summed mode keeps the starting value of every ring slot of every
+// wavefront there.  None when the configuration rules the mode out or no such kernel exists for its shape.
+uint64_t snapshot_bytes(const w2v_config *c, uint32_t *floats_per_wave)
 {
-    uint32_t shift = 0;
-    if (ctx->forced_unit_shift >= 0) return (uint32_t)ctx->forced_unit_shift;
-    if (waves <= 1 || n_sent == 0) return 0;
-    while (shift < 16 && (n_sent << shift) < 16u * waves && (n_tokens / n_sent) >> (shift + 1) >= 128u) ++shift;
-    return shift;
+    *floats_per_wave = 0;
+    if (c->update_mode == 1u) return 0;
+    w2v::KernelArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.dim = c->dim;
+    a.ld = c->ld ? c->ld : ((c->dim + 31u) & ~31u);
+    a.window = c->window_mode ? (c->window + 1u) / 2u : c->window;
+    a.negatives = c->negatives;
+    *floats_per_wave = w2v::train_snap_floats(a);
+    return (uint64_t)*floats_per_wave * 4u * w2v::kMaxSummedWaves;
 }
 
-// Wavefronts of the window kernel the device holds at once (asked of the runtime once per context: the kernel and
-// its LDS need follow from the configuration alone).
-uint64_t resident_waves(w2v_ctx *ctx, const w2v::KernelArgs &a)
+// Queues one launch of the window kernel over the sentences described by `a`: picks the update mode and the
+// number of wavefronts, plans the units on the device, launches.
+int queue_launch(w2v_ctx *ctx, w2v::KernelArgs &a)
 {
-    if (ctx->resident_waves == 0) ctx->resident_waves = w2v::train_resident_waves(a, ctx->cfg.device);
-    return ctx->resident_waves;
-}
-
-// Cuts the launch's sentences into units and returns how many there are.  Lock-free launches end the queue with
-// units half the size (the last eighth of the sentences, stretches of at least 32 tokens on average): a
-// wavefront holds a unit until it is done, so the launch ends when the slowest last unit does.  (Measured on
-// 17,000 sentences of 1,000 tokens: 1.2 % faster than equal units; units a quarter or an eighth the size, or a
-// longer fine part, lose the gain to the context every unit re-reads.)
-uint64_t plan_units(const w2v_ctx *ctx, uint64_t n_sent, uint64_t n_tokens, uint64_t waves, w2v::KernelArgs *a)
-{
-    a->unit_shift = pick_unit_shift(ctx, n_sent, n_tokens, waves);
-    a->fine_shift = a->unit_shift;
-    a->coarse_sent = n_sent;
-    if (ctx->forced_fine_shift >= 0) {
-        a->fine_shift = (uint32_t)ctx->forced_fine_shift;
-        a->coarse_sent = ctx->forced_coarse_sent < n_sent ? ctx->forced_coarse_sent : n_sent;
-    } else if (ctx->forced_unit_shift < 0 && waves > 1 && n_sent > 0) {
-        uint32_t fine = a->unit_shift;
-        if (fine < 16u && (n_tokens / n_sent) >> (fine + 1u) >= 32u) ++fine;
-        if (fine > a->unit_shift) {
-            const uint64_t tail = n_sent / 8u ? n_sent / 8u : 1u;
-            a->fine_shift = fine;
-            a->coarse_sent = n_sent - tail;
-        }
+    const w2v_config &c = ctx->cfg;
+    // Summed updates when wavefronts run side by side and either the caller asks for them or (automatic) the
+    // counts say that the corpus spreads its tokens over far more rows than an L2 holds.
+    int update = (c.update_mode == 2u || (c.update_mode == 0u && ctx->flat_corpus)) && ctx->snap_floats ? 1 : 0;
+    if (c.sentences_in_flight == 1u) update = 0;       // strict order: nothing to sum
+    if (ctx->forced_update >= 0) update = ctx->forced_update;
+    uint64_t waves = c.sentences_in_flight;
+    if (waves == 0) {
+        if (ctx->resident_waves[update] == 0) ctx->resident_waves[update] = w2v::train_resident_waves(a, update, c.device);
+        waves = ctx->resident_waves[update];
+        if (waves == 0) return fail(ctx, W2V_EHIP, "could not query kernel occupancy");
+        waves = lock_free_waves(ctx, waves);
     }
-    return (a->coarse_sent << a->unit_shift) + ((n_sent - a->coarse_sent) << a->fine_shift);
+    if (update) {
+        if (waves > w2v::kMaxSummedWaves) waves = w2v::kMaxSummedWaves;
+        a.snap = reinterpret_cast<float *>(static_cast<unsigned char *>(c.workspace) + ctx->ws.snap_off);
+        a.snap_stride = ctx->snap_floats;
+        a.hog_flags = ctx->hog_flags;
+    }
+    if (a.n_sent < 65536u && waves > (a.n_sent << 16)) waves = a.n_sent << 16;   // a sentence is never cut into more units than that
+    w2v::PlanRequest rq;
+    rq.n_sent = a.n_sent;
+    rq.waves = waves;
+    rq.forced_unit_shift = ctx->forced_unit_shift;
+    rq.forced_fine_shift = ctx->forced_fine_shift;
+    rq.forced_coarse_sent = ctx->forced_coarse_sent;
+    HIP_TRY(ctx, w2v::launch_plan(a.accum, a.sent_off, rq, stream_of(ctx)));
+    HIP_TRY(ctx, w2v::launch_train(a, update, (uint32_t)waves, stream_of(ctx)));
+    ctx->last_update = update;
+    ctx->last_waves = waves;
+    return W2V_OK;
 }
 
 }  // namespace
@@ -209,7 +216,12 @@ int w2v_query_workspace(const w2v_config *cfg, uint32_t table_size, uint64_t *by
 {
     if (!cfg || !bytes_out || cfg->vocab < 1 || cfg->vocab > W2V_MAX_VOCAB || table_size < 1 || table_size > (1u << 31))
         return W2V_EINVAL;
-    *bytes_out = w2v::workspace_layout(cfg->vocab, table_size).total;
+    uint32_t per_wave = 0;
+    uint64_t snap = 0;
+    if (cfg->dim >= 1 && cfg->dim <= W2V_MAX_DIM && cfg->window >= 1 && cfg->window <= W2V_MAX_WINDOW &&
+        cfg->negatives <= W2V_MAX_NEGATIVES && cfg->update_mode <= 2u)
+        snap = snapshot_bytes(cfg, &per_wave);
+    *bytes_out = w2v::workspace_layout(cfg->vocab, table_size, snap).total;
     return W2V_OK;
 }
 
@@ -219,12 +231,17 @@ int w2v_create(const w2v_config *cfg, int init_weights, w2v_ctx **out)
     *out = nullptr;
     const std::string why = check_config(cfg);
     if (!why.empty()) return fail(nullptr, W2V_EINVAL, why);
-    const w2v::WorkspaceLayout minimal = w2v::workspace_layout(cfg->vocab, 1);
+    uint32_t snap_floats = 0;
+    const uint64_t snap_bytes = snapshot_bytes(cfg, &snap_floats);
+    if (cfg->update_mode == 2u && snap_floats == 0)
+        return fail(nullptr, W2V_EINVAL, "cfg.update_mode 2 (summed updates) needs dim <= 256, window <= 10 (as it occurs) and 5 to 11 negatives");
+    const w2v::WorkspaceLayout minimal = w2v::workspace_layout(cfg->vocab, 1, snap_bytes);
     if (cfg->workspace_bytes < minimal.total) return fail(nullptr, W2V_ENOMEM, "cfg.workspace_bytes is smaller than w2v_query_workspace()");
     w2v_ctx *ctx = new (std::nothrow) w2v_ctx();
     if (!ctx) return fail(nullptr, W2V_ENOMEM, "out of host memory");
     ctx->cfg = *cfg;
     ctx->ws = minimal;
+    ctx->snap_floats = snap_floats;
     hipError_t e = hipSetDevice(cfg->device);
     if (e == hipSuccess)
         e = w2v::launch_reset_accum(reinterpret_cast<w2v::Accum *>(static_cast<unsigned char *>(cfg->workspace)), 2, stream_of(ctx));
@@ -263,7 +280,7 @@ int w2v_build_unigram_table(w2v_ctx *ctx, const uint64_t *counts_host, uint32_t 
     if (!counts_host) return fail(ctx, W2V_EINVAL, "counts_host is NULL");
     if (table_size < 1 || table_size > (1u << 31)) return fail(ctx, W2V_EINVAL, "table_size out of range [1, 2^31]");
     const uint32_t V = ctx->cfg.vocab;
-    const w2v::WorkspaceLayout lay = w2v::workspace_layout(V, table_size);
+    const w2v::WorkspaceLayout lay = w2v::workspace_layout(V, table_size, (uint64_t)ctx->snap_floats * 4u * w2v::kMaxSummedWaves);
     if (ctx->cfg.workspace_bytes < lay.total) return fail(ctx, W2V_ENOMEM, "workspace too small for this table_size");
 
     // share of word i: count_i^(3/4) = sqrt(c) * sqrt(sqrt(c)), accumulated in id order
@@ -304,6 +321,17 @@ int w2v_build_unigram_table(w2v_ctx *ctx, const uint64_t *counts_host, uint32_t 
         }
     }
     ctx->kept_fraction = kept_c / total_c;
+    // Share of the tokens carried by the rows that fit one XCD's L2 (2 MB of each table): small for walks over a
+    // large graph, large for text.  Where it is small the frequent rows are not held in L2 anyway, and it is exactly
+    // those rows whose copies must not diverge between XCDs: such corpora get summed, system-scope updates.
+    {
+        std::vector<uint64_t> by_count(counts_host, counts_host + V);
+        const size_t rows = std::min<size_t>(V, std::max<size_t>(1, (2u << 20) / ((size_t)ctx->cfg.ld * 4u)));
+        std::nth_element(by_count.begin(), by_count.begin() + (rows - 1), by_count.end(), std::greater<uint64_t>());
+        double top = 0.0;
+        for (size_t i = 0; i < rows; ++i) top += (double)by_count[i];
+        ctx->flat_corpus = top < 0.30 * total_c;
+    }
 
     unsigned char *ws = static_cast<unsigned char *>(ctx->cfg.workspace);
     HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
@@ -324,19 +352,7 @@ int w2v_train_epoch(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_t *sen
     if (n_sent == 0) return W2V_OK;
     HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
     w2v::KernelArgs a = kernel_args(ctx, tokens_dev, sent_off_dev, n_sent, first_token_global_pos, epoch);
-    uint64_t waves = ctx->cfg.sentences_in_flight;
-    if (waves == 0) {
-        waves = resident_waves(ctx, a);
-        if (waves == 0) return fail(ctx, W2V_EHIP, "could not query kernel occupancy");
-        waves = lock_free_waves(ctx, waves);
-    }
-    // the token count of this call is on the device; the epoch's count stands in for it (a call that feeds
-    // part of an epoch gets units that are shorter than intended, never wrong)
-    const uint64_t units = plan_units(ctx, n_sent, ctx->cfg.tokens_per_epoch, waves, &a);
-    if (waves > units) waves = units;
-    HIP_TRY(ctx, w2v::launch_reset_accum(a.accum, 1, stream_of(ctx)));
-    HIP_TRY(ctx, w2v::launch_train(a, (uint32_t)waves, stream_of(ctx)));
-    return W2V_OK;
+    return queue_launch(ctx, a);
 }
 
 int w2v_train_epoch_host(w2v_ctx *ctx, const int32_t *tokens_host, const uint64_t *sent_off_host, uint64_t n_sent,
@@ -397,16 +413,8 @@ int w2v_train_epoch_host(w2v_ctx *ctx, const int32_t *tokens_host, const uint64_
         // batch's first offset instead, so positions (random keys, learning rate) are those of the corpus.
         const int32_t *tok_moved = reinterpret_cast<const int32_t *>(reinterpret_cast<uintptr_t>(tok_dev) - 4u * t_begin);
         w2v::KernelArgs a = kernel_args(ctx, tok_moved, off_dev, nsent, first_token_global_pos, epoch);
-        uint64_t waves = ctx->cfg.sentences_in_flight;
-        if (waves == 0) {
-            waves = resident_waves(ctx, a);
-            if (waves == 0) return fail(ctx, W2V_EHIP, "could not query kernel occupancy");
-            waves = lock_free_waves(ctx, waves);
-        }
-        const uint64_t units = plan_units(ctx, nsent, ntok, waves, &a);
-        if (waves > units) waves = units;
-        HIP_TRY(ctx, w2v::launch_reset_accum(a.accum, 1, stream_of(ctx)));
-        HIP_TRY(ctx, w2v::launch_train(a, (uint32_t)waves, stream_of(ctx)));
+        const int qrc = queue_launch(ctx, a);
+        if (qrc != W2V_OK) return qrc;
         HIP_TRY(ctx, hipEventRecord(ctx->drained[h], stream_of(ctx)));
         ctx->drained_recorded[h] = true;
         s0 = s1;
@@ -493,6 +501,55 @@ int w2v_debug_draws(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_t *sen
     HIP_TRY(ctx, hipStreamSynchronize(stream_of(ctx)));
     const w2v::KernelArgs a = kernel_args(ctx, tokens_dev, sent_off_dev, n_sent, first_token_global_pos, epoch);
     HIP_TRY(ctx, w2v::launch_draws(a, n_tokens, keep_dev, width_dev, neg_dev, stream_of(ctx)));
+    return W2V_OK;
+}
+
+int w2v_debug_train_draws(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_t *sent_off_dev, uint64_t n_sent,
+                          uint64_t first_token_global_pos, uint32_t epoch, uint8_t *keep_dev, uint8_t *width_dev,
+                          int32_t *neg_dev)
+{
+    const int rc = check_train_call(ctx, tokens_dev, sent_off_dev, n_sent, first_token_global_pos, epoch);
+    if (rc != W2V_OK) return rc;
+    if (!keep_dev || !width_dev || (ctx->cfg.negatives && !neg_dev)) return fail(ctx, W2V_EINVAL, "an output pointer is NULL");
+    if (n_sent == 0) return W2V_OK;
+    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    uint64_t n_tokens = 0;
+    HIP_TRY(ctx, hipMemcpyAsync(&n_tokens, sent_off_dev + n_sent, sizeof(uint64_t), hipMemcpyDeviceToHost, stream_of(ctx)));
+    HIP_TRY(ctx, hipStreamSynchronize(stream_of(ctx)));
+    w2v::KernelArgs a = kernel_args(ctx, tokens_dev, sent_off_dev, n_sent, first_token_global_pos, epoch);
+    a.dump.keep = keep_dev;
+    a.dump.width = width_dev;
+    a.dump.neg = neg_dev;
+    HIP_TRY(ctx, w2v::launch_fill_dump(a.dump, n_tokens, ctx->cfg.negatives, stream_of(ctx)));
+    return queue_launch(ctx, a);
+}
+
+int w2v_debug_set_update(w2v_ctx *ctx, int update, uint32_t flags)
+{
+    if (!ctx) return fail(nullptr, W2V_EINVAL, "ctx is NULL");
+    if (update < -1 || update > 1) return fail(ctx, W2V_EINVAL, "update must be -1 (by the rules), 0 (overwrite) or 1 (summed)");
+    if (update == 1 && ctx->snap_floats == 0) return fail(ctx, W2V_EINVAL, "no summed-update kernel for this configuration");
+    if (flags > 0xFu) return fail(ctx, W2V_EINVAL, "flags must be below 16");
+    ctx->forced_update = update;
+    ctx->hog_flags = flags;
+    return W2V_OK;
+}
+
+int w2v_debug_get_plan(w2v_ctx *ctx, uint32_t *unit_shift, uint32_t *fine_shift, uint64_t *coarse_sentences, uint64_t *units,
+                       uint32_t *update, uint64_t *wavefronts)
+{
+    if (!ctx) return fail(nullptr, W2V_EINVAL, "ctx is NULL");
+    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    w2v::Accum host;
+    w2v::Accum *dev = reinterpret_cast<w2v::Accum *>(static_cast<unsigned char *>(ctx->cfg.workspace) + ctx->ws.accum_off);
+    HIP_TRY(ctx, hipMemcpyAsync(&host, dev, sizeof(host), hipMemcpyDeviceToHost, stream_of(ctx)));
+    HIP_TRY(ctx, hipStreamSynchronize(stream_of(ctx)));
+    if (unit_shift) *unit_shift = host.unit_shift;
+    if (fine_shift) *fine_shift = host.fine_shift;
+    if (coarse_sentences) *coarse_sentences = host.coarse_sent;
+    if (units) *units = host.n_units;
+    if (update) *update = (uint32_t)ctx->last_update;
+    if (wavefronts) *wavefronts = ctx->last_waves;
     return W2V_OK;
 }
 

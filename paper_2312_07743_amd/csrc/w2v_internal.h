@@ -16,13 +16,35 @@ struct Accum {
     unsigned long long next_sentence;  // work queue head of the current launch
     unsigned long long dropped;        // tokens with ids outside [0, V)
     unsigned long long kept;           // tokens that survived subsampling (windows processed)
+    // Work plan of the current launch, written by the planning kernel that precedes it: the first coarse_sent
+    // sentences are handed out as 2^unit_shift units each, the others as 2^fine_shift, n_units in all.
+    unsigned long long coarse_sent, n_units;
+    uint32_t           unit_shift, fine_shift;
+};
+
+// How a launch's sentences are to be cut into units of work (input of the planning kernel).
+struct PlanRequest {
+    uint64_t n_sent;
+    uint64_t waves;               // wavefronts the launch will have
+    int32_t  forced_unit_shift;   // -1: choose from the sizes
+    int32_t  forced_fine_shift;   // -1: choose
+    uint64_t forced_coarse_sent;  // used with forced_fine_shift
+};
+
+// Optional dump of the window kernel's own integer decisions (all NULL in production), indexed by token offset in
+// `tokens`: keep[t] = 1 and width[t], neg[t*N + k] for every token that gets a window in the launch.
+struct DrawDump {
+    uint8_t *keep, *width;
+    int32_t *neg;
 };
 
 // Layout of the caller-provided workspace (all offsets multiples of 256 bytes).
 struct WorkspaceLayout {
-    uint64_t accum_off, thr_off, table_off, total;
+    uint64_t accum_off, thr_off, snap_off, table_off, total;
 };
-WorkspaceLayout workspace_layout(uint32_t vocab, uint32_t table_size);
+WorkspaceLayout workspace_layout(uint32_t vocab, uint32_t table_size, uint64_t snap_bytes);
+// most wavefronts a launch with summed updates uses (each owns a snapshot area in the workspace)
+constexpr uint32_t kMaxSummedWaves = 4096;
 
 // Everything a training / draw kernel needs; passed by value.
 struct KernelArgs {
@@ -38,11 +60,14 @@ struct KernelArgs {
     double             lr0, lr_min_frac;
     uint32_t           vocab, dim, ld, window, negatives, window_mode, table_size;
     uint32_t           subsample;      // 0: every threshold is "always keep", thr is not read
-    uint32_t           unit_shift;     // a sentence is handed out as 2^unit_shift units of work (window kernel only)
-    uint32_t           fine_shift;     // ... the sentences from coarse_sent on as 2^fine_shift units each (the end of
-    uint64_t           coarse_sent;    //     the queue is cut finer, so that the wavefronts finish close together)
     uint32_t           neg_shift;      // 0: negatives drawn at each window's own position; s: at the first position
                                        // of the stretch of 2^s tokens (offsets in the sentence) the centre lies in
+    // Summed lock-free updates (window kernel instantiated with SUMMED): wavefront w keeps the value each of its
+    // ring slots had when it was fetched in snap + w * snap_stride floats.
+    float             *snap;
+    uint32_t           snap_stride;
+    uint32_t           hog_flags;      // experiment switches of the summed mode (see the window kernel)
+    DrawDump           dump;
 };
 
 using TrainFn = void (*)(KernelArgs);
@@ -61,13 +86,19 @@ uint32_t train_lds_bytes(const KernelArgs &a, RowShape s);
 hipError_t launch_init_weights(float *syn0, float *syn1neg, uint32_t vocab, uint32_t dim, uint32_t ld,
                                uint64_t seed, hipStream_t stream);
 hipError_t launch_reset_accum(Accum *accum, int what /*1: work counter only, 2: everything*/, hipStream_t stream);
-hipError_t launch_train(const KernelArgs &a, uint32_t waves, hipStream_t stream);
+// resets the work counter and writes the launch's work plan into accum (the token count of the call is read from
+// sent_off on the device)
+hipError_t launch_plan(Accum *accum, const uint64_t *sent_off, const PlanRequest &req, hipStream_t stream);
+hipError_t launch_train(const KernelArgs &a, int update, uint32_t waves, hipStream_t stream);
+// floats of snapshot space one wavefront of the summed mode needs (0 if the shape has no such instantiation)
+uint32_t train_snap_floats(const KernelArgs &a);
+hipError_t launch_fill_dump(const DrawDump &d, uint64_t n_tokens, uint32_t negatives, hipStream_t stream);
 hipError_t launch_train_naive(const KernelArgs &a, uint32_t waves, hipStream_t stream);
 hipError_t launch_draws(const KernelArgs &a, uint64_t n_tokens_hint, uint8_t *keep, uint8_t *width, int32_t *neg,
                         hipStream_t stream);
 hipError_t launch_reduce_selftest(const float *in, float *out, hipStream_t stream);
 // waves that fit the device at once for this configuration (0 on error)
-uint32_t train_resident_waves(const KernelArgs &a, int device);
+uint32_t train_resident_waves(const KernelArgs &a, int update, int device);
 uint32_t naive_resident_waves(int device);
 
 }  // namespace w2v
@@ -88,6 +119,12 @@ struct w2v_ctx {
     hipEvent_t           drained[2] = {nullptr, nullptr};
     bool                 drained_recorded[2] = {false, false};
     double               kept_fraction = 1.0;  // expected share of the tokens that survive subsampling (from the counts)
-    uint64_t             resident_waves = 0; // wavefronts of the window kernel the device holds (0: not asked yet)
+    uint64_t             resident_waves[2] = {0, 0}; // wavefronts of the window kernel the device holds, by update mode (0: not asked yet)
+    uint32_t             snap_floats = 0;    // snapshot floats per wavefront of the summed mode (0: no such kernel for this shape)
+    bool                 flat_corpus = false; // from the counts: the rows one L2 holds carry a small share of the tokens
+    int                  forced_update = -1; // test override: update mode of every launch, strict order included (-1: by the rules)
+    uint32_t             hog_flags = 0xFu;   // switches of the summed mode (test surface)
+    int                  last_update = 0;    // update mode and wavefronts of the last launch (test surface)
+    uint64_t             last_waves = 0;
     int                  next_half = 0;      // staging half the next batch goes to (alternates across calls too)
 };

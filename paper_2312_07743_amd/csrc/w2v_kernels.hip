@@ -32,6 +32,49 @@ __global__ void reset_accum_kernel(Accum *a, int what)
     }
 }
 
+// Cuts the launch's sentences into units of work and leaves the plan in the accumulator block.  A wavefront holds a
+// unit until it is done, so there must be enough units that the wavefronts finish within a small fraction of the
+// launch of one another; every unit re-reads the few tokens of context on either side, so units stay at 128 tokens
+// or more on average.  Lock-free launches end the queue with units half that size (the last eighth of the
+// sentences, at least 32 tokens on average).  (Measured on 17,000 sentences of 1,000 tokens: 250-token units 4 %
+// faster than whole sentences, the finer end another 1.2 %; finer still loses to the context every unit re-reads.)
+// The token count is that of this call, read from the offsets: a call that feeds part of an epoch is planned by
+// its own size.  One wavefront (strict order) gains nothing from a finer queue.
+__global__ void plan_kernel(Accum *a, const uint64_t *sent_off, PlanRequest rq)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const uint64_t n_sent = rq.n_sent;
+    const uint64_t n_tokens = n_sent ? sent_off[n_sent] - sent_off[0] : 0;
+    uint32_t shift = 0;
+    if (rq.forced_unit_shift >= 0) shift = (uint32_t)rq.forced_unit_shift;
+    else if (rq.waves > 1 && n_sent > 0)
+        while (shift < 16 && (n_sent << shift) < 16u * rq.waves && (n_tokens / n_sent) >> (shift + 1) >= 128u) ++shift;
+    uint32_t fine = shift;
+    uint64_t coarse = n_sent;
+    if (rq.forced_fine_shift >= 0) {
+        fine = (uint32_t)rq.forced_fine_shift;
+        coarse = rq.forced_coarse_sent < n_sent ? rq.forced_coarse_sent : n_sent;
+    } else if (rq.forced_unit_shift < 0 && rq.waves > 1 && n_sent > 0) {
+        if (fine < 16u && (n_tokens / n_sent) >> (fine + 1u) >= 32u) ++fine;
+        if (fine > shift) coarse = n_sent - (n_sent / 8u ? n_sent / 8u : 1u);
+    }
+    a->unit_shift = shift;
+    a->fine_shift = fine;
+    a->coarse_sent = coarse;
+    a->n_units = (coarse << shift) + ((n_sent - coarse) << fine);
+    a->next_sentence = 0;
+}
+
+// test surface: defaults of the decision dump (a token that gets no window reads as dropped)
+__global__ void fill_dump_kernel(DrawDump d, uint64_t n_tokens, uint32_t negatives)
+{
+    for (uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; t < n_tokens; t += (uint64_t)gridDim.x * blockDim.x) {
+        d.keep[t] = 0;
+        d.width[t] = 0;
+        for (uint32_t k = 0; k < negatives; ++k) d.neg[t * negatives + k] = -1;
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // draw dump: the integer decisions of every token, one thread per token
 // ---------------------------------------------------------------------------------------------
@@ -71,58 +114,16 @@ __global__ void __launch_bounds__(kLanes) reduce_selftest_kernel(const float *in
 
 }  // namespace
 
-TrainFn train_fn_v1r1k0(uint32_t window, bool full);
-TrainFn train_fn_v1r1k1(uint32_t window, bool full);
-TrainFn train_fn_v1r1k2(uint32_t window, bool full);
-TrainFn train_fn_v1r1k3(uint32_t window, bool full);
-TrainFn train_fn_v2r1k0(uint32_t window, bool full);
-TrainFn train_fn_v2r1k1(uint32_t window, bool full);
-TrainFn train_fn_v2r1k2(uint32_t window, bool full);
-TrainFn train_fn_v2r1k3(uint32_t window, bool full);
-TrainFn train_fn_v4r1k0(uint32_t window, bool full);
-TrainFn train_fn_v4r1k1(uint32_t window, bool full);
-TrainFn train_fn_v4r1k2(uint32_t window, bool full);
-TrainFn train_fn_v4r1k3(uint32_t window, bool full);
-TrainFn train_fn_v4r1t1k0(uint32_t window, bool full);
-TrainFn train_fn_v4r1t1k1(uint32_t window, bool full);
-TrainFn train_fn_v4r1t1k2(uint32_t window, bool full);
-TrainFn train_fn_v4r1t1k3(uint32_t window, bool full);
-TrainFn train_fn_v4r1t4k0(uint32_t window, bool full);
-TrainFn train_fn_v4r1t4k1(uint32_t window, bool full);
-TrainFn train_fn_v4r1t4k2(uint32_t window, bool full);
-TrainFn train_fn_v4r1t4k3(uint32_t window, bool full);
-TrainFn train_fn_v1r5k0(uint32_t window, bool full);
-TrainFn train_fn_v1r5k1(uint32_t window, bool full);
-TrainFn train_fn_v1r5k2(uint32_t window, bool full);
-TrainFn train_fn_v1r5k3(uint32_t window, bool full);
-TrainFn train_fn_v4r2k0(uint32_t window, bool full);
-TrainFn train_fn_v4r2k1(uint32_t window, bool full);
-TrainFn train_fn_v4r2k2(uint32_t window, bool full);
-TrainFn train_fn_v4r2k3(uint32_t window, bool full);
+#include "w2v_train_table.inc"      // generated by build.py: one entry per instantiation unit that was built
 
 namespace {
-TrainFn train_fn(const KernelArgs &a, RowShape s)
+TrainFn train_fn(const KernelArgs &a, RowShape s, int update)
 {
     const bool full = a.dim == (uint32_t)(kLanes * floats_per_lane(s));
     const uint32_t rows = a.negatives + 1;                  // output rows of a window
     const int kmode = rows > 2u * KC ? 3 : rows > (uint32_t)KC ? 2 : rows == (uint32_t)KC ? 1 : 0;
-#define W2V_PICK(VW, R)                                                                              \
-    if (s.vw == VW && s.r == R && s.tail == 0)                                                       \
-        return kmode == 3 ? train_fn_v##VW##r##R##k3(a.window, full)                                 \
-             : kmode == 2 ? train_fn_v##VW##r##R##k2(a.window, full)                                 \
-             : kmode == 1 ? train_fn_v##VW##r##R##k1(a.window, full) : train_fn_v##VW##r##R##k0(a.window, full);
-    if (s.vw == 4 && s.r == 1 && s.tail == 1)
-        return kmode == 3 ? train_fn_v4r1t1k3(a.window, full) : kmode == 2 ? train_fn_v4r1t1k2(a.window, full)
-             : kmode == 1 ? train_fn_v4r1t1k1(a.window, full) : train_fn_v4r1t1k0(a.window, full);
-    if (s.vw == 4 && s.r == 1 && s.tail == 4)
-        return kmode == 3 ? train_fn_v4r1t4k3(a.window, full) : kmode == 2 ? train_fn_v4r1t4k2(a.window, full)
-             : kmode == 1 ? train_fn_v4r1t4k1(a.window, full) : train_fn_v4r1t4k0(a.window, full);
-    W2V_PICK(1, 1)
-    W2V_PICK(2, 1)
-    W2V_PICK(4, 1)
-    W2V_PICK(1, 5)
-    W2V_PICK(4, 2)
-#undef W2V_PICK
+    for (const TrainEntry &e : kTrainTable)
+        if (e.vw == s.vw && e.r == s.r && e.tail == s.tail && e.kmode == kmode) return e.get(a.window, full, update);
     return nullptr;
 }
 }  // namespace
@@ -169,11 +170,32 @@ hipError_t launch_reset_accum(Accum *accum, int what, hipStream_t stream)
     return hipGetLastError();
 }
 
-uint32_t train_resident_waves(const KernelArgs &a, int device)
+hipError_t launch_plan(Accum *accum, const uint64_t *sent_off, const PlanRequest &req, hipStream_t stream)
+{
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(64), 0, stream, accum, sent_off, req);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_dump(const DrawDump &d, uint64_t n_tokens, uint32_t negatives, hipStream_t stream)
+{
+    if (n_tokens == 0) return hipSuccess;
+    const uint32_t blocks = (uint32_t)((n_tokens + 255) / 256 < 16384 ? (n_tokens + 255) / 256 : 16384);
+    hipLaunchKernelGGL(fill_dump_kernel, dim3(blocks), dim3(256), 0, stream, d, n_tokens, negatives);
+    return hipGetLastError();
+}
+
+uint32_t train_snap_floats(const KernelArgs &a)
+{
+    RowShape s;
+    if (!pick_row_shape(a.dim, a.ld, &s) || !train_fn(a, s, 1)) return 0;
+    return (2 * a.window + 2) * (uint32_t)(kLanes * floats_per_lane(s));
+}
+
+uint32_t train_resident_waves(const KernelArgs &a, int update, int device)
 {
     RowShape s;
     if (!pick_row_shape(a.dim, a.ld, &s)) return 0;
-    TrainFn fn = train_fn(a, s);
+    TrainFn fn = train_fn(a, s, update);
     if (!fn) return 0;
     int per_cu = 0, cus = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kLanes, train_lds_bytes(a, s)) != hipSuccess) return 0;
@@ -181,11 +203,11 @@ uint32_t train_resident_waves(const KernelArgs &a, int device)
     return (uint32_t)(per_cu > 0 ? per_cu : 1) * (uint32_t)(cus > 0 ? cus : 1);
 }
 
-hipError_t launch_train(const KernelArgs &a, uint32_t waves, hipStream_t stream)
+hipError_t launch_train(const KernelArgs &a, int update, uint32_t waves, hipStream_t stream)
 {
     RowShape s;
     if (!pick_row_shape(a.dim, a.ld, &s)) return hipErrorInvalidValue;
-    TrainFn fn = train_fn(a, s);
+    TrainFn fn = train_fn(a, s, update);
     if (!fn) return hipErrorInvalidValue;
     hipLaunchKernelGGL(fn, dim3(waves), dim3(kLanes), train_lds_bytes(a, s), stream, a);
     return hipGetLastError();

@@ -198,30 +198,34 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t row_resource(const float *base
 {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(base), 0, (int)bytes, 0x00020000);
 }
-template <int VW>
+// AUX is the cache-policy operand of the buffer instructions: 0 = ordinary (served by the L2 of the wavefront's own
+// XCD), kSystemScope = sc0 sc1: the access is made at the memory side that all XCDs share (loads do not hit in
+// L2, stores are written through), which is what keeps rows coherent between wavefronts on different XCDs.
+constexpr int kSystemScope = 0x11;
+template <int VW, int AUX = 0>
 __device__ __forceinline__ void row_load_vec(__amdgpu_buffer_rsrc_t rs, int lane_bytes, uint32_t row_bytes_off, float *dst)
 {
     if constexpr (VW == 1) {
-        dst[0] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, lane_bytes, (int)row_bytes_off, 0));
+        dst[0] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, lane_bytes, (int)row_bytes_off, AUX));
     } else if constexpr (VW == 2) {
-        const vec2u t = __builtin_amdgcn_raw_buffer_load_b64(rs, lane_bytes, (int)row_bytes_off, 0);
+        const vec2u t = __builtin_amdgcn_raw_buffer_load_b64(rs, lane_bytes, (int)row_bytes_off, AUX);
         dst[0] = __uint_as_float(t.x); dst[1] = __uint_as_float(t.y);
     } else {
-        const vec4u t = __builtin_amdgcn_raw_buffer_load_b128(rs, lane_bytes, (int)row_bytes_off, 0);
+        const vec4u t = __builtin_amdgcn_raw_buffer_load_b128(rs, lane_bytes, (int)row_bytes_off, AUX);
         dst[0] = __uint_as_float(t.x); dst[1] = __uint_as_float(t.y); dst[2] = __uint_as_float(t.z); dst[3] = __uint_as_float(t.w);
     }
 }
-template <int VW>
+template <int VW, int AUX = 0>
 __device__ __forceinline__ void row_store_vec(__amdgpu_buffer_rsrc_t rs, int lane_bytes, uint32_t row_bytes_off, const float *src)
 {
     if constexpr (VW == 1) {
-        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(src[0]), rs, lane_bytes, (int)row_bytes_off, 0);
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(src[0]), rs, lane_bytes, (int)row_bytes_off, AUX);
     } else if constexpr (VW == 2) {
         vec2u t; t.x = __float_as_uint(src[0]); t.y = __float_as_uint(src[1]);
-        __builtin_amdgcn_raw_buffer_store_b64(t, rs, lane_bytes, (int)row_bytes_off, 0);
+        __builtin_amdgcn_raw_buffer_store_b64(t, rs, lane_bytes, (int)row_bytes_off, AUX);
     } else {
         vec4u t; t.x = __float_as_uint(src[0]); t.y = __float_as_uint(src[1]); t.z = __float_as_uint(src[2]); t.w = __float_as_uint(src[3]);
-        __builtin_amdgcn_raw_buffer_store_b128(t, rs, lane_bytes, (int)row_bytes_off, 0);
+        __builtin_amdgcn_raw_buffer_store_b128(t, rs, lane_bytes, (int)row_bytes_off, AUX);
     }
 }
 
@@ -263,10 +267,14 @@ constexpr uint32_t kNoWord = 0xFFFFFFFFu;
 // because LDS then limits the CU; 3 for rows of 4 floats per lane spills)
 constexpr int occupancy_goal(int e, int wcap) { return (e == 1 && wcap <= 5) ? 4 : (e <= 2 && wcap <= 10) ? 3 : ((e * wcap <= 25) ? 2 : 1); }
 
-template <int VW, int R, int TAIL, int WCAP, bool FULL, int KMODE>
+// SUMMED: lock-free updates are added to what memory holds when a row goes back, instead of overwriting it with a copy
+// that was fetched up to 2W+1 windows earlier (see "summed updates" below); all table accesses are then made at
+// system scope.
+template <int VW, int R, int TAIL, int WCAP, bool FULL, int KMODE, bool SUMMED>
 __global__ void __launch_bounds__(kLanes) __attribute__((amdgpu_waves_per_eu(occupancy_goal(VW * R + TAIL, WCAP))))
 train_kernel(KernelArgs A)
 {
+    static_assert(!(SUMMED && FULL), "the summed mode reaches every row through a buffer resource");
     constexpr int E = VW * R + TAIL;     // floats of a row per lane
     constexpr int NCH = R + TAIL;        // chunks of a row per lane: R of VW floats, then TAIL single floats
     constexpr int ROWF = kLanes * E;     // floats of a ring row in LDS
@@ -308,6 +316,8 @@ train_kernel(KernelArgs A)
 
     const uint32_t row_bytes = A.dim * 4u;
     // row `word` of a table -> registers (zeros beyond dim) / registers -> the row (nothing beyond dim)
+    // (summed mode: at system scope when the launch asks for it, one wave-uniform branch per row)
+    const bool sys_loads = SUMMED && (A.hog_flags & 4u), sys_stores = SUMMED && (A.hog_flags & 8u);
     auto load_row = [&](const float *table, uint32_t word, float *dst) {
         const float *row = table + (size_t)word * A.ld;
         if constexpr (FULL) {
@@ -317,10 +327,17 @@ train_kernel(KernelArgs A)
             });
         } else {
             const __amdgpu_buffer_rsrc_t rs = row_resource(row, row_bytes);
-            chunks([&](auto r_, auto w_, auto o_) {
-                constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
-                row_load_vec<CW>(rs, eoff[r] * 4, 0u, dst + RO);
-            });
+            if (sys_loads) {
+                chunks([&](auto r_, auto w_, auto o_) {
+                    constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
+                    row_load_vec<CW, kSystemScope>(rs, eoff[r] * 4, 0u, dst + RO);
+                });
+            } else {
+                chunks([&](auto r_, auto w_, auto o_) {
+                    constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
+                    row_load_vec<CW>(rs, eoff[r] * 4, 0u, dst + RO);
+                });
+            }
         }
     };
     auto store_row = [&](float *table, uint32_t word, const float *src) {
@@ -332,11 +349,41 @@ train_kernel(KernelArgs A)
             });
         } else {
             const __amdgpu_buffer_rsrc_t rs = row_resource(row, row_bytes);
-            chunks([&](auto r_, auto w_, auto o_) {
-                constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
-                row_store_vec<CW>(rs, eoff[r] * 4, 0u, src + RO);
-            });
+            if (sys_stores) {
+                chunks([&](auto r_, auto w_, auto o_) {
+                    constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
+                    row_store_vec<CW, kSystemScope>(rs, eoff[r] * 4, 0u, src + RO);
+                });
+            } else {
+                chunks([&](auto r_, auto w_, auto o_) {
+                    constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
+                    row_store_vec<CW>(rs, eoff[r] * 4, 0u, src + RO);
+                });
+            }
         }
+    };
+    // Summed updates.  A wavefront works on copies: a context row stays in its ring for up to 2W+1 windows, an
+    // output row in its registers from the fetch one window ahead to the end of its window.  Writing the copy back
+    // discards whatever other wavefronts added to the row meanwhile.  In the summed mode a row goes back as
+    // (what memory holds now) + (copy - value the copy started from): the update is added, and the time in which
+    // another wavefront's update can be lost shrinks from the copy's lifetime to one memory round trip.  The
+    // starting value of a ring slot is kept in a snapshot row of the wavefront's own in global memory (written
+    // when the slot is filled, read when it is evicted); an output row's starting value is still in registers.
+    const bool sum_ring = SUMMED && (A.hog_flags & 1u), sum_out = SUMMED && (A.hog_flags & 2u);
+    float *snap_base = SUMMED ? A.snap + (size_t)blockIdx.x * A.snap_stride : nullptr;
+    auto snap_store = [&](uint32_t slot, const float *src) {
+        float *row = snap_base + (size_t)slot * ROWF;
+        chunks([&](auto r_, auto w_, auto o_) {
+            constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
+            store_vec<CW>(row + eoff[r], src + RO);
+        });
+    };
+    auto snap_load = [&](uint32_t slot, float *dst) {
+        const float *row = snap_base + (size_t)slot * ROWF;
+        chunks([&](auto r_, auto w_, auto o_) {
+            constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
+            load_vec<CW>(row + eoff[r], dst + RO);
+        });
     };
     auto load_ctx = [&](uint32_t word, float *dst) { load_row(A.syn0, word, dst); };
     auto load_out = [&](uint32_t word, float *dst) { load_row(A.syn1neg, word, dst); };
@@ -362,6 +409,9 @@ train_kernel(KernelArgs A)
 
     double loss_acc = 0.0;
     unsigned long long pairs_acc = 0, dropped_acc = 0, kept_acc = 0;
+    // the launch's work plan (written by the planning kernel that precedes the launch on the stream)
+    const uint32_t plan_unit_shift = uni(A.accum->unit_shift), plan_fine_shift = uni(A.accum->fine_shift);
+    const uint64_t plan_coarse = uni64(A.accum->coarse_sent), plan_units = uni64(A.accum->n_units);
 
     for (;;) {
         // ---- next unit of work from the queue ---------------------------------------------------
@@ -372,13 +422,13 @@ train_kernel(KernelArgs A)
         unsigned long long q_raw = 0;
         if (lane == 0) q_raw = atomicAdd(&A.accum->next_sentence, 1ull);
         const uint64_t q = uni64(q_raw);
-        // (sentences from A.coarse_sent on are cut into 2^fine_shift stretches instead: the queue ends in small units)
-        const uint64_t n_coarse = A.coarse_sent << A.unit_shift;
-        if (q >= n_coarse + ((A.n_sent - A.coarse_sent) << A.fine_shift)) break;
+        // (sentences from plan_coarse on are cut into 2^fine_shift stretches instead: the queue ends in small units)
+        const uint64_t n_coarse = plan_coarse << plan_unit_shift;
+        if (q >= plan_units) break;
         const bool fine = q >= n_coarse;
-        const uint32_t shift = fine ? A.fine_shift : A.unit_shift;
+        const uint32_t shift = fine ? plan_fine_shift : plan_unit_shift;
         const uint64_t qs = fine ? q - n_coarse : q;                 // index among the units of its own kind
-        const uint64_t s = (fine ? A.coarse_sent : 0ull) + (qs >> shift);
+        const uint64_t s = (fine ? plan_coarse : 0ull) + (qs >> shift);
         const uint64_t t0 = uni64(A.sent_off[s]);
         const uint64_t t1 = uni64(A.sent_off[s + 1]);
         const uint32_t len = (t1 > t0) ? (uint32_t)(t1 - t0) : 0u;
@@ -449,18 +499,31 @@ train_kernel(KernelArgs A)
             if (lane == (int)(p & 63u)) { meta_word = word; meta_slot = slot; }
             return fetch;
         };
-        // position p leaves the ring; its row goes back to syn0 unless another position shares it
-        auto ring_leave = [&](uint32_t p) {
+        // position p leaves the ring: true if its row must go back to syn0 (no other position shares it)
+        auto leave_decide = [&](uint32_t p, uint32_t &slot, uint32_t &word) -> bool {
             const uint32_t l = p & 63u;
-            const uint32_t slot = lane_value(meta_slot, l);
-            const int32_t word = (int32_t)lane_value((uint32_t)meta_word, l);
+            slot = lane_value(meta_slot, l);
+            word = lane_value((uint32_t)meta_word, l);
             if (lane == (int)l) meta_word = -1;
-            const uint64_t shared = __ballot(meta_word >= 0 && meta_slot == slot);
-            if (!shared) {
-                float t[E];
-                ring_to_regs(ring + (size_t)slot * ROWF, t);
-                store_row(A.syn0, (uint32_t)word, t);
-                give_slot(slot);
+            return __ballot(meta_word >= 0 && meta_slot == slot) == 0;
+        };
+        // the row of `slot` goes back: as it is, or (summed mode) as fresh + (row - snapshot)
+        auto leave_finish = [&](uint32_t slot, uint32_t word, const float *fresh, const float *snapv) {
+            float t[E];
+            ring_to_regs(ring + (size_t)slot * ROWF, t);
+            if (sum_ring) {
+#pragma unroll
+                for (int x = 0; x < E; ++x) t[x] = fresh[x] + (t[x] - snapv[x]);
+            }
+            store_row(A.syn0, word, t);
+            give_slot(slot);
+        };
+        auto ring_leave = [&](uint32_t p) {
+            uint32_t slot, word;
+            if (leave_decide(p, slot, word)) {
+                float fresh[E] = {}, snapv[E] = {};
+                if (sum_ring) { load_row(A.syn0, word, fresh); snap_load(slot, snapv); }
+                leave_finish(slot, word, fresh, snapv);
             }
         };
 
@@ -503,6 +566,8 @@ train_kernel(KernelArgs A)
                 my_b = (i0 + lane < n_lead) ? 0u : window_width(base, W, A.window_mode);   // lead-in tokens: context only
                 // negatives: drawn at my own position, or at the first position of my stretch of 2^neg_shift tokens
                 my_stretch = my_off >> A.neg_shift;
+                const bool dump = A.dump.keep != nullptr && i0 + lane >= n_lead;   // test surface: my own decisions
+                if (dump) { A.dump.keep[t0 + my_off] = 1; A.dump.width[t0 + my_off] = (uint8_t)my_b; }
                 const uint64_t nbase = A.neg_shift ? position_base(A.key, A.first_pos + t0 + (my_stretch << A.neg_shift)) : base;
                 const uint32_t pe = i0 + lane + W + 1;
                 if (pe < n_prod) my_enter = (uint32_t)kw[pe & (FCAP - 1)];
@@ -513,6 +578,7 @@ train_kernel(KernelArgs A)
                     for (int k = 0; k < KC - 1; ++k) {
                         nid[k] = kIdMask + 1u + (uint32_t)k;
                         if (KEXACT || (uint32_t)k < N) nid[k] = (uint32_t)A.table[negative_slot(nbase, (uint32_t)k, A.table_size)];
+                        if (dump && (KEXACT || (uint32_t)k < N)) A.dump.neg[(t0 + my_off) * N + k] = (int32_t)nid[k];
                     }
 #pragma unroll
                     for (int k = 0; k < KC - 1; ++k) {
@@ -530,6 +596,7 @@ train_kernel(KernelArgs A)
                     }
                 } else {
                     for (uint32_t k = 0; k < N; ++k) pk[k] = (uint32_t)A.table[negative_slot(nbase, k, A.table_size)];
+                    if (dump) for (uint32_t k = 0; k < N; ++k) A.dump.neg[(t0 + my_off) * N + k] = (int32_t)pk[k];
                     for (uint32_t k = 0; k < N; ++k) {
                         const uint32_t id = pk[k] & kIdMask;
                         uint32_t m = (id == (uint32_t)my_w) ? 0u : 1u;
@@ -622,7 +689,7 @@ train_kernel(KernelArgs A)
             // negative distinct and different from either target, some context to train on).  The handing window
             // skips the stores of its negative rows, the receiving one skips their fetch.
             uint32_t hand_over = 0;
-            if constexpr (!MULTI) {
+            if constexpr (!MULTI && !SUMMED) {
                 const uint32_t ok = (have && A.neg_shift && my_b != 0u && my_plain && !overflow && n_prod > 1u) ? 1u : 0u;
                 const uint32_t mine = (my_stretch << 1) | ok;
                 const uint32_t next = (uint32_t)__shfl_down((int)mine, 1, kLanes);
@@ -647,6 +714,7 @@ train_kernel(KernelArgs A)
                         float t[E];
                         load_ctx((uint32_t)word, t);
                         regs_to_ring(ring + (size_t)slot * ROWF, t);
+                        if (sum_ring) snap_store(slot, t);
                     }
                     ++n_ins;
                 }
@@ -695,6 +763,17 @@ train_kernel(KernelArgs A)
                     pend = ring_enter(n_ins, (int32_t)enter_word, pend_slot);
                     if (pend) load_ctx(enter_word, pend_row);
                     ++n_ins;
+                }
+                //     summed mode: the position that leaves the span after this window is known now; what memory holds
+                //     of its row and the slot's snapshot are requested here and used in step (h)
+                bool lv = false;
+                uint32_t lv_slot = 0, lv_word = 0;
+                float lv_fresh[SUMMED ? E : 1] = {}, lv_snap[SUMMED ? E : 1] = {};
+                if constexpr (SUMMED) {
+                    if (sum_ring && i >= W) {
+                        lv = leave_decide(i - W, lv_slot, lv_word);
+                        if (lv) { load_row(A.syn0, lv_word, lv_fresh); snap_load(lv_slot, lv_snap); }
+                    }
                 }
 
                 // (c) contexts of this window: slot c <-> distance a=(c>>1)+1, right side if c odd;
@@ -776,6 +855,20 @@ train_kernel(KernelArgs A)
                         for (int kk = 0; kk < KC; ++kk)
 #pragma unroll
                             for (int x = 0; x < E; ++x) dO[kk][x] = 0.0f;
+                        // summed mode: what memory holds of the output rows now, requested while the last block's
+                        // multiply-adds run and added to this window's deltas in step (f)
+                        float FR[SUMMED ? KC : 1][SUMMED ? E : 1];
+                        bool fresh_loaded = false;
+                        auto load_fresh = [&]() {
+                            if constexpr (SUMMED) {
+#pragma unroll
+                                for (int kk = 0; kk < KC; ++kk) {
+                                    const uint32_t pk = lane_value(pv, (uint32_t)kk);
+                                    if ((KEXACT || kb + kk <= N) && (!GENERAL || (pk >> kIdBits))) load_out(pk & kIdMask, FR[kk]);
+                                }
+                            }
+                            fresh_loaded = true;
+                        };
 
                         static_for<NQW>([&](auto q_tag) {
                             // NC context rows (slots C0 .. C0+NC-1) against the KC output rows
@@ -823,6 +916,7 @@ train_kernel(KernelArgs A)
                             }
                             // every lane needs every g: straight-line windows take it through the row-broadcast
                             // operand of the multiply-adds, the general path through scalar registers
+                            if constexpr (SUMMED && q == NQW - 1) { if (sum_out) load_fresh(); }
                             float G[4] = {0.0f, 0.0f, 0.0f, 0.0f};
                             if constexpr (!MASKED) rows_to_all<(NC * KC + 15) / 16>(g, G);
                             static_for<CC>([&](auto cc_tag) {
@@ -899,13 +993,19 @@ train_kernel(KernelArgs A)
 #pragma unroll
                                 for (int x = 0; x < E; ++x) OB[kk][x] += dO[kk][x];
                         } else {
+                            if constexpr (SUMMED) { if (sum_out && !fresh_loaded) load_fresh(); }
 #pragma unroll
                             for (int kk = 0; kk < KC; ++kk) {
                                 const uint32_t pk = lane_value(pv, (uint32_t)kk);
                                 if ((KEXACT || kb + kk <= N) && (!GENERAL || (pk >> kIdBits))) {
                                     float t[E];
+                                    if constexpr (SUMMED) {
 #pragma unroll
-                                    for (int x = 0; x < E; ++x) t[x] = OB[kk][x] + dO[kk][x];
+                                        for (int x = 0; x < E; ++x) t[x] = (sum_out ? FR[kk][x] : OB[kk][x]) + dO[kk][x];
+                                    } else {
+#pragma unroll
+                                        for (int x = 0; x < E; ++x) t[x] = OB[kk][x] + dO[kk][x];
+                                    }
                                     store_out(pk & kIdMask, t);
                                 }
                             }
@@ -1000,8 +1100,14 @@ train_kernel(KernelArgs A)
                 //     (every lane only touches its own elements of a ring row: no barrier needed)
                 if (pend) {
                     regs_to_ring(ring + (size_t)pend_slot * ROWF, pend_row);
+                    if (sum_ring) snap_store(pend_slot, pend_row);
                 }
-                if (i >= W) ring_leave(i - W);
+                if constexpr (SUMMED) {
+                    if (sum_ring) { if (lv) leave_finish(lv_slot, lv_word, lv_fresh, lv_snap); }
+                    else if (i >= W) ring_leave(i - W);
+                } else {
+                    if (i >= W) ring_leave(i - W);
+                }
 
                 // (i) next window's scalars and rows become current
                 if (has_next) {
@@ -1027,7 +1133,30 @@ train_kernel(KernelArgs A)
         // ---- sentence done: the rows still in the ring go back -------------------------------------
         {
             const uint32_t first = (n_own > W) ? n_own - W : 0u;     // positions < first left already
-            for (uint32_t p = first; p < n_ins; ++p) ring_leave(p);
+            if (sum_ring) {
+                // four rows at a time: their loads travel together
+                uint32_t p = first;
+                while (p < n_ins) {
+                    uint32_t sl[4], wd[4];
+                    bool on[4];
+                    float fr[4][E], sn[4][E];
+                    static_for<4>([&](auto b_) {
+                        constexpr int b = decltype(b_)::value;
+                        on[b] = false;
+                        if (p < n_ins) { on[b] = leave_decide(p, sl[b], wd[b]); ++p; }
+                    });
+                    static_for<4>([&](auto b_) {
+                        constexpr int b = decltype(b_)::value;
+                        if (on[b]) { load_row(A.syn0, wd[b], fr[b]); snap_load(sl[b], sn[b]); }
+                    });
+                    static_for<4>([&](auto b_) {
+                        constexpr int b = decltype(b_)::value;
+                        if (on[b]) leave_finish(sl[b], wd[b], fr[b], sn[b]);
+                    });
+                }
+            } else {
+                for (uint32_t p = first; p < n_ins; ++p) ring_leave(p);
+            }
         }
         __syncthreads();
     }

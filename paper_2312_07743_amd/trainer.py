@@ -6,15 +6,23 @@ import torch
 from . import binding as B
 
 
-_UNCACHED = []          # uncached device allocations are kept until the process ends (see _uncached_zeros)
+_UNCACHED = []          # every uncached device allocation of the process: (pointer, owner of the interface dict)
+_UNCACHED_FREE = {}     # (device index, shape) -> tensors handed back by Trainer.close(), reused by later Trainers
 
 
 def _uncached_zeros(shape, dev):
     """float32 zeros in device memory that the L2 caches do not hold (hipExtMallocWithFlags, hipDeviceMallocUncached),
     as a torch tensor.  Every access then goes to the memory side, which all eight XCDs share, so a wavefront sees
     the rows another XCD has just written.  The allocation is never freed: freeing uncached memory that kernels
-    have read has been followed by wrong values in later allocations on this platform."""
+    have read has been followed by wrong values in later allocations on this platform.  Trainer.close() returns
+    its buffers to a pool instead, and a later Trainer of the same shape takes them from there, so a process that
+    builds many Trainers holds as much uncached memory as the most it used at one time."""
     import ctypes as C
+    key = (dev.index or 0, tuple(int(x) for x in shape))
+    if _UNCACHED_FREE.get(key):
+        t = _UNCACHED_FREE[key].pop()
+        t.zero_()
+        return t
     hip = C.CDLL("libamdhip64.so")
     hip.hipExtMallocWithFlags.argtypes = [C.POINTER(C.c_void_p), C.c_size_t, C.c_uint]
     n = int(np.prod(shape))
@@ -39,35 +47,32 @@ class Trainer:
     def __init__(self, *, vocab, dim, window, negatives, counts, tokens_per_epoch, seed, table_size=1 << 24,
                  subsample_t=0.0, total_epochs=1, sentences_in_flight=0, window_mode=0, lr0=0.025,
                  lr_min_frac=1e-4, device=0, init_weights=True, syn0=None, syn1neg=None, negative_block=0,
-                 coherent_tables=False):
-        """coherent_tables: keep syn0 / syn1neg in uncached device memory.  Lock-free wavefronts on different XCDs
-        then read each other's updates instead of what their own L2 last saw.  Worth it where the words of a
-        window are spread over a large vocabulary (random walks on graphs: 6 % slower, and the loss of an epoch
-        on 128 wavefronts within 0.5 % of strict order instead of 3.3 %); text, whose frequent rows live in L2,
-        trains four times slower with it for a gain of 0.2 % in loss.  "auto" decides from the counts."""
+                 coherent_tables=False, update_mode=0):
+        """update_mode: cfg.update_mode of the library (0 automatic, 1 overwrite, 2 summed lock-free updates).
+        coherent_tables (experiments only; the library's summed mode reaches the same end with system-scope
+        accesses to ordinary memory): keep syn0 / syn1neg, or the one table named, in uncached device memory.  Such
+        memory is never freed (see _uncached_zeros); close() hands it to a pool for later Trainers."""
         if not torch.cuda.is_available():
             raise RuntimeError("the SGNS trainer needs a GPU; there is no CPU implementation in this package")
         self.dev = torch.device("cuda", device)
         self.vocab, self.dim, self.window, self.negatives = vocab, dim, window, negatives
         self.ld = B.w2v_query_ld(dim)
-        if coherent_tables == "auto":
-            # uncached when the rows that fit one XCD's L2 (2 MB per table) carry under 30 % of the tokens: those are
-            # the corpora (walks over a large graph) that gain from coherent rows and lose little speed without L2
-            by_count = np.sort(np.asarray(counts, dtype=np.float64))[::-1]
-            rows = max(1, (2 << 20) // (self.ld * 4))
-            coherent_tables = bool(by_count[:rows].sum() < 0.3 * max(by_count.sum(), 1.0))
         self.coherent_tables = coherent_tables
+        self._uncached = []
 
-        def table(name):       # coherent_tables may also name one table ("syn0" / "syn1neg") for experiments
+        def table(name):       # coherent_tables may also name one table ("syn0" / "syn1neg")
             if coherent_tables is True or coherent_tables == name:
-                return _uncached_zeros((vocab, self.ld), self.dev)
+                t = _uncached_zeros((vocab, self.ld), self.dev)
+                self._uncached.append(t)
+                return t
             return torch.zeros((vocab, self.ld), dtype=torch.float32, device=self.dev)
         self.syn0, self.syn1neg = table("syn0"), table("syn1neg")
         if syn0 is not None:
             self.syn0[:, :dim] = torch.as_tensor(np.asarray(syn0, np.float32)).to(self.dev)
             self.syn1neg[:, :dim] = torch.as_tensor(np.asarray(syn1neg, np.float32)).to(self.dev)
             init_weights = False
-        ws_bytes = B.w2v_query_workspace(vocab, table_size)
+        ws_bytes = B.w2v_query_workspace(vocab, table_size, dim=dim, window=window, negatives=negatives,
+                                         window_mode=window_mode, update_mode=update_mode)
         self.workspace = torch.zeros(ws_bytes, dtype=torch.uint8, device=self.dev)
         assert self.workspace.data_ptr() % 256 == 0
         self.stream = torch.cuda.current_stream(self.dev)
@@ -76,7 +81,7 @@ class Trainer:
                                  ld=self.ld, workspace=self.workspace, workspace_bytes=ws_bytes, device=device,
                                  stream=self.stream.cuda_stream, window_mode=window_mode, total_epochs=total_epochs,
                                  sentences_in_flight=sentences_in_flight, lr0=lr0, lr_min_frac=lr_min_frac,
-                                 subsample_t=subsample_t, negative_block=negative_block)
+                                 subsample_t=subsample_t, negative_block=negative_block, update_mode=update_mode)
         torch.cuda.synchronize(self.dev)
         self.ctx = B.w2v_create(self.cfg, 1 if init_weights else 0)
         B.w2v_build_unigram_table(self.ctx, counts, table_size)
@@ -133,10 +138,26 @@ class Trainer:
         torch.cuda.synchronize(self.dev)
         return keep.cpu().numpy(), width.cpu().numpy(), neg.cpu().numpy()[:, :self.negatives]
 
+    def train_draws(self, epoch=0, first_token_global_pos=0):
+        """One training pass in which the window kernel itself writes out its integer decisions."""
+        T = self.n_tokens
+        keep = torch.empty(T, dtype=torch.uint8, device=self.dev)
+        width = torch.empty(T, dtype=torch.uint8, device=self.dev)
+        neg = torch.empty((T, max(self.negatives, 1)), dtype=torch.int32, device=self.dev)
+        if self.negatives == 0:
+            neg.fill_(-1)
+        B.w2v_debug_train_draws(self.ctx, self.tokens, self.sent_off, self.n_sent, first_token_global_pos, epoch, keep,
+                                width, neg.view(-1)[:T * self.negatives] if self.negatives else neg)
+        torch.cuda.synchronize(self.dev)
+        return keep.cpu().numpy(), width.cpu().numpy(), neg.view(-1)[:T * self.negatives].view(T, self.negatives).cpu().numpy()
+
     def close(self):
         if self.ctx is not None:
-            B.w2v_destroy(self.ctx)
+            B.w2v_destroy(self.ctx)           # waits for the stream: nothing uses the tables any more
             self.ctx = None
+            for t in self._uncached:
+                _UNCACHED_FREE.setdefault((self.dev.index or 0, tuple(t.shape)), []).append(t)
+            self._uncached = []
 
     def __del__(self):
         try:

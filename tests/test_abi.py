@@ -52,6 +52,13 @@ def test_query_ld_and_workspace():
     assert big - small >= 4 * ((1 << 20) - (1 << 10)) and small % 256 == 0
     with pytest.raises(B.W2VError):
         B.w2v_query_workspace(1000, 0)
+    # summed lock-free updates keep a snapshot of (2W+2) ring rows for each of up to 4,096 wavefronts
+    auto = B.w2v_query_workspace(1000, 1 << 10, dim=128, window=10, negatives=5, update_mode=0)
+    assert auto - small == 4096 * 22 * 128 * 4
+    assert B.w2v_query_workspace(1000, 1 << 10, dim=128, window=10, negatives=5, window_mode=1, update_mode=2) - small == 4096 * 12 * 128 * 4
+    # no such kernel for rows of more than 256 floats or fewer than 5 negatives: no snapshot space
+    assert B.w2v_query_workspace(1000, 1 << 10, dim=300, window=5, negatives=10, update_mode=0) == small
+    assert B.w2v_query_workspace(1000, 1 << 10, dim=128, window=5, negatives=2, update_mode=0) == small
 
 
 def _good_cfg(**over):
@@ -63,7 +70,8 @@ def _good_cfg(**over):
 
 @pytest.mark.parametrize("over", [
     dict(vocab=0), dict(vocab=(1 << 27) + 1), dict(dim=0), dict(dim=513), dict(window=0), dict(window=17),
-    dict(negatives=21), dict(window_mode=2), dict(negative_block=3), dict(negative_block=128),
+    dict(negatives=21), dict(window_mode=2), dict(negative_block=3), dict(negative_block=128), dict(update_mode=3),
+    dict(update_mode=2, dim=300, ld=320), dict(update_mode=2, negatives=3), dict(update_mode=2, window=11),
     dict(total_epochs=0), dict(tokens_per_epoch=0), dict(lr0=0.0),
     dict(lr0=float("nan")), dict(lr_min_frac=1.5), dict(subsample_t=-1.0), dict(syn0=None), dict(syn1neg=None),
     dict(ld=127), dict(ld=64), dict(ld=130), dict(workspace=None), dict(workspace=0x10001), dict(device=-1),
@@ -98,6 +106,9 @@ def test_null_context_is_an_error_everywhere():
     assert L.w2v_debug_draws(None, None, None, 1, 0, 0, None, None, None) == B.W2V_EINVAL
     assert L.w2v_debug_reduce(None, None, None) == B.W2V_EINVAL
     assert L.w2v_debug_set_units(None, 0) == B.W2V_EINVAL
+    assert L.w2v_debug_train_draws(None, None, None, 1, 0, 0, None, None, None) == B.W2V_EINVAL
+    assert L.w2v_debug_set_update(None, 0, 15) == B.W2V_EINVAL
+    assert L.w2v_debug_get_plan(None, None, None, None, None, None, None) == B.W2V_EINVAL
     assert L.w2v_debug_set_unit_tail(None, 0, 0) == B.W2V_EINVAL
     assert L.w2v_train_epoch_host(None, None, None, 1, 0, 0, None, 0) == B.W2V_EINVAL
 

@@ -138,14 +138,21 @@ def test_tables_in_uncached_memory_train_the_same(orc32):
     assert_rows_close(got[1][1], r1, 1e-4, "syn1neg")
 
 
-def test_automatic_choice_of_uncached_tables():
-    """coherent_tables="auto": text (a few thousand frequent rows carry most tokens) keeps cached tables, walks over a
-    graph with far more nodes than an L2 holds rows get uncached ones."""
+def test_automatic_choice_of_the_update_mode():
+    """cfg.update_mode = 0: text (a few thousand frequent rows carry most tokens) is trained with overwriting
+    updates, walks over a graph with far more nodes than an L2 holds rows with summed ones; strict order and
+    update_mode = 1 always overwrite, update_mode = 2 sums on text too."""
     from paper_2312_07743_amd.trainer import Trainer
     text = synth.zipf_corpus(71000, 1.05, 50, 1000, seed=2)
     walks = synth.barabasi_albert_walks(n_nodes=200000, m=5, walks_per_node=1, walk_len=20, seed=2)
-    for c, want in ((text, False), (walks, True)):
+    for c, mode, in_flight, want in ((text, 0, 0, 0), (walks, 0, 0, 1), (walks, 0, 1, 0), (walks, 1, 0, 0),
+                                     (text, 2, 0, 1), (walks, 0, 100, 1)):
         tr = Trainer(vocab=c.vocab, dim=128, window=5, negatives=5, counts=c.counts, tokens_per_epoch=c.n_tokens, seed=1,
-                     table_size=1 << 16, coherent_tables="auto")
-        assert tr.coherent_tables is want
+                     table_size=1 << 16, update_mode=mode, sentences_in_flight=in_flight)
+        tr.set_corpus(c.tokens, c.sent_off)
+        tr.train_epoch(0)
+        plan = B.w2v_debug_get_plan(tr.ctx)
+        assert plan["update"] == want, (mode, in_flight, plan)
+        assert plan["wavefronts"] == (in_flight if in_flight else plan["wavefronts"]) and plan["wavefronts"] >= 1
+        assert bool(torch.isfinite(tr.syn0).all())
         tr.close()
