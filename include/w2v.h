@@ -83,8 +83,8 @@ typedef struct w2v_config {
                                         wavefronts make to one row at the same time only the last writer's
                                         survives;
                                      2: summed -- a row goes back as (what memory holds now) + (the change the
-                                        wavefront made to its copy), and every table access is made at system
-                                        scope, so wavefronts on different XCDs see each other's rows.  Exists
+                                        wavefront made to its copy), and rows are stored at system scope, so
+                                        wavefronts on different XCDs see each other's updates.  Exists
                                         for dim <= 256, 5 <= N <= 11 and windows of at most 10 as they occur;
                                         W2V_EINVAL otherwise.  Needs the snapshot space that
                                         w2v_query_workspace() then adds;
@@ -185,10 +185,8 @@ int w2v_debug_train_draws(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_
                           uint8_t *keep_dev, uint8_t *width_dev, int32_t *neg_dev);
 
 /* Test surface: fixes the update mode of every later launch, strict order included (update = 0
- * overwrite, 1 summed, -1 back to cfg.update_mode's rules), and the parts of the summed mode that are
- * switched on: flags bit 0 context rows summed, bit 1 output rows summed, bit 2 table loads at system
- * scope, bit 3 table stores at system scope (15 = the mode as shipped). */
-int w2v_debug_set_update(w2v_ctx *ctx, int update, uint32_t flags);
+ * overwrite, 1 summed, -1 back to cfg.update_mode's rules). */
+int w2v_debug_set_update(w2v_ctx *ctx, int update);
 
 /* Test surface: the work plan of the last launch (sentences before coarse_sentences were handed out as
  * 2^unit_shift units each, the others as 2^fine_shift; units in all), its update mode (0 overwrite,

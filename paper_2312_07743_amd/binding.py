@@ -60,7 +60,7 @@ def lib():
         L.w2v_counters.argtypes = [vp, C.POINTER(u64), C.POINTER(u64), i32]
         L.w2v_debug_draws.argtypes = [vp, vp, vp, u64, u64, u32, vp, vp, vp]
         L.w2v_debug_train_draws.argtypes = [vp, vp, vp, u64, u64, u32, vp, vp, vp]
-        L.w2v_debug_set_update.argtypes = [vp, i32, u32]
+        L.w2v_debug_set_update.argtypes = [vp, i32]
         L.w2v_debug_get_plan.argtypes = [vp, C.POINTER(u32), C.POINTER(u32), C.POINTER(u64), C.POINTER(u64), C.POINTER(u32),
                                          C.POINTER(u64)]
         L.w2v_debug_reduce.argtypes = [vp, vp, vp]
@@ -186,8 +186,8 @@ def w2v_debug_train_draws(ctx, tokens_dev, sent_off_dev, n_sent, first_token_glo
                                        epoch, _ptr(keep_dev), _ptr(width_dev), _ptr(neg_dev)), ctx)
 
 
-def w2v_debug_set_update(ctx, update, flags=15):
-    _check(lib().w2v_debug_set_update(ctx, int(update), int(flags)), ctx)
+def w2v_debug_set_update(ctx, update):
+    _check(lib().w2v_debug_set_update(ctx, int(update)), ctx)
 
 
 def w2v_debug_get_plan(ctx):

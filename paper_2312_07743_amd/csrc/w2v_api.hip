@@ -139,11 +139,26 @@ hipStream_t stream_of(const w2v_ctx *ctx) { return static_cast<hipStream_t>(ctx-
 // wavefronts does not learn at all; 9.5M tokens of which 30 % are kept, N=10, on 1,536 wavefronts: score 0.67 after
 // two epochs, on 512: 1.00; 5.6M tokens of that kind, four epochs, loss against the serial oracle: 360 wavefronts
 // +0.9 %, 196 (this rule) +0.6 %.  The 17M-token corpus (N=5) keeps every wavefront.
-uint64_t lock_free_waves(const w2v_ctx *ctx, uint64_t resident)
+//
+// Summed updates lose nothing, but every change is made to a copy that does not see what the other holders of the row
+// do meanwhile, and the changes of all holders add up: where many wavefronts hold one row at once the step on that row
+// multiplies and the loss ends higher.  The measure is the collision mass C = wavefronts x rows a wavefront holds
+// (2W+2 ring rows + N+1 output rows) x sum over words of (share of the kept tokens)^2, the expected number of other
+// wavefronts that hold the row of a token at the moment it is used.  Measured on uniform walks (W=10, N=5, two
+// epochs, loss against strict order): 100,000 nodes, 16M tokens: C=2.2 (2,304 wavefronts) +2.2 %, C=0.49 (512)
+// +0.44 %; 100,000 nodes, 80M tokens: C=2.2 +1.5 %, C=0.98 +0.9 %, C=0.49 +0.5 %, C=0.24 +0.2 %; 1M nodes, 80M
+// tokens: C=0.27 (all 2,304 wavefronts) +0.5 %.  The summed mode therefore runs at most 0.5 / (rows x mass) wavefronts.
+uint64_t lock_free_waves(const w2v_ctx *ctx, uint64_t resident, int update)
 {
     const double kept = (double)ctx->cfg.tokens_per_epoch * ctx->kept_fraction;
     const double rows = (double)(ctx->cfg.negatives + 1u);
     uint64_t cap = (uint64_t)(kept * 36.0 / (2048.0 * rows * rows));
+    if (update == 1 && ctx->collision_mass > 0.0) {
+        const uint32_t w = ctx->cfg.window_mode ? (ctx->cfg.window + 1u) / 2u : ctx->cfg.window;
+        const double held = (double)(2u * w + 2u) + rows;
+        const double by_mass = 0.5 / (held * ctx->collision_mass);
+        if (by_mass < (double)cap) cap = (uint64_t)by_mass;
+    }
     if (cap < 64u) cap = 64u;
     return resident < cap ? resident : cap;
 }
@@ -164,9 +179,15 @@ uint64_t snapshot_bytes(const w2v_config *c, uint32_t *floats_per_wave)
     return (uint64_t)*floats_per_wave * 4u * w2v::kMaxSummedWaves;
 }
 
+float *workspace_snap(const w2v_ctx *ctx)
+{
+    return reinterpret_cast<float *>(static_cast<unsigned char *>(ctx->cfg.workspace) + ctx->ws.snap_off);
+}
+
 // Queues one launch of the window kernel over the sentences described by `a`: picks the update mode and the
 // number of wavefronts, plans the units on the device, launches.
-int queue_launch(w2v_ctx *ctx, w2v::KernelArgs &a)
+// snap / snap_waves: where the summed mode keeps its snapshots and for how many wavefronts there is room.
+int queue_launch(w2v_ctx *ctx, w2v::KernelArgs &a, float *snap, uint64_t snap_waves)
 {
     const w2v_config &c = ctx->cfg;
     // Summed updates when wavefronts run side by side and either the caller asks for them or (automatic) the
@@ -179,13 +200,16 @@ int queue_launch(w2v_ctx *ctx, w2v::KernelArgs &a)
         if (ctx->resident_waves[update] == 0) ctx->resident_waves[update] = w2v::train_resident_waves(a, update, c.device);
         waves = ctx->resident_waves[update];
         if (waves == 0) return fail(ctx, W2V_EHIP, "could not query kernel occupancy");
-        waves = lock_free_waves(ctx, waves);
+        waves = lock_free_waves(ctx, waves, update);
     }
     if (update) {
-        if (waves > w2v::kMaxSummedWaves) waves = w2v::kMaxSummedWaves;
-        a.snap = reinterpret_cast<float *>(static_cast<unsigned char *>(c.workspace) + ctx->ws.snap_off);
+        if (c.sentences_in_flight > snap_waves)
+            return fail(ctx, W2V_EINVAL, "cfg.sentences_in_flight: the scratch memory holds the ring snapshots of " +
+                                             std::to_string(snap_waves) + " wavefronts with summed updates (" +
+                                             std::to_string((uint64_t)ctx->snap_floats * 4u) + " bytes each)");
+        if (waves > snap_waves) waves = snap_waves;
+        a.snap = snap;
         a.snap_stride = ctx->snap_floats;
-        a.hog_flags = ctx->hog_flags;
     }
     if (a.n_sent < 65536u && waves > (a.n_sent << 16)) waves = a.n_sent << 16;   // a sentence is never cut into more units than that
     w2v::PlanRequest rq;
@@ -309,18 +333,24 @@ int w2v_build_unigram_table(w2v_ctx *ctx, const uint64_t *counts_host, uint32_t 
     std::vector<uint32_t> thr(V, 0xFFFFFFFFu);
     const double t = ctx->cfg.subsample_t;
     double kept_c = total_c;                       // expected count of the tokens that survive subsampling
-    if (t > 0.0) {
-        for (uint32_t i = 0; i < V; ++i) {
-            if (counts_host[i] == 0) continue;
+    double kept_sq = 0.0;                          // ... and the sum of the squares of the words' expected kept counts
+    for (uint32_t i = 0; i < V; ++i) {
+        if (counts_host[i] == 0) continue;
+        double keep = 1.0;
+        if (t > 0.0) {
             const double f = (double)counts_host[i] / total_c;
             const double p = std::sqrt(t / f);
-            if (p >= 1.0) continue;
-            const double q = std::floor(p * 4294967296.0);
-            thr[i] = q >= 4294967295.0 ? 0xFFFFFFFFu : (uint32_t)q;
-            kept_c -= (1.0 - p) * (double)counts_host[i];
+            if (p < 1.0) {
+                const double q = std::floor(p * 4294967296.0);
+                thr[i] = q >= 4294967295.0 ? 0xFFFFFFFFu : (uint32_t)q;
+                kept_c -= (1.0 - p) * (double)counts_host[i];
+                keep = p;
+            }
         }
+        kept_sq += (keep * (double)counts_host[i]) * (keep * (double)counts_host[i]);
     }
     ctx->kept_fraction = kept_c / total_c;
+    ctx->collision_mass = kept_c > 0.0 ? kept_sq / (kept_c * kept_c) : 0.0;
     // Share of the tokens carried by the rows that fit one XCD's L2 (2 MB of each table): small for walks over a
     // large graph, large for text.  Where it is small the frequent rows are not held in L2 anyway, and it is exactly
     // those rows whose copies must not diverge between XCDs: such corpora get summed, system-scope updates.
@@ -352,7 +382,7 @@ int w2v_train_epoch(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_t *sen
     if (n_sent == 0) return W2V_OK;
     HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
     w2v::KernelArgs a = kernel_args(ctx, tokens_dev, sent_off_dev, n_sent, first_token_global_pos, epoch);
-    return queue_launch(ctx, a);
+    return queue_launch(ctx, a, workspace_snap(ctx), w2v::kMaxSummedWaves);
 }
 
 int w2v_train_epoch_host(w2v_ctx *ctx, const int32_t *tokens_host, const uint64_t *sent_off_host, uint64_t n_sent,
@@ -413,7 +443,7 @@ int w2v_train_epoch_host(w2v_ctx *ctx, const int32_t *tokens_host, const uint64_
         // batch's first offset instead, so positions (random keys, learning rate) are those of the corpus.
         const int32_t *tok_moved = reinterpret_cast<const int32_t *>(reinterpret_cast<uintptr_t>(tok_dev) - 4u * t_begin);
         w2v::KernelArgs a = kernel_args(ctx, tok_moved, off_dev, nsent, first_token_global_pos, epoch);
-        const int qrc = queue_launch(ctx, a);
+        const int qrc = queue_launch(ctx, a, workspace_snap(ctx), w2v::kMaxSummedWaves);
         if (qrc != W2V_OK) return qrc;
         HIP_TRY(ctx, hipEventRecord(ctx->drained[h], stream_of(ctx)));
         ctx->drained_recorded[h] = true;
@@ -521,17 +551,15 @@ int w2v_debug_train_draws(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_
     a.dump.width = width_dev;
     a.dump.neg = neg_dev;
     HIP_TRY(ctx, w2v::launch_fill_dump(a.dump, n_tokens, ctx->cfg.negatives, stream_of(ctx)));
-    return queue_launch(ctx, a);
+    return queue_launch(ctx, a, workspace_snap(ctx), w2v::kMaxSummedWaves);
 }
 
-int w2v_debug_set_update(w2v_ctx *ctx, int update, uint32_t flags)
+int w2v_debug_set_update(w2v_ctx *ctx, int update)
 {
     if (!ctx) return fail(nullptr, W2V_EINVAL, "ctx is NULL");
     if (update < -1 || update > 1) return fail(ctx, W2V_EINVAL, "update must be -1 (by the rules), 0 (overwrite) or 1 (summed)");
     if (update == 1 && ctx->snap_floats == 0) return fail(ctx, W2V_EINVAL, "no summed-update kernel for this configuration");
-    if (flags > 0xFu) return fail(ctx, W2V_EINVAL, "flags must be below 16");
     ctx->forced_update = update;
-    ctx->hog_flags = flags;
     return W2V_OK;
 }
 

@@ -66,7 +66,6 @@ struct KernelArgs {
     // ring slots had when it was fetched in snap + w * snap_stride floats.
     float             *snap;
     uint32_t           snap_stride;
-    uint32_t           hog_flags;      // experiment switches of the summed mode (see the window kernel)
     DrawDump           dump;
 };
 
@@ -123,7 +122,7 @@ struct w2v_ctx {
     uint32_t             snap_floats = 0;    // snapshot floats per wavefront of the summed mode (0: no such kernel for this shape)
     bool                 flat_corpus = false; // from the counts: the rows one L2 holds carry a small share of the tokens
     int                  forced_update = -1; // test override: update mode of every launch, strict order included (-1: by the rules)
-    uint32_t             hog_flags = 0xFu;   // switches of the summed mode (test surface)
+    double               collision_mass = 0.0; // sum over words of (share of the kept tokens)^2, from the counts
     int                  last_update = 0;    // update mode and wavefronts of the last launch (test surface)
     uint64_t             last_waves = 0;
     int                  next_half = 0;      // staging half the next batch goes to (alternates across calls too)

@@ -4,6 +4,7 @@
 #include "w2v_train_kernel.h"
 
 namespace w2v {
+
 namespace {
 
 // ---------------------------------------------------------------------------------------------

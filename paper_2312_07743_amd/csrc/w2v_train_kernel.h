@@ -188,6 +188,21 @@ template <int VW> __device__ __forceinline__ void store_vec(float *p, const floa
     else { *reinterpret_cast<float4 *>(p) = make_float4(src[0], src[1], src[2], src[3]); }
 }
 
+// the same store at system scope (written through to the memory side that all XCDs share): relaxed atomic stores of
+// 4 or 8 bytes are what the compiler turns into global_store ... sc0 sc1
+template <int VW> __device__ __forceinline__ void store_vec_system(float *p, const float *src)
+{
+    if constexpr (VW == 1) {
+        __hip_atomic_store(reinterpret_cast<uint32_t *>(p), __float_as_uint(src[0]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    } else {
+#pragma unroll
+        for (int h = 0; h < VW / 2; ++h) {
+            const uint64_t v = ((uint64_t)__float_as_uint(src[2 * h + 1]) << 32) | __float_as_uint(src[2 * h]);
+            __hip_atomic_store(reinterpret_cast<uint64_t *>(p) + h, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+    }
+}
+
 // Rows whose length does not fill the lanes' shares (dim < 64 * floats per lane) are reached through a buffer
 // resource per row, dim floats long: a lane whose share lies past the last column loads 0 and its stores are
 // dropped by the hardware's range check, so no lane needs a test of its own, and the lane's constant byte offset
@@ -268,13 +283,11 @@ constexpr uint32_t kNoWord = 0xFFFFFFFFu;
 constexpr int occupancy_goal(int e, int wcap) { return (e == 1 && wcap <= 5) ? 4 : (e <= 2 && wcap <= 10) ? 3 : ((e * wcap <= 25) ? 2 : 1); }
 
 // SUMMED: lock-free updates are added to what memory holds when a row goes back, instead of overwriting it with a copy
-// that was fetched up to 2W+1 windows earlier (see "summed updates" below); all table accesses are then made at
-// system scope.
+// that was fetched up to 2W+1 windows earlier (see "summed updates" below); the rows are then stored at system scope.
 template <int VW, int R, int TAIL, int WCAP, bool FULL, int KMODE, bool SUMMED>
 __global__ void __launch_bounds__(kLanes) __attribute__((amdgpu_waves_per_eu(occupancy_goal(VW * R + TAIL, WCAP))))
 train_kernel(KernelArgs A)
 {
-    static_assert(!(SUMMED && FULL), "the summed mode reaches every row through a buffer resource");
     constexpr int E = VW * R + TAIL;     // floats of a row per lane
     constexpr int NCH = R + TAIL;        // chunks of a row per lane: R of VW floats, then TAIL single floats
     constexpr int ROWF = kLanes * E;     // floats of a ring row in LDS
@@ -316,8 +329,8 @@ train_kernel(KernelArgs A)
 
     const uint32_t row_bytes = A.dim * 4u;
     // row `word` of a table -> registers (zeros beyond dim) / registers -> the row (nothing beyond dim)
-    // (summed mode: at system scope when the launch asks for it, one wave-uniform branch per row)
-    const bool sys_loads = SUMMED && (A.hog_flags & 4u), sys_stores = SUMMED && (A.hog_flags & 8u);
+    // (summed mode: stores are made at system scope, i.e. written through to the memory side that all XCDs share;
+    // measured on walks over a 1M-node graph, system-scope loads on top of that change nothing)
     auto load_row = [&](const float *table, uint32_t word, float *dst) {
         const float *row = table + (size_t)word * A.ld;
         if constexpr (FULL) {
@@ -327,17 +340,10 @@ train_kernel(KernelArgs A)
             });
         } else {
             const __amdgpu_buffer_rsrc_t rs = row_resource(row, row_bytes);
-            if (sys_loads) {
-                chunks([&](auto r_, auto w_, auto o_) {
-                    constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
-                    row_load_vec<CW, kSystemScope>(rs, eoff[r] * 4, 0u, dst + RO);
-                });
-            } else {
-                chunks([&](auto r_, auto w_, auto o_) {
-                    constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
-                    row_load_vec<CW>(rs, eoff[r] * 4, 0u, dst + RO);
-                });
-            }
+            chunks([&](auto r_, auto w_, auto o_) {
+                constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
+                row_load_vec<CW>(rs, eoff[r] * 4, 0u, dst + RO);
+            });
         }
     };
     auto store_row = [&](float *table, uint32_t word, const float *src) {
@@ -345,21 +351,15 @@ train_kernel(KernelArgs A)
         if constexpr (FULL) {
             chunks([&](auto r_, auto w_, auto o_) {
                 constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
-                store_vec<CW>(row + eoff[r], src + RO);
+                if constexpr (SUMMED) store_vec_system<CW>(row + eoff[r], src + RO);
+                else store_vec<CW>(row + eoff[r], src + RO);
             });
         } else {
             const __amdgpu_buffer_rsrc_t rs = row_resource(row, row_bytes);
-            if (sys_stores) {
-                chunks([&](auto r_, auto w_, auto o_) {
-                    constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
-                    row_store_vec<CW, kSystemScope>(rs, eoff[r] * 4, 0u, src + RO);
-                });
-            } else {
-                chunks([&](auto r_, auto w_, auto o_) {
-                    constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
-                    row_store_vec<CW>(rs, eoff[r] * 4, 0u, src + RO);
-                });
-            }
+            chunks([&](auto r_, auto w_, auto o_) {
+                constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
+                row_store_vec<CW, SUMMED ? kSystemScope : 0>(rs, eoff[r] * 4, 0u, src + RO);
+            });
         }
     };
     // Summed updates.  A wavefront works on copies: a context row stays in its ring for up to 2W+1 windows, an
@@ -369,7 +369,7 @@ train_kernel(KernelArgs A)
     // another wavefront's update can be lost shrinks from the copy's lifetime to one memory round trip.  The
     // starting value of a ring slot is kept in a snapshot row of the wavefront's own in global memory (written
     // when the slot is filled, read when it is evicted); an output row's starting value is still in registers.
-    const bool sum_ring = SUMMED && (A.hog_flags & 1u), sum_out = SUMMED && (A.hog_flags & 2u);
+    constexpr bool sum_ring = SUMMED;
     float *snap_base = SUMMED ? A.snap + (size_t)blockIdx.x * A.snap_stride : nullptr;
     auto snap_store = [&](uint32_t slot, const float *src) {
         float *row = snap_base + (size_t)slot * ROWF;
@@ -507,11 +507,11 @@ train_kernel(KernelArgs A)
             if (lane == (int)l) meta_word = -1;
             return __ballot(meta_word >= 0 && meta_slot == slot) == 0;
         };
-        // the row of `slot` goes back: as it is, or (summed mode) as fresh + (row - snapshot)
-        auto leave_finish = [&](uint32_t slot, uint32_t word, const float *fresh, const float *snapv) {
+        // the row of `slot` goes back: as it is, or (summed) as fresh + (row - snapshot)
+        auto leave_finish = [&](uint32_t slot, uint32_t word, bool summed, const float *fresh, const float *snapv) {
             float t[E];
             ring_to_regs(ring + (size_t)slot * ROWF, t);
-            if (sum_ring) {
+            if (summed) {
 #pragma unroll
                 for (int x = 0; x < E; ++x) t[x] = fresh[x] + (t[x] - snapv[x]);
             }
@@ -522,8 +522,9 @@ train_kernel(KernelArgs A)
             uint32_t slot, word;
             if (leave_decide(p, slot, word)) {
                 float fresh[E] = {}, snapv[E] = {};
-                if (sum_ring) { load_row(A.syn0, word, fresh); snap_load(slot, snapv); }
-                leave_finish(slot, word, fresh, snapv);
+                const bool summed = sum_ring;
+                if (summed) { load_row(A.syn0, word, fresh); snap_load(slot, snapv); }
+                leave_finish(slot, word, summed, fresh, snapv);
             }
         };
 
@@ -766,13 +767,16 @@ train_kernel(KernelArgs A)
                 }
                 //     summed mode: the position that leaves the span after this window is known now; what memory holds
                 //     of its row and the slot's snapshot are requested here and used in step (h)
-                bool lv = false;
+                bool lv = false, lv_summed = false;
                 uint32_t lv_slot = 0, lv_word = 0;
                 float lv_fresh[SUMMED ? E : 1] = {}, lv_snap[SUMMED ? E : 1] = {};
                 if constexpr (SUMMED) {
                     if (sum_ring && i >= W) {
                         lv = leave_decide(i - W, lv_slot, lv_word);
-                        if (lv) { load_row(A.syn0, lv_word, lv_fresh); snap_load(lv_slot, lv_snap); }
+                        if (lv) {
+                            lv_summed = true;
+                            if (lv_summed) { load_row(A.syn0, lv_word, lv_fresh); snap_load(lv_slot, lv_snap); }
+                        }
                     }
                 }
 
@@ -855,16 +859,16 @@ train_kernel(KernelArgs A)
                         for (int kk = 0; kk < KC; ++kk)
 #pragma unroll
                             for (int x = 0; x < E; ++x) dO[kk][x] = 0.0f;
-                        // summed mode: what memory holds of the output rows now, requested while the last block's
-                        // multiply-adds run and added to this window's deltas in step (f)
-                        float FR[SUMMED ? KC : 1][SUMMED ? E : 1];
+                        // summed mode: what memory holds of the output rows now is fetched into the registers of the
+                        // window's copies as soon as the last block no longer needs those (its context deltas are
+                        // formed first, its output deltas while the loads travel) and takes the deltas in step (f)
                         bool fresh_loaded = false;
                         auto load_fresh = [&]() {
                             if constexpr (SUMMED) {
 #pragma unroll
                                 for (int kk = 0; kk < KC; ++kk) {
                                     const uint32_t pk = lane_value(pv, (uint32_t)kk);
-                                    if ((KEXACT || kb + kk <= N) && (!GENERAL || (pk >> kIdBits))) load_out(pk & kIdMask, FR[kk]);
+                                    if ((KEXACT || kb + kk <= N) && (!GENERAL || (pk >> kIdBits))) load_out(pk & kIdMask, OB[kk]);
                                 }
                             }
                             fresh_loaded = true;
@@ -916,9 +920,12 @@ train_kernel(KernelArgs A)
                             }
                             // every lane needs every g: straight-line windows take it through the row-broadcast
                             // operand of the multiply-adds, the general path through scalar registers
-                            if constexpr (SUMMED && q == NQW - 1) { if (sum_out) load_fresh(); }
                             float G[4] = {0.0f, 0.0f, 0.0f, 0.0f};
                             if constexpr (!MASKED) rows_to_all<(NC * KC + 15) / 16>(g, G);
+                            // the deltas of both sides from the block's gradients: DO_I / DO_O say which side(s) this
+                            // sweep over the block forms (one sweep for both, except the summed mode's last block)
+                            auto sweep = [&](auto do_i_tag, auto do_o_tag) {
+                            constexpr bool DO_I = decltype(do_i_tag)::value, DO_O = decltype(do_o_tag)::value;
                             static_for<CC>([&](auto cc_tag) {
                                 constexpr int cc = decltype(cc_tag)::value;
                                 constexpr int c = C0 + cc;
@@ -932,20 +939,25 @@ train_kernel(KernelArgs A)
                                         if constexpr (!MASKED) {
 #pragma unroll
                                             for (int x = 0; x < E; ++x) {
-                                                if (kk == 0) dI[x] = mul_row_lane<v % 16>(G[v / 16], OB[kk][x]);
-                                                else fma_row_lane<v % 16>(dI[x], G[v / 16], OB[kk][x]);
-                                                if (q == 0 && cc == 0) dO[kk][x] = mul_row_lane<v % 16>(G[v / 16], I[c][x]);
-                                                else fma_row_lane<v % 16>(dO[kk][x], G[v / 16], I[c][x]);
+                                                if constexpr (DO_I) {
+                                                    if (kk == 0) dI[x] = mul_row_lane<v % 16>(G[v / 16], OB[kk][x]);
+                                                    else fma_row_lane<v % 16>(dI[x], G[v / 16], OB[kk][x]);
+                                                }
+                                                if constexpr (DO_O) {
+                                                    if (q == 0 && cc == 0) dO[kk][x] = mul_row_lane<v % 16>(G[v / 16], I[c][x]);
+                                                    else fma_row_lane<v % 16>(dO[kk][x], G[v / 16], I[c][x]);
+                                                }
                                             }
                                         } else {
                                             const float gs = lane_value(g, (uint32_t)v);
 #pragma unroll
                                             for (int x = 0; x < E; ++x) {
-                                                dI[x] = __builtin_fmaf(gs, OB[kk][x], dI[x]);
-                                                dO[kk][x] = __builtin_fmaf(gs, I[c][x], dO[kk][x]);
+                                                if constexpr (DO_I) dI[x] = __builtin_fmaf(gs, OB[kk][x], dI[x]);
+                                                if constexpr (DO_O) dO[kk][x] = __builtin_fmaf(gs, I[c][x], dO[kk][x]);
                                             }
                                         }
                                     });
+                                    if constexpr (!DO_I) return;
                                     float *dst = ring + (size_t)cslot[c] * ROWF;
                                     if (GENERAL && shared_rows) {
                                         // positions that share a ring row add up (LDS float add)
@@ -978,6 +990,16 @@ train_kernel(KernelArgs A)
                                     }
                                 }
                             });
+                            };
+                            using std::true_type;
+                            using std::false_type;
+                            if constexpr (SUMMED && q == NQW - 1) {
+                                sweep(true_type{}, false_type{});
+                                load_fresh();
+                                sweep(false_type{}, true_type{});
+                            } else {
+                                sweep(true_type{}, true_type{});
+                            }
                         });
 
                         // (f) output rows go back (lock-free) once per window
@@ -993,19 +1015,14 @@ train_kernel(KernelArgs A)
 #pragma unroll
                                 for (int x = 0; x < E; ++x) OB[kk][x] += dO[kk][x];
                         } else {
-                            if constexpr (SUMMED) { if (sum_out && !fresh_loaded) load_fresh(); }
+                            if constexpr (SUMMED) { if (!fresh_loaded) load_fresh(); }
 #pragma unroll
                             for (int kk = 0; kk < KC; ++kk) {
                                 const uint32_t pk = lane_value(pv, (uint32_t)kk);
                                 if ((KEXACT || kb + kk <= N) && (!GENERAL || (pk >> kIdBits))) {
                                     float t[E];
-                                    if constexpr (SUMMED) {
 #pragma unroll
-                                        for (int x = 0; x < E; ++x) t[x] = (sum_out ? FR[kk][x] : OB[kk][x]) + dO[kk][x];
-                                    } else {
-#pragma unroll
-                                        for (int x = 0; x < E; ++x) t[x] = OB[kk][x] + dO[kk][x];
-                                    }
+                                    for (int x = 0; x < E; ++x) t[x] = OB[kk][x] + dO[kk][x];
                                     store_out(pk & kIdMask, t);
                                 }
                             }
@@ -1103,7 +1120,7 @@ train_kernel(KernelArgs A)
                     if (sum_ring) snap_store(pend_slot, pend_row);
                 }
                 if constexpr (SUMMED) {
-                    if (sum_ring) { if (lv) leave_finish(lv_slot, lv_word, lv_fresh, lv_snap); }
+                    if (sum_ring) { if (lv) leave_finish(lv_slot, lv_word, lv_summed, lv_fresh, lv_snap); }
                     else if (i >= W) ring_leave(i - W);
                 } else {
                     if (i >= W) ring_leave(i - W);
@@ -1138,7 +1155,7 @@ train_kernel(KernelArgs A)
                 uint32_t p = first;
                 while (p < n_ins) {
                     uint32_t sl[4], wd[4];
-                    bool on[4];
+                    bool on[4], sm[4];
                     float fr[4][E], sn[4][E];
                     static_for<4>([&](auto b_) {
                         constexpr int b = decltype(b_)::value;
@@ -1147,11 +1164,12 @@ train_kernel(KernelArgs A)
                     });
                     static_for<4>([&](auto b_) {
                         constexpr int b = decltype(b_)::value;
-                        if (on[b]) { load_row(A.syn0, wd[b], fr[b]); snap_load(sl[b], sn[b]); }
+                        sm[b] = on[b];
+                        if (sm[b]) { load_row(A.syn0, wd[b], fr[b]); snap_load(sl[b], sn[b]); }
                     });
                     static_for<4>([&](auto b_) {
                         constexpr int b = decltype(b_)::value;
-                        if (on[b]) leave_finish(sl[b], wd[b], fr[b], sn[b]);
+                        if (on[b]) leave_finish(sl[b], wd[b], sm[b], fr[b], sn[b]);
                     });
                 }
             } else {

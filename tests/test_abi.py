@@ -107,7 +107,7 @@ def test_null_context_is_an_error_everywhere():
     assert L.w2v_debug_reduce(None, None, None) == B.W2V_EINVAL
     assert L.w2v_debug_set_units(None, 0) == B.W2V_EINVAL
     assert L.w2v_debug_train_draws(None, None, None, 1, 0, 0, None, None, None) == B.W2V_EINVAL
-    assert L.w2v_debug_set_update(None, 0, 15) == B.W2V_EINVAL
+    assert L.w2v_debug_set_update(None, 0) == B.W2V_EINVAL
     assert L.w2v_debug_get_plan(None, None, None, None, None, None, None) == B.W2V_EINVAL
     assert L.w2v_debug_set_unit_tail(None, 0, 0) == B.W2V_EINVAL
     assert L.w2v_train_epoch_host(None, None, None, 1, 0, 0, None, 0) == B.W2V_EINVAL

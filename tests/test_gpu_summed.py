@@ -73,11 +73,9 @@ def test_training_launch_writes_out_the_oracles_decisions(orc32, case):
 
 
 @pytest.mark.parametrize("shape", ["graph", "text_d64", "text_d256_n10", "text_d100_fixed_width"])
-@pytest.mark.parametrize("flags", [15, 3, 1, 2])
-def test_summed_updates_in_strict_order_match_the_oracle(orc32, shape, flags):
+def test_summed_updates_in_strict_order_match_the_oracle(orc32, shape):
     """With one wavefront nobody else writes, so (what memory holds) + (copy - starting value) is the copy: the
-    summed mode, forced on in strict order, must reproduce the oracle within the strict-order tolerance.  flags:
-    15 the mode as shipped, 3 without system scope, 1 context rows only, 2 output rows only."""
+    summed mode, forced on in strict order, must reproduce the oracle within the strict-order tolerance."""
     if shape == "graph":
         c = synth.barabasi_albert_walks(n_nodes=3000, m=5, walks_per_node=1, walk_len=80, seed=4)
         kw = dict(dim=128, window=10, negatives=5, seed=23, table_size=1 << 18)
@@ -92,7 +90,7 @@ def test_summed_updates_in_strict_order_match_the_oracle(orc32, shape, flags):
         kw = dict(dim=100, window=9, negatives=6, seed=5, table_size=50021, window_mode=1)
     tr = _trainer(c, sentences_in_flight=1, update_mode=2, **kw)
     tr.set_corpus(c.tokens, c.sent_off)
-    B.w2v_debug_set_update(tr.ctx, 1, flags)
+    B.w2v_debug_set_update(tr.ctx, 1)
     tr.train_epoch(0)
     assert B.w2v_debug_get_plan(tr.ctx)["update"] == 1
     loss, pairs = tr.loss()
@@ -117,7 +115,7 @@ def test_summed_updates_with_units_and_the_flush_at_sentence_ends(orc32):
         kw = dict(dim=128, window=10, negatives=5, seed=9, subsample_t=t, table_size=50021)
         tr = _trainer(c, sentences_in_flight=1, update_mode=2, **kw)
         tr.set_corpus(c.tokens, c.sent_off)
-        B.w2v_debug_set_update(tr.ctx, 1, 15)
+        B.w2v_debug_set_update(tr.ctx, 1)
         B.w2v_debug_set_units(tr.ctx, unit_shift)
         tr.train_epoch(0)
         loss, pairs = tr.loss()
