@@ -126,6 +126,23 @@ int w2v_build_unigram_table(w2v_ctx *ctx, const uint64_t *counts_host, uint32_t 
 int w2v_train_epoch(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_t *sent_off_dev,
                     uint64_t n_sent, uint64_t first_token_global_pos, uint32_t epoch);
 
+/* w2v_train_epoch for callers that cannot allocate or be handed extra memory at the time of the call: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation.  It allocates no memory (no
+ * hipMalloc / hipFree, no allocating library call) and uses none of the caller's workspace as scratch: its accumulators, its work-queue
+ * head and (summed updates) its ring snapshots live in an array of W2V_STATIC_SCRATCH_BYTES that is part of the
+ * library's code object (every GPU the library runs on holds one copy until the process ends).  The workspace is
+ * only read (sampling table, thresholds).  Trains exactly like w2v_train_epoch (same kernels, same draws).
+ * loss_sum_dev / pairs_dev: device locations that receive the loss sum and the number of (context, target) pairs of
+ * THIS call (either may be NULL); the context's own accumulators (w2v_loss, w2v_counters) are not touched.
+ * With summed updates the array holds the snapshots of (W2V_STATIC_SCRATCH_BYTES - 256) / (4 * (2W+2) * row floats
+ * per wavefront) wavefronts: automatic concurrency is limited to that, an explicit cfg.sentences_in_flight beyond
+ * it is W2V_EINVAL.  All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ * streams, two contexts) race and give wrong counts; calls on one stream do not.  Asynchronous. */
+#define W2V_STATIC_SCRATCH_BYTES (32u << 20)
+int w2v_train_epoch_static(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_t *sent_off_dev,
+                           uint64_t n_sent, uint64_t first_token_global_pos, uint32_t epoch,
+                           double *loss_sum_dev, uint64_t *pairs_dev);
+
 /* The same pass for a corpus that lives in host memory (the batching pipeline of Sec. 4.1 without
  * the CPU-side sampling: only word ids cross the bus).  tokens_host / sent_off_host: host arrays
  * laid out as for w2v_train_epoch.  The sentences are cut into batches that fit one half of

@@ -14,7 +14,7 @@ W2V_OK, W2V_EINVAL, W2V_ESTATE, W2V_ENOMEM, W2V_EHIP = 0, -1, -2, -3, -4
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libw2v.so")
 EXPORTS = ["w2v_query_ld", "w2v_query_workspace", "w2v_create", "w2v_destroy", "w2v_build_unigram_table",
-           "w2v_train_epoch", "w2v_train_epoch_host", "w2v_train_epoch_naive", "w2v_get_embeddings", "w2v_loss", "w2v_counters", "w2v_debug_draws",
+           "w2v_train_epoch", "w2v_train_epoch_static", "w2v_train_epoch_host", "w2v_train_epoch_naive", "w2v_get_embeddings", "w2v_loss", "w2v_counters", "w2v_debug_draws",
            "w2v_debug_train_draws", "w2v_debug_set_update", "w2v_debug_get_plan",
            "w2v_debug_set_units", "w2v_debug_set_unit_tail", "w2v_debug_reduce", "w2v_last_error"]
 
@@ -53,6 +53,7 @@ def lib():
         L.w2v_destroy.argtypes = [vp]
         L.w2v_build_unigram_table.argtypes = [vp, vp, u32]
         L.w2v_train_epoch.argtypes = [vp, vp, vp, u64, u64, u32]
+        L.w2v_train_epoch_static.argtypes = [vp, vp, vp, u64, u64, u32, vp, vp]
         L.w2v_train_epoch_naive.argtypes = [vp, vp, vp, u64, u64, u32]
         L.w2v_train_epoch_host.argtypes = [vp, vp, vp, u64, u64, u32, vp, u64]
         L.w2v_get_embeddings.argtypes = [vp, i32, vp, u64, i32]
@@ -138,6 +139,11 @@ def w2v_build_unigram_table(ctx, counts_host, table_size):
 
 def w2v_train_epoch(ctx, tokens_dev, sent_off_dev, n_sent, first_token_global_pos=0, epoch=0):
     _check(lib().w2v_train_epoch(ctx, _ptr(tokens_dev), _ptr(sent_off_dev), n_sent, first_token_global_pos, epoch), ctx)
+
+
+def w2v_train_epoch_static(ctx, tokens_dev, sent_off_dev, n_sent, first_token_global_pos, epoch, loss_sum_dev, pairs_dev):
+    _check(lib().w2v_train_epoch_static(ctx, _ptr(tokens_dev), _ptr(sent_off_dev), n_sent, first_token_global_pos,
+                                        epoch, _ptr(loss_sum_dev), _ptr(pairs_dev)), ctx)
 
 
 def w2v_train_epoch_host(ctx, tokens_host, sent_off_host, n_sent, first_token_global_pos, epoch, staging_dev,

@@ -29,6 +29,8 @@ WorkspaceLayout workspace_layout(uint32_t vocab, uint32_t table_size, uint64_t s
 
 }  // namespace w2v
 
+static_assert(sizeof(w2v::Accum) <= 256, "the accumulator block heads the static scratch array");
+
 namespace {
 
 std::string g_create_error;
@@ -383,6 +385,31 @@ int w2v_train_epoch(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_t *sen
     HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
     w2v::KernelArgs a = kernel_args(ctx, tokens_dev, sent_off_dev, n_sent, first_token_global_pos, epoch);
     return queue_launch(ctx, a, workspace_snap(ctx), w2v::kMaxSummedWaves);
+}
+
+int w2v_train_epoch_static(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_t *sent_off_dev, uint64_t n_sent,
+                           uint64_t first_token_global_pos, uint32_t epoch, double *loss_sum_dev, uint64_t *pairs_dev)
+{
+    const int rc = check_train_call(ctx, tokens_dev, sent_off_dev, n_sent, first_token_global_pos, epoch);
+    if (rc != W2V_OK) return rc;
+    // the scratch array: accumulator block first, then the snapshot rows of as many wavefronts as fit
+    const uint64_t head = 256;
+    const uint64_t per_wave = (uint64_t)ctx->snap_floats * 4u;
+    const uint64_t snap_waves = per_wave ? (w2v::kStaticScratchBytes - head) / per_wave : 0;
+    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    unsigned char *scratch = nullptr;
+    HIP_TRY(ctx, w2v::static_scratch(ctx->cfg.device, &scratch));
+    w2v::KernelArgs a = kernel_args(ctx, tokens_dev, sent_off_dev, n_sent, first_token_global_pos, epoch);
+    a.accum = reinterpret_cast<w2v::Accum *>(scratch);
+    // the array keeps what the last call left: the accumulators start from zero (a kernel, not a memset, so that the
+    // call may be captured into a graph); the snapshot rows are written before they are read
+    HIP_TRY(ctx, w2v::launch_reset_accum(a.accum, 2, stream_of(ctx)));
+    if (n_sent) {
+        const int qrc = queue_launch(ctx, a, reinterpret_cast<float *>(scratch + head), snap_waves);
+        if (qrc != W2V_OK) return qrc;
+    }
+    HIP_TRY(ctx, w2v::launch_export_accum(a.accum, loss_sum_dev, pairs_dev, stream_of(ctx)));
+    return W2V_OK;
 }
 
 int w2v_train_epoch_host(w2v_ctx *ctx, const int32_t *tokens_host, const uint64_t *sent_off_host, uint64_t n_sent,

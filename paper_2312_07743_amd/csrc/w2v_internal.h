@@ -96,6 +96,13 @@ hipError_t launch_train_naive(const KernelArgs &a, uint32_t waves, hipStream_t s
 hipError_t launch_draws(const KernelArgs &a, uint64_t n_tokens_hint, uint8_t *keep, uint8_t *width, int32_t *neg,
                         hipStream_t stream);
 hipError_t launch_reduce_selftest(const float *in, float *out, hipStream_t stream);
+// The library's own scratch memory for w2v_train_epoch_static: a file-scope device array of kStaticScratchBytes, one
+// copy per GPU.  static_scratch() returns its device address on `device`, which must be the current device (asked of
+// the runtime once per device).
+constexpr uint64_t kStaticScratchBytes = 32ull << 20;
+hipError_t static_scratch(int device, unsigned char **ptr);
+// copies the loss sum and the pair count of an accumulator block to device locations of the caller (either may be NULL)
+hipError_t launch_export_accum(const Accum *accum, double *loss_sum_dev, uint64_t *pairs_dev, hipStream_t stream);
 // waves that fit the device at once for this configuration (0 on error)
 uint32_t train_resident_waves(const KernelArgs &a, int update, int device);
 uint32_t naive_resident_waves(int device);

@@ -1,9 +1,34 @@
 // HIP kernels of the SGNS trainer for gfx950 (MI355X) other than the window kernel: weight
 // initialisation, the draw dump used by the parity tests, the reduction self-test; and the host-side
 // launchers of all kernels.
+#include <mutex>
+
 #include "w2v_train_kernel.h"
 
 namespace w2v {
+
+// Scratch memory of w2v_train_epoch_static (accumulators, work-queue head, ring snapshots of the summed mode): part of
+// the code object, so no call allocates it; every GPU the library runs on holds its own copy until the process ends.
+// In host code the array's name is only a handle for hipGetSymbolAddress: kernels get the address asked for here.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+hipError_t static_scratch(int device, unsigned char **ptr)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex lock;
+    static unsigned char *address[kMaxDevices] = {};
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> hold(lock);
+    if (!address[device]) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        address[device] = static_cast<unsigned char *>(p);
+    }
+    *ptr = address[device];
+    return hipSuccess;
+}
 
 namespace {
 
@@ -30,6 +55,14 @@ __global__ void reset_accum_kernel(Accum *a, int what)
     if (threadIdx.x == 0 && blockIdx.x == 0) {
         a->next_sentence = 0;
         if (what >= 2) { a->loss_sum = 0.0; a->pairs = 0; a->dropped = 0; a->kept = 0; }
+    }
+}
+
+__global__ void export_accum_kernel(const Accum *a, double *loss_sum, uint64_t *pairs)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        if (loss_sum) *loss_sum = a->loss_sum;
+        if (pairs) *pairs = a->pairs;
     }
 }
 
@@ -168,6 +201,12 @@ hipError_t launch_init_weights(float *syn0, float *syn1neg, uint32_t vocab, uint
 hipError_t launch_reset_accum(Accum *accum, int what, hipStream_t stream)
 {
     hipLaunchKernelGGL(reset_accum_kernel, dim3(1), dim3(64), 0, stream, accum, what);
+    return hipGetLastError();
+}
+
+hipError_t launch_export_accum(const Accum *accum, double *loss_sum_dev, uint64_t *pairs_dev, hipStream_t stream)
+{
+    hipLaunchKernelGGL(export_accum_kernel, dim3(1), dim3(64), 0, stream, accum, loss_sum_dev, pairs_dev);
     return hipGetLastError();
 }
 

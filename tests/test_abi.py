@@ -100,6 +100,7 @@ def test_null_context_is_an_error_everywhere():
     assert L.w2v_build_unigram_table(None, None, 16) == B.W2V_EINVAL
     assert L.w2v_train_epoch(None, None, None, 1, 0, 0) == B.W2V_EINVAL
     assert L.w2v_train_epoch_naive(None, None, None, 1, 0, 0) == B.W2V_EINVAL
+    assert L.w2v_train_epoch_static(None, None, None, 1, 0, 0, None, None) == B.W2V_EINVAL
     assert L.w2v_get_embeddings(None, 0, None, 0, 0) == B.W2V_EINVAL
     assert L.w2v_loss(None, None, None, 0) == B.W2V_EINVAL
     assert L.w2v_counters(None, None, None, 0) == B.W2V_EINVAL
