@@ -31,6 +31,68 @@ WORKLOADS = {
 }
 
 
+def time_epochs(tokens, sent_off, counts, *, dim, window, negatives, subsample_t, table_size, steps, warmup,
+                update_mode=0):
+    """ms per epoch (HIP events on the launch stream) and the figures derived from it for one resident corpus."""
+    import numpy as np
+    import torch
+    from paper_2312_07743_amd import binding as B
+    from paper_2312_07743_amd.trainer import Trainer
+    n_tokens = int(tokens.numel()) if isinstance(tokens, torch.Tensor) else len(tokens)
+    tr = Trainer(vocab=len(counts), dim=dim, window=window, negatives=negatives, counts=counts, tokens_per_epoch=n_tokens,
+                 seed=2024, table_size=table_size, subsample_t=subsample_t, total_epochs=warmup + steps,
+                 update_mode=update_mode)
+    tr.set_corpus(tokens, sent_off)
+    for e in range(warmup):
+        tr.train_epoch(e)
+    torch.cuda.synchronize()
+    tr.counters(reset=True)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for e in range(warmup, warmup + steps):
+        tr.train_epoch(e)
+    b.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b) / steps
+    kept, _ = tr.counters()
+    loss, pairs = tr.loss()
+    plan = B.w2v_debug_get_plan(tr.ctx)
+    tr.close()
+    algo = (2 * negatives + 4) * 4 * dim * (kept / steps)
+    return {"ms_per_epoch": ms, "words_per_s": n_tokens / (ms * 1e-3), "kept_fraction": kept / (steps * n_tokens),
+            "algorithmic_GBs": algo / (ms * 1e-3) / 1e9, "frac_of_8TBs": algo / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "mean_loss": loss / max(pairs, 1), "update_mode": "summed" if plan["update"] else "overwrite",
+            "wavefronts": plan["wavefronts"], "epochs_timed": steps}
+
+
+def other_workloads(mid):
+    """The other configurations, a few epochs each on corpora generated in device memory (prefixes of the two 800M-token
+    ones: bytes and work per word do not depend on the corpus length).  Same algorithmic bytes per kept word as the
+    headline, (2N+4) rows of 4d bytes, also for the summed mode, which moves more rows than that."""
+    import torch
+    from paper_2312_07743_amd import synth_device
+    out = []
+    for d in (64, 256, 300, 512):
+        r = time_epochs(mid.tokens, mid.sent_off, mid.counts, dim=d, window=5, negatives=5, subsample_t=1e-4,
+                        table_size=1 << 24, steps=3, warmup=2)
+        out.append(dict(workload=f"mid corpus, d={d}, W=5, N=5, t=1e-4", **r))
+    tok, counts = synth_device.zipf_tokens(550000, 1.1, 44_000_000, seed=1)
+    off = torch.arange(44_001, dtype=torch.int64, device="cuda") * 1000
+    r = time_epochs(tok, off, counts, dim=300, window=5, negatives=10, subsample_t=1e-5, table_size=1 << 24, steps=3, warmup=1)
+    out.append(dict(workload="large prefix: vocab 550,000 Zipf(1.1), 44M tokens in 1,000-token sentences, d=300, W=5, N=10, t=1e-5", **r))
+    del tok
+    tok, counts = synth_device.barabasi_albert_walk_tokens(1_000_000, 5, 1, 80, seed=1)
+    off = torch.arange(1_000_001, dtype=torch.int64, device="cuda") * 80
+    for mode, name in ((0, "library default"), (1, "update_mode 1")):
+        r = time_epochs(tok, off, counts, dim=128, window=10, negatives=5, subsample_t=0.0, table_size=1 << 24, steps=3,
+                        warmup=1, update_mode=mode)
+        out.append(dict(workload=f"graph prefix: Barabasi-Albert 1M nodes (m=5), 80M tokens in walks of 80, d=128, W=10, N=5, "
+                                 f"no subsampling, {name}", **r))
+    del tok
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -56,6 +118,9 @@ def main():
     ap.add_argument("--update-mode", type=int, default=0, choices=(0, 1, 2),
                     help="cfg.update_mode: 0 the library's choice from the word counts, 1 overwrite, 2 summed lock-free updates")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the short runs of the other configurations (d sweep, large and graph prefixes) that the "
+                         "default run of the mid workload adds as `other_workloads`")
     ap.add_argument("--naive", action="store_true",
                     help="time the no-reuse comparator kernel instead of the window kernel (traffic comparison only)")
     ap.add_argument("--cpu-sentences", type=int, default=2500)
@@ -146,14 +211,16 @@ def main():
     algo_bytes_per_launch = rows_per_kept * row_bytes * (kept / args.steps)
     avg_kernel_s = float(np.mean(kernel_ms)) / 1e3
     achieved = algo_bytes_per_launch / avg_kernel_s / 1e9
-    traffic = None
-    # measured L2<->memory bytes per launch, from the committed rocprofv3 counter summary of this workload
+    traffic = traffic_source = None
+    # measured L2<->memory bytes per launch: NOT measured in this run, read from the committed rocprofv3 counter
+    # summary of this workload (two --pmc runs of this same command, see the file)
     tpath = os.path.join(ROOT, "profiles", f"window_kernel_{args.workload}_d{dim}_counters.txt")
     if os.path.exists(tpath) and not (args.naive or args.fixed_width or args.from_host or args.negative_block > 1
                                       or args.coherent_tables):
         for line in open(tpath):
             if line.startswith("hbm_bytes_per_launch:"):
                 traffic = float(line.split(":")[1])
+                traffic_source = f"profiles/{os.path.basename(tpath)} (rocprofv3 --pmc runs of this command, not this run)"
 
     # what a plain streaming copy reaches on this machine (1 GiB read + 1 GiB written per pass), for scale
     a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
@@ -189,11 +256,17 @@ def main():
                    "device": f"{props.name}, {props.multi_processor_count} CUs, "
                              f"{props.total_memory / 2**30:.0f} GiB"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
                      "kernel": "naive_kernel" if args.naive else "train_kernel", "avg_launch_ms": avg_kernel_s * 1e3,
                      "algorithmic_bytes_per_launch": algo_bytes_per_launch,
                      "streaming_copy_GBs_same_box": copy_gbs},
     }
+
+    plain = not (args.naive or args.fixed_width or args.from_host or args.negative_block > 1 or args.coherent_tables
+                 or args.dim or args.in_flight or args.update_mode)
+    if args.workload == "mid" and plain and not args.no_other_workloads:
+        tr.close()
+        out["other_workloads"] = other_workloads(corpus)
 
     if not args.no_cpu_baseline:
         from oracle import Oracle                     # the CPU oracle, timed as it stands (never tuned)
