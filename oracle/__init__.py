@@ -22,7 +22,7 @@ class Params(C.Structure):
                 ("tokens_per_epoch", C.c_uint64), ("first_token_global_pos", C.c_uint64),
                 ("seed", C.c_uint64), ("table_size", C.c_uint64),
                 ("lr0", C.c_double), ("lr_min_frac", C.c_double),
-                ("negative_block", C.c_uint32), ("reserved", C.c_uint32)]
+                ("negative_block", C.c_uint32), ("storage", C.c_uint32)]
 
 
 class Oracle:
@@ -65,6 +65,10 @@ class Oracle:
                                       C.c_uint64, C.c_uint64, C.c_uint64,
                                       C.POINTER(C.c_double), C.POINTER(C.c_uint64),
                                       C.c_void_p, C.c_void_p, C.c_void_p]
+        L.orc_round_bits.restype = C.c_uint32
+        L.orc_round_bits.argtypes = [C.c_uint64, C.c_uint32, C.c_uint64, C.c_uint32, C.c_uint32]
+        L.orc_to_bf16.restype = C.c_float
+        L.orc_to_bf16.argtypes = [C.c_float, C.c_uint32, C.c_uint32]
         L.orc_real_size.restype = C.c_uint32
         assert L.orc_real_size() == np.dtype(self.real).itemsize
 
@@ -103,11 +107,26 @@ class Oracle:
     def lr(self, lr0, lr_min_frac, epoch, total_epochs, tokens_per_epoch, sentence_start):
         return float(self.L.orc_lr(lr0, lr_min_frac, epoch, total_epochs, tokens_per_epoch, sentence_start))
 
-    def init_weights(self, seed, V, d):
+    def init_weights(self, seed, V, d, storage=0):
+        """storage != 0: the initial values rounded to the nearest bfloat16 (ties to even)."""
         syn0 = np.zeros((V, d), self.real)
         syn1 = np.zeros((V, d), self.real)
         self.L.orc_init_weights(seed, V, d, syn0, syn1)
+        if storage:
+            syn0[...] = self.nearest_bf16(syn0)
         return syn0, syn1
+
+    def nearest_bf16(self, x):
+        """Array version of to_bf16(x, 2, 0) (round to nearest bfloat16, ties to even; finite inputs)."""
+        b = np.ascontiguousarray(x, np.float32).view(np.uint32).astype(np.uint64)
+        b = (b + 0x7FFF + ((b >> 16) & 1)) & 0xFFFF0000
+        return b.astype(np.uint32).view(np.float32).astype(self.real).reshape(np.shape(x))
+
+    def round_bits(self, seed, epoch, pos, tag, e):
+        return int(self.L.orc_round_bits(seed & 0xFFFFFFFFFFFFFFFF, epoch, pos, tag, e))
+
+    def to_bf16(self, x, mode, bits16):
+        return float(self.L.orc_to_bf16(x, mode, bits16))
 
     # ---- one window ----------------------------------------------------
     def window_step(self, syn0, syn1neg, ctx, out, alpha, immediate=False, pairwise=False):
@@ -127,7 +146,7 @@ class Oracle:
                     seed, epoch=0, total_epochs=1, tokens_per_epoch=None, first_token_global_pos=0,
                     table_size=1 << 24, lr0=0.025, lr_min_frac=1e-4, subsample_t=0.0,
                     window_mode=0, update_mode=0, dump=False, s_begin=0, s_end=None, s_stride=1,
-                    negative_block=0):
+                    negative_block=0, storage=0):
         """Serial SGNS over sentences [s_begin, s_end) with the given stride, in place.
         Returns dict(loss_sum, pairs[, keep, width, neg])."""
         assert syn0.dtype == self.real and syn1neg.dtype == self.real
@@ -140,7 +159,7 @@ class Oracle:
         T = len(tokens)
         P = Params(V, d, window, negatives, window_mode, update_mode, total_epochs, epoch,
                    T if tokens_per_epoch is None else tokens_per_epoch, first_token_global_pos,
-                   seed, table_size, lr0, lr_min_frac, negative_block, 0)
+                   seed, table_size, lr0, lr_min_frac, negative_block, storage)
         end = self.table_ends(counts, table_size)
         thr = self.thresholds(counts, subsample_t)
         loss = C.c_double(0.0)

@@ -27,6 +27,11 @@
  *                                                    Section 7 (future work)
  *   - words with >= 5 occurrences, <= 1000 words per sentence: corpus
  *     preparation, done by the caller ............... Table 3 caption
+ *   - extension, not in the paper (which computes and stores in fp32,
+ *     Section 5.1): tables STORED as bfloat16, arithmetic in fp32 on the
+ *     on-chip copies the paper keeps (context rows for as long as the
+ *     window span holds them, Section 3.2; target and negative rows for
+ *     one window, Section 3.1), stochastic rounding when a copy goes back
  * Where the paper is silent (sampling distribution exponent, subsampling
  * rule, learning-rate schedule, random numbers, weight initialisation) the
  * conventions of the word2vec papers it cites are used; each such choice is
@@ -306,6 +311,47 @@ void orc_window_step_pairwise(real_t *syn0, real_t *syn1neg, uint32_t d,
 }
 
 /* ------------------------------------------------------------------ */
+/* bfloat16 storage (extension).  A stored value is a float whose low  */
+/* 16 bits are zero.  Going from a working value x to storage:         */
+/*   stochastic: add a 16-bit uniform number to the float's bit        */
+/*   pattern and drop the low 16 bits, so x goes to its upper          */
+/*   neighbour with probability (distance to the lower neighbour) /    */
+/*   (distance between the neighbours): unbiased;                      */
+/*   nearest (ties to even): kept only to show why it is not used.     */
+/* The 16 random bits of element e of a row written for token          */
+/* position pos:  S = draw(seed, epoch, pos, 64 + tag), tag = 0 for the */
+/* window's target row, 1+k for its negative k, 32 for the context row */
+/* of the token itself when it leaves the window span;                 */
+/*   c = high word of mix64(0x726F756E64 + e)   (a constant of e),     */
+/*   a = (lo32(S) + c) ^ rotl32(hi32(S) ^ c, 11);  a += rotl32(a, 15); */
+/*   bits = a >> 16.                                                   */
+/* ------------------------------------------------------------------ */
+static uint32_t rotl32(uint32_t x, int r) { return (x << r) | (x >> (32 - r)); }
+
+uint32_t orc_round_bits(uint64_t seed, uint32_t epoch, uint64_t pos, uint32_t tag, uint32_t e)
+{
+    uint64_t S = orc_draw(seed, epoch, pos, 64u + tag);
+    uint32_t c = u32_of(orc_mix64(0x726F756E64ull + e));
+    uint32_t a = ((uint32_t)S + c) ^ rotl32((uint32_t)(S >> 32) ^ c, 11);
+    a += rotl32(a, 15);
+    return a >> 16;
+}
+
+/* mode 1: stochastic with the given 16 bits, mode 2: nearest-even.  Returns the stored value as a float. */
+float orc_to_bf16(float x, uint32_t mode, uint32_t bits16)
+{
+    uint32_t b;
+    memcpy(&b, &x, 4);
+    if ((b & 0x7F800000u) != 0x7F800000u) {
+        if (mode == 1) b += (bits16 & 0xFFFFu);
+        else b += 0x7FFFu + ((b >> 16) & 1u);
+    }
+    b &= 0xFFFF0000u;
+    memcpy(&x, &b, 4);
+    return x;
+}
+
+/* ------------------------------------------------------------------ */
 /* One epoch, sentences in order, windows in order.                    */
 /* ------------------------------------------------------------------ */
 typedef struct orc_params {
@@ -319,8 +365,103 @@ typedef struct orc_params {
      * tokens of a sentence are taken in stretches of B consecutive tokens (by offset in the sentence, before
      * subsampling), and every window centred in a stretch uses the N negatives drawn at the stretch's first
      * token position.  A negative equal to a window's own target is still skipped for that window only. */
-    uint32_t negative_block, reserved;
+    uint32_t negative_block;
+    /* 0: tables in fp32 (the paper).  1 / 2: tables stored as bfloat16, rounded stochastically / to nearest when a
+     * working copy goes back (see orc_train_sentence_bf16). */
+    uint32_t storage;
 } orc_params;
+
+/* One sentence with bfloat16 tables.  Working copies are fp32 (real_t): the context row of kept token p is read when
+ * the window span first reaches p (window centre p-W, or the sentence start) and goes back, rounded, after the window
+ * centred W tokens later (or at the sentence end); tokens of one word that are in the span together share one copy,
+ * which goes back when the last of them leaves, with that token's position as the key of the random bits.  The target
+ * and negative rows are read at the start of their window and go back, rounded, at its end: one write per distinct
+ * row (a negative drawn twice is one row that received two deltas), keyed by the centre's position and the first slot
+ * the row fills.  The window itself is orc_window_step on the copies. */
+static void orc_train_sentence_bf16(const orc_params *P, real_t *syn0, real_t *syn1neg, const uint64_t *table_end,
+                                    const int32_t *kw, const uint64_t *kp, size_t nk, uint64_t a, real_t alpha,
+                                    double *loss_sum, uint64_t *pairs, uint8_t *width_out, int32_t *neg_out)
+{
+    const uint32_t W = P->window, N = P->negatives, d = P->dim;
+    const uint32_t cap = 2 * W + 2;
+    real_t *ring = (real_t *)malloc(sizeof(real_t) * (size_t)cap * d);      /* working copies of context rows */
+    real_t *outs = (real_t *)malloc(sizeof(real_t) * (size_t)(N + 1) * d);  /* working copies of output rows  */
+    int32_t slot_word[2 * ORC_MAX_CTX + 2];
+    uint32_t slot_refs[2 * ORC_MAX_CTX + 2];
+    for (uint32_t q = 0; q < cap; ++q) { slot_word[q] = -1; slot_refs[q] = 0; }
+    size_t entered = 0;                                          /* kept positions [0, entered) have entered */
+#define ORC_SLOT_OF(word, q_out) do { q_out = cap; for (uint32_t q_ = 0; q_ < cap; ++q_) if (slot_refs[q_] && slot_word[q_] == (word)) q_out = q_; } while (0)
+    for (size_t i = 0; i < nk; ++i) {
+        /* positions up to i+W enter the span */
+        while (entered < nk && entered <= i + W) {
+            uint32_t q;
+            ORC_SLOT_OF(kw[entered], q);
+            if (q == cap) {
+                for (q = 0; slot_refs[q]; ++q) {}
+                slot_word[q] = kw[entered];
+                for (uint32_t j = 0; j < d; ++j) ring[(size_t)q * d + j] = syn0[(size_t)kw[entered] * d + j];
+            }
+            ++slot_refs[q];
+            ++entered;
+        }
+        uint64_t pos = P->first_token_global_pos + kp[i];
+        uint32_t bw = orc_width(W, P->window_mode, P->seed, P->epoch, pos);
+        int32_t out[ORC_MAX_NEG + 1];
+        out[0] = kw[i];
+        uint64_t neg_pos = pos;
+        if (P->negative_block > 1) {
+            const uint64_t off = kp[i] - a;
+            neg_pos = P->first_token_global_pos + a + (off / P->negative_block) * P->negative_block;
+        }
+        for (uint32_t k = 0; k < N; ++k)
+            out[1 + k] = orc_negative(table_end, P->vocab, P->table_size, P->seed, P->epoch, neg_pos, k);
+        if (width_out) width_out[kp[i]] = (uint8_t)bw;
+        if (neg_out) for (uint32_t k = 0; k < N; ++k) neg_out[kp[i] * N + k] = out[1 + k];
+        int32_t ctx_slot[ORC_MAX_CTX]; uint32_t nctx = 0;
+        for (int64_t j = (int64_t)i - (int64_t)bw; j <= (int64_t)i + (int64_t)bw; ++j) {
+            if (j < 0 || j >= (int64_t)nk || j == (int64_t)i) continue;
+            uint32_t q;
+            ORC_SLOT_OF(kw[j], q);
+            ctx_slot[nctx++] = (int32_t)q;
+        }
+        if (nctx) {
+            /* distinct output rows: local index = first slot that holds the word */
+            int32_t out_local[ORC_MAX_NEG + 1];
+            for (uint32_t k = 0; k <= N; ++k) {
+                out_local[k] = (int32_t)k;
+                for (uint32_t k1 = 0; k1 < k; ++k1) if (out[k1] == out[k]) { out_local[k] = (int32_t)k1; break; }
+                if (out_local[k] == (int32_t)k)
+                    for (uint32_t j = 0; j < d; ++j) outs[(size_t)k * d + j] = syn1neg[(size_t)out[k] * d + j];
+            }
+            orc_window_step(ring, outs, d, ctx_slot, nctx, out_local, N + 1, alpha, loss_sum);
+            for (uint32_t k = 0; k <= N; ++k) {
+                if (out_local[k] != (int32_t)k) continue;
+                for (uint32_t j = 0; j < d; ++j)
+                    syn1neg[(size_t)out[k] * d + j] = (real_t)orc_to_bf16((float)outs[(size_t)k * d + j], P->storage,
+                                                                          orc_round_bits(P->seed, P->epoch, pos, k, j));
+            }
+            if (pairs) *pairs += nctx;
+        }
+        /* the position that no later window reaches leaves the span; after the last window all that remain leave */
+        size_t lv[ORC_MAX_CTX + 2], nlv = 0;
+        if (i >= W) lv[nlv++] = i - W;
+        if (i + 1 == nk) for (size_t p = (nk > W ? nk - W : 0); p < nk; ++p) lv[nlv++] = p;
+        for (size_t x = 0; x < nlv; ++x) {
+            const size_t p = lv[x];
+            uint32_t q;
+            ORC_SLOT_OF(kw[p], q);
+            if (--slot_refs[q] == 0) {
+                uint64_t ppos = P->first_token_global_pos + kp[p];
+                for (uint32_t j = 0; j < d; ++j)
+                    syn0[(size_t)kw[p] * d + j] = (real_t)orc_to_bf16((float)ring[(size_t)q * d + j], P->storage,
+                                                                      orc_round_bits(P->seed, P->epoch, ppos, 32u, j));
+            }
+        }
+    }
+#undef ORC_SLOT_OF
+    free(ring);
+    free(outs);
+}
 
 /* Optional dumps (any may be NULL), indexed by token offset in `tokens`:
  *   keep_out[T] 1/0, width_out[T] (0 where dropped), neg_out[T*N] (-1 where dropped). */
@@ -352,6 +493,11 @@ int orc_train_range(const orc_params *P, real_t *syn0, real_t *syn1neg,
             if (width_out) width_out[t] = 0;
             if (neg_out) for (uint32_t k = 0; k < N; ++k) neg_out[t * N + k] = -1;
             if (keep) { kw[nk] = w; kp[nk] = t; ++nk; }
+        }
+        if (P->storage) {
+            orc_train_sentence_bf16(P, syn0, syn1neg, table_end, kw, kp, nk, a, (real_t)alpha, loss_sum, pairs,
+                                    width_out, neg_out);
+            continue;
         }
         for (size_t i = 0; i < nk; ++i) {
             uint64_t pos = P->first_token_global_pos + kp[i];

@@ -137,3 +137,12 @@ def edge_recovery(emb, tokens, sent_off, n_sample=2000, topk=10, seed=0):
     ra, rb = rng.choice(seen, size=200000), rng.choice(seen, size=200000)
     at_random = float((e[ra] * e[rb]).sum(axis=1).mean())
     return hits / (len(sample) * topk), on_edges - at_random
+
+
+def bf16_steps_apart(a, b):
+    """How many bfloat16 values lie between the elements of a and b (float32 arrays of bfloat16-representable
+    values), counted on the ordered line of bfloat16 numbers."""
+    def line(x):
+        u = np.ascontiguousarray(x, np.float32).view(np.uint32).astype(np.int64) >> 16
+        return np.where(u & 0x8000, -(u & 0x7FFF), u & 0x7FFF)
+    return np.abs(line(a) - line(b))
