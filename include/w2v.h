@@ -62,7 +62,7 @@ typedef struct w2v_config {
     double   lr0;                 /* starting learning rate (0.025)                                     */
     double   lr_min_frac;         /* floor of the decay as a fraction of lr0 (1e-4)                     */
     double   subsample_t;         /* frequent-word subsampling threshold t; 0 switches it off           */
-    void    *syn0;                /* device, float[vocab*ld]: input (context-word) embeddings           */
+    void    *syn0;                /* device, float[vocab*ld] (uint16 if storage = 1): input (context-word) embeddings */
     void    *syn1neg;             /* device, float[vocab*ld]: output (target / negative) weights          */
     uint32_t ld;                  /* row stride in floats, >= dim and a multiple of 4; columns
                                      dim..ld-1 are never read or written by training                    */
@@ -93,6 +93,18 @@ typedef struct w2v_config {
                                         (walks over a large graph), overwrite otherwise (text).
                                      Strict order (sentences_in_flight = 1) always overwrites: there is
                                      nothing to sum                                                      */
+    uint32_t storage;             /* 0: the tables hold float (the paper's precision, Sec. 5.1).
+                                     1 (extension): the tables hold bfloat16 -- uint16[vocab*ld], the upper halves
+                                     of floats -- which halves the bytes every window moves.  All arithmetic stays
+                                     in fp32 on the on-chip copies (a context row for as long as the window span
+                                     holds it, Sec. 3.2; target and negative rows for one window, Sec. 3.1); a copy
+                                     that goes back is rounded STOCHASTICALLY, with bits from the counter-based
+                                     generator keyed by the token position that writes (nearest rounding would
+                                     undo most steps, which are far smaller than a bfloat16's last place).  Exists
+                                     for dim <= 320 that are multiples of 4 (or <= 128 and even, or <= 64),
+                                     5 <= N <= 11, windows of at most 10 as they occur, update_mode 0 or 1
+                                     (always overwriting); W2V_EINVAL otherwise                           */
+    uint32_t reserved;            /* 0                                                                  */
 } w2v_config;
 
 /* Row stride (in floats) that keeps every row aligned to 128-byte memory lines. */
@@ -170,7 +182,7 @@ int w2v_train_epoch_host(w2v_ctx *ctx, const int32_t *tokens_host, const uint64_
 int w2v_train_epoch_naive(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_t *sent_off_dev,
                           uint64_t n_sent, uint64_t first_token_global_pos, uint32_t epoch);
 
-/* Copies matrix `which` (0 = syn0, 1 = syn1neg) as a dense [vocab][dim] float array into dst
+/* Copies matrix `which` (0 = syn0, 1 = syn1neg) as a dense [vocab][dim] float array (widened if storage = 1) into dst
  * (device memory if dst_is_device != 0, else host memory), dst_floats >= vocab*dim.
  * Waits for the stream. */
 int w2v_get_embeddings(w2v_ctx *ctx, int which, float *dst, uint64_t dst_floats, int dst_is_device);

@@ -371,9 +371,11 @@ typedef struct orc_params {
     uint32_t storage;
 } orc_params;
 
-/* One sentence with bfloat16 tables.  Working copies are fp32 (real_t): the context row of kept token p is read when
- * the window span first reaches p (window centre p-W, or the sentence start) and goes back, rounded, after the window
- * centred W tokens later (or at the sentence end); tokens of one word that are in the span together share one copy,
+/* One sentence with bfloat16 tables.  Working copies are fp32 (real_t): the context row of kept token p is read one
+ * window before the window span reaches p (during the window centred at p-W-1, after that window's arithmetic and
+ * before its write-backs: the fetch of a row is started a window ahead of its first use; the first W+1 tokens are read
+ * at the sentence start) and goes back, rounded, after the window centred W tokens after p (or at the sentence end);
+ * tokens of one word whose copies are alive together share one copy,
  * which goes back when the last of them leaves, with that token's position as the key of the random bits.  The target
  * and negative rows are read at the start of their window and go back, rounded, at its end: one write per distinct
  * row (a negative drawn twice is one row that received two deltas), keyed by the centre's position and the first slot
@@ -382,7 +384,9 @@ static void orc_train_sentence_bf16(const orc_params *P, real_t *syn0, real_t *s
                                     const int32_t *kw, const uint64_t *kp, size_t nk, uint64_t a, real_t alpha,
                                     double *loss_sum, uint64_t *pairs, uint8_t *width_out, int32_t *neg_out)
 {
-    const uint32_t W = P->window, N = P->negatives, d = P->dim;
+    /* the span reaches as far as the widest window that occurs: W, or the fixed width ceil(W/2) */
+    const uint32_t W = P->window_mode == 1 ? (P->window + 1u) / 2u : P->window;
+    const uint32_t N = P->negatives, d = P->dim;
     const uint32_t cap = 2 * W + 2;
     real_t *ring = (real_t *)malloc(sizeof(real_t) * (size_t)cap * d);      /* working copies of context rows */
     real_t *outs = (real_t *)malloc(sizeof(real_t) * (size_t)(N + 1) * d);  /* working copies of output rows  */
@@ -392,7 +396,7 @@ static void orc_train_sentence_bf16(const orc_params *P, real_t *syn0, real_t *s
     size_t entered = 0;                                          /* kept positions [0, entered) have entered */
 #define ORC_SLOT_OF(word, q_out) do { q_out = cap; for (uint32_t q_ = 0; q_ < cap; ++q_) if (slot_refs[q_] && slot_word[q_] == (word)) q_out = q_; } while (0)
     for (size_t i = 0; i < nk; ++i) {
-        /* positions up to i+W enter the span */
+        /* positions up to i+W have entered (this loop only does work before the first window) */
         while (entered < nk && entered <= i + W) {
             uint32_t q;
             ORC_SLOT_OF(kw[entered], q);
@@ -405,7 +409,7 @@ static void orc_train_sentence_bf16(const orc_params *P, real_t *syn0, real_t *s
             ++entered;
         }
         uint64_t pos = P->first_token_global_pos + kp[i];
-        uint32_t bw = orc_width(W, P->window_mode, P->seed, P->epoch, pos);
+        uint32_t bw = orc_width(P->window, P->window_mode, P->seed, P->epoch, pos);
         int32_t out[ORC_MAX_NEG + 1];
         out[0] = kw[i];
         uint64_t neg_pos = pos;
@@ -441,6 +445,18 @@ static void orc_train_sentence_bf16(const orc_params *P, real_t *syn0, real_t *s
                                                                           orc_round_bits(P->seed, P->epoch, pos, k, j));
             }
             if (pairs) *pairs += nctx;
+        }
+        /* the token that the next window will reach is read now */
+        if (entered < nk && entered == i + W + 1) {
+            uint32_t q;
+            ORC_SLOT_OF(kw[entered], q);
+            if (q == cap) {
+                for (q = 0; slot_refs[q]; ++q) {}
+                slot_word[q] = kw[entered];
+                for (uint32_t j = 0; j < d; ++j) ring[(size_t)q * d + j] = syn0[(size_t)kw[entered] * d + j];
+            }
+            ++slot_refs[q];
+            ++entered;
         }
         /* the position that no later window reaches leaves the span; after the last window all that remain leave */
         size_t lv[ORC_MAX_CTX + 2], nlv = 0;

@@ -26,7 +26,7 @@ class W2VConfig(C.Structure):
                 ("lr0", C.c_double), ("lr_min_frac", C.c_double), ("subsample_t", C.c_double),
                 ("syn0", C.c_void_p), ("syn1neg", C.c_void_p), ("ld", C.c_uint32), ("device", C.c_int32),
                 ("stream", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_uint64),
-                ("negative_block", C.c_uint32), ("update_mode", C.c_uint32)]
+                ("negative_block", C.c_uint32), ("update_mode", C.c_uint32), ("storage", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 class W2VError(RuntimeError):
@@ -113,13 +113,13 @@ def w2v_query_workspace(vocab, table_size, dim=0, window=0, negatives=0, window_
 
 def make_config(*, vocab, dim, window, negatives, tokens_per_epoch, seed, syn0, syn1neg, ld, workspace,
                 workspace_bytes, device=0, stream=None, window_mode=0, total_epochs=1, sentences_in_flight=0,
-                lr0=0.025, lr_min_frac=1e-4, subsample_t=0.0, negative_block=0, update_mode=0):
+                lr0=0.025, lr_min_frac=1e-4, subsample_t=0.0, negative_block=0, update_mode=0, storage=0):
     return W2VConfig(struct_size=C.sizeof(W2VConfig), vocab=vocab, dim=dim, window=window, negatives=negatives,
                      window_mode=window_mode, total_epochs=total_epochs, sentences_in_flight=sentences_in_flight,
                      tokens_per_epoch=tokens_per_epoch, seed=seed, lr0=lr0, lr_min_frac=lr_min_frac,
                      subsample_t=subsample_t, syn0=_ptr(syn0), syn1neg=_ptr(syn1neg), ld=ld, device=device,
                      stream=_ptr(stream), workspace=_ptr(workspace), workspace_bytes=workspace_bytes,
-                     negative_block=negative_block, update_mode=update_mode)
+                     negative_block=negative_block, update_mode=update_mode, storage=storage, reserved=0)
 
 
 def w2v_create(cfg, init_weights=1):

@@ -65,6 +65,9 @@ std::string check_config(const w2v_config *c)
     if (c->negative_block > 64u || (c->negative_block & (c->negative_block - 1u)) != 0)
         return "cfg.negative_block must be 0 or a power of two up to 64";
     if (c->update_mode > 2) return "cfg.update_mode must be 0 (automatic), 1 (overwrite) or 2 (summed)";
+    if (c->storage > 1) return "cfg.storage must be 0 (float) or 1 (bfloat16)";
+    if (c->storage == 1 && c->update_mode == 2) return "cfg.storage 1 (bfloat16 tables) always overwrites: cfg.update_mode must be 0 or 1";
+    if (c->reserved != 0) return "cfg.reserved must be 0";
     if (c->total_epochs < 1) return "cfg.total_epochs must be >= 1";
     if (c->tokens_per_epoch < 1) return "cfg.tokens_per_epoch must be >= 1";
     if (c->tokens_per_epoch > (1ull << 52) / c->total_epochs) return "total_epochs * tokens_per_epoch exceeds 2^52";
@@ -170,7 +173,7 @@ uint64_t lock_free_waves(const w2v_ctx *ctx, uint64_t resident, int update)
 uint64_t snapshot_bytes(const w2v_config *c, uint32_t *floats_per_wave)
 {
     *floats_per_wave = 0;
-    if (c->update_mode == 1u) return 0;
+    if (c->update_mode == 1u || c->storage != 0u) return 0;
     w2v::KernelArgs a;
     std::memset(&a, 0, sizeof(a));
     a.dim = c->dim;
@@ -197,6 +200,7 @@ int queue_launch(w2v_ctx *ctx, w2v::KernelArgs &a, float *snap, uint64_t snap_wa
     int update = (c.update_mode == 2u || (c.update_mode == 0u && ctx->flat_corpus)) && ctx->snap_floats ? 1 : 0;
     if (c.sentences_in_flight == 1u) update = 0;       // strict order: nothing to sum
     if (ctx->forced_update >= 0) update = ctx->forced_update;
+    if (c.storage) update = 2;                         // bfloat16 tables: their own kernels, always overwriting
     uint64_t waves = c.sentences_in_flight;
     if (waves == 0) {
         if (ctx->resident_waves[update] == 0) ctx->resident_waves[update] = w2v::train_resident_waves(a, update, c.device);
@@ -204,7 +208,7 @@ int queue_launch(w2v_ctx *ctx, w2v::KernelArgs &a, float *snap, uint64_t snap_wa
         if (waves == 0) return fail(ctx, W2V_EHIP, "could not query kernel occupancy");
         waves = lock_free_waves(ctx, waves, update);
     }
-    if (update) {
+    if (update == 1) {
         if (c.sentences_in_flight > snap_waves)
             return fail(ctx, W2V_EINVAL, "cfg.sentences_in_flight: the scratch memory holds the ring snapshots of " +
                                              std::to_string(snap_waves) + " wavefronts with summed updates (" +
@@ -259,6 +263,17 @@ int w2v_create(const w2v_config *cfg, int init_weights, w2v_ctx **out)
     if (!why.empty()) return fail(nullptr, W2V_EINVAL, why);
     uint32_t snap_floats = 0;
     const uint64_t snap_bytes = snapshot_bytes(cfg, &snap_floats);
+    if (cfg->storage == 1u) {
+        w2v::KernelArgs probe;
+        std::memset(&probe, 0, sizeof(probe));
+        probe.dim = cfg->dim;
+        probe.ld = cfg->ld;
+        probe.window = cfg->window_mode ? (cfg->window + 1u) / 2u : cfg->window;
+        probe.negatives = cfg->negatives;
+        if (!w2v::train_kernel_exists(probe, 2))
+            return fail(nullptr, W2V_EINVAL, "cfg.storage 1 (bfloat16 tables) needs dim <= 320 in a 4-element layout (or <= 128 even, or <= 64), "
+                                             "window <= 10 (as it occurs) and 5 to 11 negatives");
+    }
     if (cfg->update_mode == 2u && snap_floats == 0)
         return fail(nullptr, W2V_EINVAL, "cfg.update_mode 2 (summed updates) needs dim <= 256, window <= 10 (as it occurs) and 5 to 11 negatives");
     const w2v::WorkspaceLayout minimal = w2v::workspace_layout(cfg->vocab, 1, snap_bytes);
@@ -272,8 +287,8 @@ int w2v_create(const w2v_config *cfg, int init_weights, w2v_ctx **out)
     if (e == hipSuccess)
         e = w2v::launch_reset_accum(reinterpret_cast<w2v::Accum *>(static_cast<unsigned char *>(cfg->workspace)), 2, stream_of(ctx));
     if (e == hipSuccess && init_weights)
-        e = w2v::launch_init_weights(static_cast<float *>(cfg->syn0), static_cast<float *>(cfg->syn1neg), cfg->vocab,
-                                     cfg->dim, cfg->ld, cfg->seed, stream_of(ctx));
+        e = w2v::launch_init_weights(cfg->syn0, cfg->syn1neg, cfg->vocab, cfg->dim, cfg->ld, cfg->seed, cfg->storage,
+                                     stream_of(ctx));
     if (e != hipSuccess) {
         fail_hip(nullptr, e, "w2v_create");
         delete ctx;
@@ -486,6 +501,7 @@ int w2v_train_epoch_naive(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_
     if (rc != W2V_OK) return rc;
     if (ctx->cfg.negative_block > 1u)
         return fail(ctx, W2V_EINVAL, "the no-reuse comparator draws fresh negatives per window (cfg.negative_block must be 0 or 1)");
+    if (ctx->cfg.storage) return fail(ctx, W2V_EINVAL, "the no-reuse comparator works on float tables (cfg.storage must be 0)");
     if (n_sent == 0) return W2V_OK;
     HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
     const w2v::KernelArgs a = kernel_args(ctx, tokens_dev, sent_off_dev, n_sent, first_token_global_pos, epoch);
@@ -509,6 +525,13 @@ int w2v_get_embeddings(w2v_ctx *ctx, int which, float *dst, uint64_t dst_floats,
     if (dst_floats < (uint64_t)c.vocab * c.dim) return fail(ctx, W2V_EINVAL, "dst_floats is smaller than vocab*dim");
     HIP_TRY(ctx, hipSetDevice(c.device));
     const void *src = which == 0 ? c.syn0 : c.syn1neg;
+    if (c.storage) {
+        if (!dst_is_device)
+            return fail(ctx, W2V_EINVAL, "bfloat16 tables are widened on the device: dst must be device memory (dst_is_device != 0)");
+        HIP_TRY(ctx, w2v::launch_widen_rows(src, dst, c.vocab, c.dim, c.ld, stream_of(ctx)));
+        HIP_TRY(ctx, hipStreamSynchronize(stream_of(ctx)));
+        return W2V_OK;
+    }
     HIP_TRY(ctx, hipMemcpy2DAsync(dst, (size_t)c.dim * sizeof(float), src, (size_t)c.ld * sizeof(float),
                                   (size_t)c.dim * sizeof(float), c.vocab,
                                   dst_is_device ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost, stream_of(ctx)));

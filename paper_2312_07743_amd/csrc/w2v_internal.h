@@ -82,13 +82,17 @@ bool pick_row_shape(uint32_t dim, uint32_t ld, RowShape *out);
 uint32_t train_lds_bytes(const KernelArgs &a, RowShape s);
 
 // Launchers (all asynchronous on `stream`).  Return hipSuccess or the launch error.
-hipError_t launch_init_weights(float *syn0, float *syn1neg, uint32_t vocab, uint32_t dim, uint32_t ld,
-                               uint64_t seed, hipStream_t stream);
+hipError_t launch_init_weights(void *syn0, void *syn1neg, uint32_t vocab, uint32_t dim, uint32_t ld,
+                               uint64_t seed, uint32_t storage, hipStream_t stream);
+// dense float copy of a bfloat16 table: dst[i*dim + j] = widen(src[i*ld + j]); dst is device memory
+hipError_t launch_widen_rows(const void *src, float *dst, uint32_t vocab, uint32_t dim, uint32_t ld, hipStream_t stream);
 hipError_t launch_reset_accum(Accum *accum, int what /*1: work counter only, 2: everything*/, hipStream_t stream);
 // resets the work counter and writes the launch's work plan into accum (the token count of the call is read from
 // sent_off on the device)
 hipError_t launch_plan(Accum *accum, const uint64_t *sent_off, const PlanRequest &req, hipStream_t stream);
 hipError_t launch_train(const KernelArgs &a, int update, uint32_t waves, hipStream_t stream);
+// is there an instantiation of the window kernel for this shape and update mode (0 overwrite, 1 summed, 2 bfloat16)?
+bool train_kernel_exists(const KernelArgs &a, int update);
 // floats of snapshot space one wavefront of the summed mode needs (0 if the shape has no such instantiation)
 uint32_t train_snap_floats(const KernelArgs &a);
 hipError_t launch_fill_dump(const DrawDump &d, uint64_t n_tokens, uint32_t negatives, hipStream_t stream);
@@ -125,7 +129,7 @@ struct w2v_ctx {
     hipEvent_t           drained[2] = {nullptr, nullptr};
     bool                 drained_recorded[2] = {false, false};
     double               kept_fraction = 1.0;  // expected share of the tokens that survive subsampling (from the counts)
-    uint64_t             resident_waves[2] = {0, 0}; // wavefronts of the window kernel the device holds, by update mode (0: not asked yet)
+    uint64_t             resident_waves[3] = {0, 0, 0}; // wavefronts of the window kernel the device holds, by update mode (0: not asked yet)
     uint32_t             snap_floats = 0;    // snapshot floats per wavefront of the summed mode (0: no such kernel for this shape)
     bool                 flat_corpus = false; // from the counts: the rows one L2 holds carry a small share of the tokens
     int                  forced_update = -1; // test override: update mode of every launch, strict order included (-1: by the rules)

@@ -50,6 +50,30 @@ __global__ void init_weights_kernel(float *syn0, float *syn1neg, uint32_t vocab,
     }
 }
 
+// the same initial values rounded to the nearest bfloat16 (ties to even)
+__global__ void init_weights_bf16_kernel(uint16_t *syn0, uint16_t *syn1neg, uint32_t vocab, uint32_t dim, uint32_t ld, uint64_t k0)
+{
+    const uint64_t n = (uint64_t)vocab * ld;
+    for (uint64_t x = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; x < n; x += (uint64_t)gridDim.x * blockDim.x) {
+        const uint64_t i = x / ld, j = x % ld;
+        uint32_t b = 0;
+        if (j < dim) {
+            const uint32_t u = (uint32_t)(mix64(k0 + (i * dim + j)) >> 32);
+            b = __float_as_uint((float)(((double)(u >> 8) * (1.0 / 16777216.0) - 0.5) / (double)dim));
+            b += 0x7FFFu + ((b >> 16) & 1u);
+        }
+        syn0[x] = (uint16_t)(b >> 16);
+        syn1neg[x] = 0;
+    }
+}
+
+__global__ void widen_rows_kernel(const uint16_t *src, float *dst, uint32_t vocab, uint32_t dim, uint32_t ld)
+{
+    const uint64_t n = (uint64_t)vocab * dim;
+    for (uint64_t x = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; x < n; x += (uint64_t)gridDim.x * blockDim.x)
+        dst[x] = __uint_as_float((uint32_t)src[(x / dim) * ld + x % dim] << 16);
+}
+
 __global__ void reset_accum_kernel(Accum *a, int what)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
@@ -188,13 +212,25 @@ uint32_t train_lds_bytes(const KernelArgs &a, RowShape s)
     return (2 * a.window + 3) * rowf * 4u + FCAP * 8u + kLanes * 32u + kLanes * a.negatives * 4u;
 }
 
-hipError_t launch_init_weights(float *syn0, float *syn1neg, uint32_t vocab, uint32_t dim, uint32_t ld,
-                               uint64_t seed, hipStream_t stream)
+hipError_t launch_init_weights(void *syn0, void *syn1neg, uint32_t vocab, uint32_t dim, uint32_t ld,
+                               uint64_t seed, uint32_t storage, hipStream_t stream)
 {
     const uint64_t n = (uint64_t)vocab * ld;
     const uint32_t blocks = (uint32_t)((n + 255) / 256 < 8192 ? (n + 255) / 256 : 8192);
-    hipLaunchKernelGGL(init_weights_kernel, dim3(blocks), dim3(256), 0, stream, syn0, syn1neg, vocab, dim, ld,
-                       mix64(seed ^ 0x696E6974ull));
+    if (storage)
+        hipLaunchKernelGGL(init_weights_bf16_kernel, dim3(blocks), dim3(256), 0, stream, static_cast<uint16_t *>(syn0),
+                           static_cast<uint16_t *>(syn1neg), vocab, dim, ld, mix64(seed ^ 0x696E6974ull));
+    else
+        hipLaunchKernelGGL(init_weights_kernel, dim3(blocks), dim3(256), 0, stream, static_cast<float *>(syn0),
+                           static_cast<float *>(syn1neg), vocab, dim, ld, mix64(seed ^ 0x696E6974ull));
+    return hipGetLastError();
+}
+
+hipError_t launch_widen_rows(const void *src, float *dst, uint32_t vocab, uint32_t dim, uint32_t ld, hipStream_t stream)
+{
+    const uint64_t n = (uint64_t)vocab * dim;
+    const uint32_t blocks = (uint32_t)((n + 255) / 256 < 8192 ? (n + 255) / 256 : 8192);
+    hipLaunchKernelGGL(widen_rows_kernel, dim3(blocks), dim3(256), 0, stream, static_cast<const uint16_t *>(src), dst, vocab, dim, ld);
     return hipGetLastError();
 }
 
@@ -222,6 +258,12 @@ hipError_t launch_fill_dump(const DrawDump &d, uint64_t n_tokens, uint32_t negat
     const uint32_t blocks = (uint32_t)((n_tokens + 255) / 256 < 16384 ? (n_tokens + 255) / 256 : 16384);
     hipLaunchKernelGGL(fill_dump_kernel, dim3(blocks), dim3(256), 0, stream, d, n_tokens, negatives);
     return hipGetLastError();
+}
+
+bool train_kernel_exists(const KernelArgs &a, int update)
+{
+    RowShape s;
+    return pick_row_shape(a.dim, a.ld, &s) && train_fn(a, s, update) != nullptr;
 }
 
 uint32_t train_snap_floats(const KernelArgs &a)

@@ -6,7 +6,9 @@
 //   key   = mix64(seed + G*(epoch+1))
 //   base  = mix64(key ^ mix64(position))
 //   draw  = mix64(base + G*(index+1));   the high 32 bits are used
-//   index 0: subsampling decision, 1: window width, 2+k: negative k
+//   index 0: subsampling decision, 1: window width, 2+k: negative k,
+//   64+t: the 64 bits that key the stochastic rounding of a row written for this position (bfloat16 storage):
+//   t = 0 the window's target row, 1+k its negative k, 32 the token's own context row when it leaves the span
 #pragma once
 #include <stdint.h>
 
@@ -33,6 +35,7 @@ W2V_HD uint64_t mix64(uint64_t z)
 W2V_HD uint64_t epoch_key(uint64_t seed, uint32_t epoch) { return mix64(seed + kGolden * ((uint64_t)epoch + 1u)); }
 W2V_HD uint64_t position_base(uint64_t key, uint64_t pos) { return mix64(key ^ mix64(pos)); }
 W2V_HD uint32_t draw_u32(uint64_t base, uint32_t index) { return (uint32_t)(mix64(base + kGolden * ((uint64_t)index + 1u)) >> 32); }
+W2V_HD uint64_t draw_u64(uint64_t base, uint32_t index) { return mix64(base + kGolden * ((uint64_t)index + 1u)); }
 W2V_HD uint32_t mul_hi_u32(uint32_t a, uint32_t n) { return (uint32_t)(((uint64_t)a * (uint64_t)n) >> 32); }
 
 // subsampling: threshold 0xFFFFFFFF keeps always, otherwise keep iff draw < threshold

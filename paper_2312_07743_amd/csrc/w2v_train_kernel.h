@@ -244,6 +244,47 @@ __device__ __forceinline__ void row_store_vec(__amdgpu_buffer_rsrc_t rs, int lan
     }
 }
 
+// bfloat16 storage: a row of dim elements of 2 bytes.  A chunk of VW elements is one 2-, 4- or 8-byte access; a
+// stored value is the upper half of the float's bit pattern.
+template <int VW>
+__device__ __forceinline__ void row_load_bf16(__amdgpu_buffer_rsrc_t rs, int lane_bytes, float *dst)
+{
+    if constexpr (VW == 1) {
+        dst[0] = __uint_as_float((uint32_t)__builtin_amdgcn_raw_buffer_load_b16(rs, lane_bytes, 0, 0) << 16);
+    } else if constexpr (VW == 2) {
+        const uint32_t t = __builtin_amdgcn_raw_buffer_load_b32(rs, lane_bytes, 0, 0);
+        dst[0] = __uint_as_float(t << 16); dst[1] = __uint_as_float(t & 0xFFFF0000u);
+    } else {
+        const vec2u t = __builtin_amdgcn_raw_buffer_load_b64(rs, lane_bytes, 0, 0);
+        dst[0] = __uint_as_float(t.x << 16); dst[1] = __uint_as_float(t.x & 0xFFFF0000u);
+        dst[2] = __uint_as_float(t.y << 16); dst[3] = __uint_as_float(t.y & 0xFFFF0000u);
+    }
+}
+// Stochastic rounding of a working value to bfloat16: 16 random bits are added to the float's bit pattern and the
+// low half is dropped (infinities and NaNs keep their upper half).  The bits of element e of a row written with the
+// 64-bit draw S:  a = (lo32(S) + c_e) ^ rotl(hi32(S) ^ c_e, 11);  a += rotl(a, 15);  bits = a >> 16, with c_e a
+// constant of the element (the caller keeps it in a register).
+__device__ __forceinline__ uint32_t round_to_bf16(float x, uint32_t s_lo, uint32_t s_hi, uint32_t c)
+{
+    uint32_t a = (s_lo + c) ^ __builtin_rotateleft32(s_hi ^ c, 11);
+    a += __builtin_rotateleft32(a, 15);
+    uint32_t b = __float_as_uint(x);
+    if ((b & 0x7F800000u) != 0x7F800000u) b += a >> 16;
+    return b >> 16;
+}
+template <int VW>
+__device__ __forceinline__ void row_store_bf16(__amdgpu_buffer_rsrc_t rs, int lane_bytes, const uint32_t *h)
+{
+    if constexpr (VW == 1) {
+        __builtin_amdgcn_raw_buffer_store_b16((unsigned short)h[0], rs, lane_bytes, 0, 0);
+    } else if constexpr (VW == 2) {
+        __builtin_amdgcn_raw_buffer_store_b32(h[0] | (h[1] << 16), rs, lane_bytes, 0, 0);
+    } else {
+        vec2u t; t.x = h[0] | (h[1] << 16); t.y = h[2] | (h[3] << 16);
+        __builtin_amdgcn_raw_buffer_store_b64(t, rs, lane_bytes, 0, 0);
+    }
+}
+
 // learning rate of the sentence that starts at global token offset `start` of this epoch
 __device__ __forceinline__ float sentence_lr(const KernelArgs &A, uint64_t start)
 {
@@ -284,10 +325,13 @@ constexpr int occupancy_goal(int e, int wcap) { return (e == 1 && wcap <= 5) ? 4
 
 // SUMMED: lock-free updates are added to what memory holds when a row goes back, instead of overwriting it with a copy
 // that was fetched up to 2W+1 windows earlier (see "summed updates" below); the rows are then stored at system scope.
-template <int VW, int R, int TAIL, int WCAP, bool FULL, int KMODE, bool SUMMED>
+// BF16: the tables hold bfloat16 (2 bytes per element, row stride A.ld elements); rows are widened to fp32 when they are
+// fetched into registers / the ring and rounded stochastically when they go back (an extension; the paper stores fp32).
+template <int VW, int R, int TAIL, int WCAP, bool FULL, int KMODE, bool SUMMED, bool BF16>
 __global__ void __launch_bounds__(kLanes) __attribute__((amdgpu_waves_per_eu(occupancy_goal(VW * R + TAIL, WCAP))))
 train_kernel(KernelArgs A)
 {
+    static_assert(!(BF16 && (FULL || SUMMED)), "bfloat16 rows go through buffer resources and are overwritten");
     constexpr int E = VW * R + TAIL;     // floats of a row per lane
     constexpr int NCH = R + TAIL;        // chunks of a row per lane: R of VW floats, then TAIL single floats
     constexpr int ROWF = kLanes * E;     // floats of a ring row in LDS
@@ -331,7 +375,25 @@ train_kernel(KernelArgs A)
     // row `word` of a table -> registers (zeros beyond dim) / registers -> the row (nothing beyond dim)
     // (summed mode: stores are made at system scope, i.e. written through to the memory side that all XCDs share;
     // measured on walks over a 1M-node graph, system-scope loads on top of that change nothing)
+    // per-element constants of the stochastic rounding (bfloat16 storage only)
+    uint32_t round_c[BF16 ? E : 1] = {};
+    if constexpr (BF16) {
+        chunks([&](auto r_, auto w_, auto o_) {
+            constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
+#pragma unroll
+            for (int x = 0; x < CW; ++x) round_c[RO + x] = (uint32_t)(mix64(0x726F756E64ull + (uint64_t)(eoff[r] + x)) >> 32);
+        });
+    }
     auto load_row = [&](const float *table, uint32_t word, float *dst) {
+        if constexpr (BF16) {
+            const uint16_t *row16 = reinterpret_cast<const uint16_t *>(table) + (size_t)word * A.ld;
+            const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(row16), 0, (int)(A.dim * 2u), 0x00020000);
+            chunks([&](auto r_, auto w_, auto o_) {
+                constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
+                row_load_bf16<CW>(rs, eoff[r] * 2, dst + RO);
+            });
+            return;
+        }
         const float *row = table + (size_t)word * A.ld;
         if constexpr (FULL) {
             chunks([&](auto r_, auto w_, auto o_) {
@@ -346,7 +408,21 @@ train_kernel(KernelArgs A)
             });
         }
     };
-    auto store_row = [&](float *table, uint32_t word, const float *src) {
+    // sbits: the 64-bit draw that keys the rounding of this write (bfloat16 storage only)
+    auto store_row = [&](float *table, uint32_t word, const float *src, uint64_t sbits) {
+        if constexpr (BF16) {
+            uint16_t *row16 = reinterpret_cast<uint16_t *>(table) + (size_t)word * A.ld;
+            const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(row16, 0, (int)(A.dim * 2u), 0x00020000);
+            const uint32_t s_lo = (uint32_t)sbits, s_hi = (uint32_t)(sbits >> 32);
+            chunks([&](auto r_, auto w_, auto o_) {
+                constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
+                uint32_t h[CW];
+#pragma unroll
+                for (int x = 0; x < CW; ++x) h[x] = round_to_bf16(src[RO + x], s_lo, s_hi, round_c[RO + x]);
+                row_store_bf16<CW>(rs, eoff[r] * 2, h);
+            });
+            return;
+        }
         float *row = table + (size_t)word * A.ld;
         if constexpr (FULL) {
             chunks([&](auto r_, auto w_, auto o_) {
@@ -387,7 +463,7 @@ train_kernel(KernelArgs A)
     };
     auto load_ctx = [&](uint32_t word, float *dst) { load_row(A.syn0, word, dst); };
     auto load_out = [&](uint32_t word, float *dst) { load_row(A.syn1neg, word, dst); };
-    auto store_out = [&](uint32_t word, const float *src) { store_row(A.syn1neg, word, src); };
+    auto store_out = [&](uint32_t word, const float *src, uint64_t sbits) { store_row(A.syn1neg, word, src, sbits); };
     auto ring_to_regs = [&](const float *lrow, float *dst) {      // LDS ring row -> registers
         chunks([&](auto r_, auto w_, auto o_) {
             constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
@@ -508,14 +584,19 @@ train_kernel(KernelArgs A)
             return __ballot(meta_word >= 0 && meta_slot == slot) == 0;
         };
         // the row of `slot` goes back: as it is, or (summed) as fresh + (row - snapshot)
-        auto leave_finish = [&](uint32_t slot, uint32_t word, bool summed, const float *fresh, const float *snapv) {
+        // the 64-bit draw that keys the rounding of the context row of kept position p (bfloat16 storage)
+        auto leave_bits = [&](uint32_t p) -> uint64_t {
+            if constexpr (!BF16) return 0ull;
+            else return draw_u64(position_base(A.key, A.first_pos + t0 + uni(kp[p & (FCAP - 1)])), 64u + 32u);
+        };
+        auto leave_finish = [&](uint32_t slot, uint32_t word, bool summed, const float *fresh, const float *snapv, uint64_t sbits) {
             float t[E];
             ring_to_regs(ring + (size_t)slot * ROWF, t);
             if (summed) {
 #pragma unroll
                 for (int x = 0; x < E; ++x) t[x] = fresh[x] + (t[x] - snapv[x]);
             }
-            store_row(A.syn0, word, t);
+            store_row(A.syn0, word, t, sbits);
             give_slot(slot);
         };
         auto ring_leave = [&](uint32_t p) {
@@ -524,7 +605,7 @@ train_kernel(KernelArgs A)
                 float fresh[E] = {}, snapv[E] = {};
                 const bool summed = sum_ring;
                 if (summed) { load_row(A.syn0, word, fresh); snap_load(slot, snapv); }
-                leave_finish(slot, word, summed, fresh, snapv);
+                leave_finish(slot, word, summed, fresh, snapv, leave_bits(p));
             }
         };
 
@@ -690,7 +771,7 @@ train_kernel(KernelArgs A)
             // negative distinct and different from either target, some context to train on).  The handing window
             // skips the stores of its negative rows, the receiving one skips their fetch.
             uint32_t hand_over = 0;
-            if constexpr (!MULTI && !SUMMED) {
+            if constexpr (!MULTI && !SUMMED && !BF16) {
                 const uint32_t ok = (have && A.neg_shift && my_b != 0u && my_plain && !overflow && n_prod > 1u) ? 1u : 0u;
                 const uint32_t mine = (my_stretch << 1) | ok;
                 const uint32_t next = (uint32_t)__shfl_down((int)mine, 1, kLanes);
@@ -849,6 +930,9 @@ train_kernel(KernelArgs A)
                     if constexpr (!LOAD_PER_BLOCK) static_for<NCW>(fetch_slot);
                     // One pass: the KC output rows held in OB (ids in pv, rows kb .. kb+KC-1 of the window) against
                     // all context slots.
+                    // bfloat16 storage: the centre's position keys the rounding of this window's output rows
+                    const uint64_t win_base = BF16 ? position_base(A.key, A.first_pos + t0 + uni(kp[i & (FCAP - 1)])) : 0ull;
+                    auto out_bits = [&](uint32_t tag) -> uint64_t { return BF16 ? draw_u64(win_base, 64u + tag) : 0ull; };
                     auto run_pass = [&](uint32_t kb, auto &OB, uint32_t pv) {
                         const uint32_t gk = kb + lane_k;
                         const float mult_lane = (KEXACT || gk <= N) ? (GENERAL ? (float)(pv >> kIdBits) : 1.0f) : 0.0f;
@@ -1009,7 +1093,7 @@ train_kernel(KernelArgs A)
                             float t[E];
 #pragma unroll
                             for (int x = 0; x < E; ++x) t[x] = OB[0][x] + dO[0][x];
-                            store_out(lane_value(pv, 0u) & kIdMask, t);
+                            store_out(lane_value(pv, 0u) & kIdMask, t, out_bits(0u));
 #pragma unroll
                             for (int kk = 1; kk < KC; ++kk)
 #pragma unroll
@@ -1023,7 +1107,7 @@ train_kernel(KernelArgs A)
                                     float t[E];
 #pragma unroll
                                     for (int x = 0; x < E; ++x) t[x] = OB[kk][x] + dO[kk][x];
-                                    store_out(pk & kIdMask, t);
+                                    store_out(pk & kIdMask, t, out_bits(kb + (uint32_t)kk));
                                 }
                             }
                         }
@@ -1120,7 +1204,7 @@ train_kernel(KernelArgs A)
                     if (sum_ring) snap_store(pend_slot, pend_row);
                 }
                 if constexpr (SUMMED) {
-                    if (sum_ring) { if (lv) leave_finish(lv_slot, lv_word, lv_summed, lv_fresh, lv_snap); }
+                    if (sum_ring) { if (lv) leave_finish(lv_slot, lv_word, lv_summed, lv_fresh, lv_snap, 0ull); }
                     else if (i >= W) ring_leave(i - W);
                 } else {
                     if (i >= W) ring_leave(i - W);
@@ -1169,7 +1253,7 @@ train_kernel(KernelArgs A)
                     });
                     static_for<4>([&](auto b_) {
                         constexpr int b = decltype(b_)::value;
-                        if (on[b]) leave_finish(sl[b], wd[b], sm[b], fr[b], sn[b]);
+                        if (on[b]) leave_finish(sl[b], wd[b], sm[b], fr[b], sn[b], 0ull);
                     });
                 }
             } else {

@@ -47,8 +47,9 @@ class Trainer:
     def __init__(self, *, vocab, dim, window, negatives, counts, tokens_per_epoch, seed, table_size=1 << 24,
                  subsample_t=0.0, total_epochs=1, sentences_in_flight=0, window_mode=0, lr0=0.025,
                  lr_min_frac=1e-4, device=0, init_weights=True, syn0=None, syn1neg=None, negative_block=0,
-                 coherent_tables=False, update_mode=0):
-        """update_mode: cfg.update_mode of the library (0 automatic, 1 overwrite, 2 summed lock-free updates).
+                 coherent_tables=False, update_mode=0, storage=0):
+        """storage: cfg.storage of the library (0 float tables, 1 bfloat16 tables with stochastic rounding).
+        update_mode: cfg.update_mode of the library (0 automatic, 1 overwrite, 2 summed lock-free updates).
         coherent_tables (experiments only; the library's summed mode reaches the same end with system-scope
         accesses to ordinary memory): keep syn0 / syn1neg, or the one table named, in uncached device memory.  Such
         memory is never freed (see _uncached_zeros); close() hands it to a pool for later Trainers."""
@@ -58,18 +59,21 @@ class Trainer:
         self.vocab, self.dim, self.window, self.negatives = vocab, dim, window, negatives
         self.ld = B.w2v_query_ld(dim)
         self.coherent_tables = coherent_tables
+        self.storage = storage
         self._uncached = []
+        table_dtype = torch.bfloat16 if storage else torch.float32
+        assert not (storage and coherent_tables)
 
         def table(name):       # coherent_tables may also name one table ("syn0" / "syn1neg")
             if coherent_tables is True or coherent_tables == name:
                 t = _uncached_zeros((vocab, self.ld), self.dev)
                 self._uncached.append(t)
                 return t
-            return torch.zeros((vocab, self.ld), dtype=torch.float32, device=self.dev)
+            return torch.zeros((vocab, self.ld), dtype=table_dtype, device=self.dev)
         self.syn0, self.syn1neg = table("syn0"), table("syn1neg")
         if syn0 is not None:
-            self.syn0[:, :dim] = torch.as_tensor(np.asarray(syn0, np.float32)).to(self.dev)
-            self.syn1neg[:, :dim] = torch.as_tensor(np.asarray(syn1neg, np.float32)).to(self.dev)
+            self.syn0[:, :dim] = torch.as_tensor(np.asarray(syn0, np.float32)).to(self.dev).to(table_dtype)
+            self.syn1neg[:, :dim] = torch.as_tensor(np.asarray(syn1neg, np.float32)).to(self.dev).to(table_dtype)
             init_weights = False
         ws_bytes = B.w2v_query_workspace(vocab, table_size, dim=dim, window=window, negatives=negatives,
                                          window_mode=window_mode, update_mode=update_mode)
@@ -81,7 +85,8 @@ class Trainer:
                                  ld=self.ld, workspace=self.workspace, workspace_bytes=ws_bytes, device=device,
                                  stream=self.stream.cuda_stream, window_mode=window_mode, total_epochs=total_epochs,
                                  sentences_in_flight=sentences_in_flight, lr0=lr0, lr_min_frac=lr_min_frac,
-                                 subsample_t=subsample_t, negative_block=negative_block, update_mode=update_mode)
+                                 subsample_t=subsample_t, negative_block=negative_block, update_mode=update_mode,
+                                 storage=storage)
         torch.cuda.synchronize(self.dev)
         self.ctx = B.w2v_create(self.cfg, 1 if init_weights else 0)
         B.w2v_build_unigram_table(self.ctx, counts, table_size)
@@ -124,6 +129,10 @@ class Trainer:
         return B.w2v_counters(self.ctx, reset)
 
     def embeddings(self, which=0):
+        if self.storage:                         # bfloat16 tables are widened on the device
+            dev = torch.empty((self.vocab, self.dim), dtype=torch.float32, device=self.dev)
+            B.w2v_get_embeddings(self.ctx, which, dev, dev.numel(), True)
+            return dev.cpu().numpy()
         out = np.empty((self.vocab, self.dim), np.float32)
         B.w2v_get_embeddings(self.ctx, which, out, out.size, False)
         return out

@@ -16,6 +16,8 @@ draw).  Calls only oracle/ and the input generator.
         graph_hogwild_reference.json: the hyper-parameters of the 'Graph' workload, d=128, W=10, N=5, no subsampling,
         on 10 uniform walks of 80 steps from every node of a 100,000-node Barabasi-Albert graph (m=5): 80M tokens,
         as many visits per node and epoch as the whole workload has, two epochs; about an hour per seed)
+    python tests/golden/make_mid_hogwild_reference.py --bf16                  (one seed, writes
+        mid_hogwild_reference_bf16.json: the 'Mid' workload with the tables stored as bfloat16, stochastic rounding)
     --jobs J runs up to J seeds at a time in processes of their own.
 """
 import argparse
@@ -42,6 +44,8 @@ def setting(args):
     if args.negative_block > 1:
         return (f"mid_hogwild_reference_nb{args.negative_block}.json",
                 dict(MID["params"], negative_block=args.negative_block), MID["corpus"], MID["seeds"][:1])
+    if args.bf16:
+        return "mid_hogwild_reference_bf16.json", dict(MID["params"], storage=1), MID["corpus"], MID["seeds"][:1]
     if args.fixed_width:
         return ("mid_hogwild_reference_fixed_width.json", dict(MID["params"], window_mode=1), MID["corpus"],
                 MID["seeds"][:1])
@@ -64,14 +68,15 @@ def one_run(job):
     params, corpus, seed = job
     orc = Oracle("float")
     c = make_corpus(corpus)
-    syn0, syn1 = orc.init_weights(seed, c.vocab, params["dim"])
+    syn0, syn1 = orc.init_weights(seed, c.vocab, params["dim"], storage=params.get("storage", 0))
     run = {"seed": seed, "epochs": []}
     for e in range(params["epochs"]):
         t = time.time()
         r = orc.train_epoch(syn0, syn1, c.counts, c.tokens, c.sent_off, window=params["window"],
                             negatives=params["negatives"], seed=seed, epoch=e, total_epochs=params["epochs"],
                             table_size=params["table_size"], subsample_t=params["subsample_t"],
-                            negative_block=params.get("negative_block", 0), window_mode=params.get("window_mode", 0))
+                            negative_block=params.get("negative_block", 0), window_mode=params.get("window_mode", 0),
+                            storage=params.get("storage", 0))
         rec = {"mean_loss": r["loss_sum"] / r["pairs"], "pairs": r["pairs"]}
         if c.labels is not None:
             rec["planted_score"] = planted_score(syn0, c.labels)
@@ -89,6 +94,7 @@ def main():
     ap.add_argument("--fixed-width", action="store_true")
     ap.add_argument("--large-shape", action="store_true")
     ap.add_argument("--graph-shape", action="store_true")
+    ap.add_argument("--bf16", action="store_true")
     ap.add_argument("--jobs", type=int, default=1)
     args = ap.parse_args()
     name, params, corpus, seeds = setting(args)

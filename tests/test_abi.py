@@ -72,6 +72,8 @@ def _good_cfg(**over):
     dict(vocab=0), dict(vocab=(1 << 27) + 1), dict(dim=0), dict(dim=513), dict(window=0), dict(window=17),
     dict(negatives=21), dict(window_mode=2), dict(negative_block=3), dict(negative_block=128), dict(update_mode=3),
     dict(update_mode=2, dim=300, ld=320), dict(update_mode=2, negatives=3), dict(update_mode=2, window=11),
+    dict(storage=2), dict(storage=1, update_mode=2), dict(storage=1, dim=512, ld=512), dict(storage=1, negatives=2),
+    dict(storage=1, window=11), dict(storage=1, dim=130, ld=160),
     dict(total_epochs=0), dict(tokens_per_epoch=0), dict(lr0=0.0),
     dict(lr0=float("nan")), dict(lr_min_frac=1.5), dict(subsample_t=-1.0), dict(syn0=None), dict(syn1neg=None),
     dict(ld=127), dict(ld=64), dict(ld=130), dict(workspace=None), dict(workspace=0x10001), dict(device=-1),

@@ -166,3 +166,61 @@ def test_part_of_an_epoch_is_planned_by_its_own_size():
     assert pairs_serial == pairs_whole
     assert 0.99 * loss_serial <= loss_parts <= 1.01 * loss_whole, (loss_serial, loss_parts, loss_whole)
     torch.cuda.synchronize()
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# bfloat16 table storage (extension): strict order against the oracle run with the same storage
+# ---------------------------------------------------------------------------------------------------------------
+def _bf16_parity(orc32, orc64, c, **kw):
+    """Both sides round with the same random bits, but the values they round differ in the last fp32 bits (other
+    summation order), so now and then a rounding falls the other way: one bfloat16 step, which later roundings of that
+    element then see, and the two evaluations drift apart with the length of the run.  The yardstick is the distance
+    between two evaluations that are both correct, the fp32 and the fp64 build of the oracle on the same case: the HIP
+    path's result carries its own fp32 rounding (another summation order, hardware exp / log / rcp) on top of the fp32
+    oracle's, so it may be up to 2.5 times as far from the fp32 oracle as the fp64 build is: in the share of elements
+    that differ, in the mean distance in bfloat16 steps, and in the share of elements beyond two steps (+ 0.1 %)."""
+    from util import bf16_agreement, run_gpu
+    g0, g1, gl, gp = run_gpu(c, sentences_in_flight=1, storage=1, **kw)
+    r0, r1, rl, rp = run_oracle(orc32, c, storage=1, **kw)
+    d0, d1, dl, dp = run_oracle(orc64, c, storage=1, **kw)
+    assert gp == rp == dp and abs(gl - rl) <= 2 * abs(dl - rl) + 1e-4 * abs(rl), (gp, rp, gl, rl, dl)
+    out = []
+    for got, ref, dbl, name in ((g0, r0, d0, "syn0"), (g1, r1, d1, "syn1neg")):
+        assert not np.any(got.view(np.uint32) & 0xFFFF)
+        same, mean_steps, far = bf16_agreement(got, ref)
+        fsame, fmean, ffar = bf16_agreement(dbl.astype(np.float32), ref)
+        assert 1.0 - same <= 2.5 * (1.0 - fsame) + 1e-3 and mean_steps <= 2.5 * fmean + 1e-3 and far <= 2.5 * ffar + 1e-3, \
+            (name, (same, mean_steps, far), (fsame, fmean, ffar))
+        out.append(((same, mean_steps, far), (fsame, fmean, ffar)))
+    return out
+
+
+def test_bf16_initial_weights_are_the_nearest_bf16_of_the_float_ones(orc32):
+    from paper_2312_07743_amd.trainer import Trainer
+    V, d = 300, 100
+    tr = Trainer(vocab=V, dim=d, window=5, negatives=5, counts=np.ones(V, np.uint64), tokens_per_epoch=10, seed=1234,
+                 table_size=256, storage=1)
+    ref0, ref1 = orc32.init_weights(1234, V, d, storage=1)
+    assert np.array_equal(tr.embeddings(0), ref0) and np.array_equal(tr.embeddings(1), ref1)
+    assert float(tr.syn0[:, d:].float().abs().sum()) == 0.0
+    tr.close()
+
+
+@pytest.mark.parametrize("shape", ["d128", "d64_w10", "d256_n10", "d300_n10_subsampled", "d100_fixed_shared"])
+def test_bf16_storage_in_strict_order_matches_the_oracle(orc32, orc64, shape):
+    if shape == "d128":
+        c = synth.zipf_corpus(500, 1.0, 8, 400, seed=3)
+        kw = dict(dim=128, window=5, negatives=5, seed=11, table_size=1 << 16)
+    elif shape == "d64_w10":
+        c = synth.barabasi_albert_walks(n_nodes=40, m=5, walks_per_node=1, walk_len=80, seed=4)     # a short run: see above
+        kw = dict(dim=64, window=10, negatives=5, seed=23, table_size=1 << 18)
+    elif shape == "d256_n10":
+        c = synth.zipf_corpus(800, 1.1, 6, 400, seed=13)
+        kw = dict(dim=256, window=7, negatives=10, seed=5, table_size=1 << 16)
+    elif shape == "d300_n10_subsampled":
+        c = synth.zipf_corpus(3000, 1.1, 12, 600, seed=31)
+        kw = dict(dim=300, window=5, negatives=10, seed=17, subsample_t=1e-3, table_size=1 << 20)
+    else:
+        c = synth.zipf_corpus(300, 1.0, 7, 300, seed=12)
+        kw = dict(dim=100, window=9, negatives=6, seed=5, table_size=50021, window_mode=1, negative_block=4)
+    print(shape, "(identical, mean steps, beyond two steps): HIP vs fp32 oracle, fp64 vs fp32 oracle:", _bf16_parity(orc32, orc64, c, **kw))

@@ -97,9 +97,9 @@ def _bf16(orc, a):
 
 def test_copies_are_read_and_written_back_when_the_span_says(orc64):
     """Sentence a b a c with W = 1 (so widths are 1), one negative, d = 2.  Events, written out:
-    window 0 (centre a0): span holds a0, b; context {b}.   window 1 (centre b): a1 enters and shares a0's copy;
-    context {a, a} (the same copy twice); a0 leaves but the copy stays (a1 holds it).   window 2 (centre a1): c enters;
-    context {b, c}; b leaves: written with b's position as key.   window 3 (centre c): context {a}; a1 leaves after it:
+    window 0 (centre a0): span holds a0, b; context {b}; a1 is read (one window ahead) and shares a0's copy.
+    window 1 (centre b): context {a, a} (the same copy twice); c is read; a0 leaves but the copy stays (a1 holds it).
+    window 2 (centre a1): context {b, c}; b leaves: written with b's position as key.   window 3 (centre c): context {a}; a1 leaves after it:
     the copy of a, carrying the deltas of windows 1 and 3, is written once, keyed by position 2; c leaves at the
     sentence end, keyed by position 3.  Output rows are read at each window's start and written at its end."""
     a, b, c = 0, 1, 2
@@ -141,6 +141,51 @@ def test_copies_are_read_and_written_back_when_the_span_says(orc64):
     assert np.array_equal(syn0, want0), (syn0, want0)
     assert np.array_equal(syn1, want1), (syn1, want1)
     assert not np.array_equal(syn0[a], s0[a]) and np.array_equal(syn0[3:], s0[3:])
+
+
+def test_a_copy_that_is_still_alive_when_its_word_comes_again_is_shared(orc64):
+    """Sentence a x y a with W = 1: the second a is read during window 1 (one window before the span reaches it), while
+    the copy of the first a is still alive (it leaves after window 1): the two share one copy, so the row of a is
+    written once, after window 3, and is NOT rounded after window 1 in between."""
+    a, x, y = 0, 1, 2
+    V, d, seed, lr = 6, 2, 5, 0.4
+    tok = np.array([a, x, y, a], np.int32)
+    off = np.array([0, 4], np.uint64)
+    counts = np.array([0, 0, 0, 3, 5, 4], np.uint64)
+    tsz = 64
+    end = orc64.table_ends(counts, tsz)
+    rng = np.random.default_rng(8)
+    syn0 = _bf16(orc64, rng.normal(scale=0.6, size=(V, d)))
+    syn1 = _bf16(orc64, rng.normal(scale=0.6, size=(V, d)))
+    s0, s1 = syn0.copy(), syn1.copy()
+    orc64.train_epoch(syn0, syn1, counts, tok, off, window=1, negatives=1, seed=seed, lr0=lr, lr_min_frac=1.0,
+                      table_size=tsz, storage=1)
+    alpha = float(np.float32(lr))
+
+    def rounded(row, pos, tag):
+        return np.array([orc64.to_bf16(float(np.float32(row[e])), 1, orc64.round_bits(seed, 0, pos, tag, e)) for e in range(d)])
+
+    work = {a: s0[a].copy(), x: s0[x].copy(), y: s0[y].copy()}
+    want0, want1 = s0.copy(), s1.copy()
+    for i, (centre, ctx) in enumerate([(a, [x]), (x, [a, y]), (y, [x, a]), (a, [y])]):
+        neg = orc64.negative(end, tsz, seed, 0, i, 0)
+        rows = sorted(set(ctx))
+        t0 = np.stack([work[w] for w in rows])
+        t1 = np.stack([want1[centre], want1[neg]])
+        orc64.window_step(t0, t1, [rows.index(w) for w in ctx], [0, 1], alpha)
+        for k, w in enumerate(rows):
+            work[w] = t0[k]                                        # a's copy carries window 1's delta into window 2
+        want1[centre] = rounded(t1[0], i, 0)
+        want1[neg] = rounded(t1[1], i, 1)
+        if i == 2:
+            want0[x] = rounded(work.pop(x), 1, 32)
+        if i == 3:
+            want0[y] = rounded(work.pop(y), 2, 32)
+    want0[a] = rounded(work.pop(a), 3, 32)                         # once, keyed by the last holder (position 3)
+    assert np.array_equal(syn0, want0), (syn0, want0)
+    assert np.array_equal(syn1, want1)
+    # had the copy of a been written and read again between windows 1 and 2, the result would differ
+    assert not np.array_equal(want0[a], rounded(rounded(s0[a] + 0, 0, 32), 3, 32))
 
 
 def test_draws_pairs_and_untouched_rows_do_not_depend_on_the_storage(orc32):
@@ -197,10 +242,11 @@ def test_float_and_double_builds_with_stochastic_rounding_stay_close(orc32, orc6
     """The same epoch in the fp32 and the fp64 build of the oracle, bfloat16 storage, same random bits: the values
     before rounding differ in the last fp32 bits, so now and then a rounding falls the other way (one bfloat16 step,
     2^-8 relative), and later roundings of that element see a different value.  This measures how far two correct
-    evaluations drift apart, which is what the GPU gate for this storage rests on: at least 97 % of the elements
-    identical, the others within two bfloat16 steps."""
+    evaluations drift apart on a short epoch (3,200 windows; the distance grows with the length of the run), which is
+    what the GPU gate for this storage is measured against: at least 97 % of the elements identical, at most one in a
+    thousand more than two bfloat16 steps away (a step: 2^-7 of the larger of the element and its row's rms value)."""
     from paper_2312_07743_amd import synth
-    from util import bf16_steps_apart
+    from util import bf16_agreement
     c = synth.zipf_corpus(500, 1.0, 8, 400, seed=3)
     kw = dict(window=5, negatives=5, seed=11, table_size=1 << 16, storage=1)
     f0, f1 = orc32.init_weights(11, c.vocab, 128, storage=1)
@@ -210,6 +256,5 @@ def test_float_and_double_builds_with_stochastic_rounding_stay_close(orc32, orc6
     rd = orc64.train_epoch(d0, d1, c.counts, c.tokens, c.sent_off, **kw)
     assert rf["pairs"] == rd["pairs"] and abs(rf["loss_sum"] - rd["loss_sum"]) < 1e-4 * rd["loss_sum"]
     for a, b in ((f0, d0), (f1, d1)):
-        steps = bf16_steps_apart(a, b.astype(np.float32))
-        assert (steps == 0).mean() >= 0.97, (steps == 0).mean()
-        assert steps.max() <= 2, steps.max()
+        same, mean_steps, far = bf16_agreement(a, b.astype(np.float32))
+        assert same >= 0.97 and mean_steps <= 0.03 and far <= 1e-3, (same, mean_steps, far)

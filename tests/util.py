@@ -4,9 +4,9 @@ import numpy as np
 
 def run_oracle(orc, corpus, *, dim, window, negatives, seed, epochs=1, table_size=1 << 16, subsample_t=0.0,
                window_mode=0, lr0=0.025, syn0=None, syn1neg=None, first_token_global_pos=0, tokens_per_epoch=None,
-               total_epochs=None, start_epoch=0, update_mode=0, negative_block=0):
+               total_epochs=None, start_epoch=0, update_mode=0, negative_block=0, storage=0):
     if syn0 is None:
-        syn0, syn1neg = orc.init_weights(seed, corpus.vocab, dim)
+        syn0, syn1neg = orc.init_weights(seed, corpus.vocab, dim, storage=storage)
     else:
         syn0, syn1neg = syn0.copy(), syn1neg.copy()
     total_epochs = total_epochs or epochs
@@ -16,7 +16,7 @@ def run_oracle(orc, corpus, *, dim, window, negatives, seed, epochs=1, table_siz
                             negatives=negatives, seed=seed, epoch=e, total_epochs=total_epochs, table_size=table_size,
                             subsample_t=subsample_t, window_mode=window_mode, lr0=lr0, update_mode=update_mode,
                             first_token_global_pos=first_token_global_pos, tokens_per_epoch=tokens_per_epoch,
-                            negative_block=negative_block)
+                            negative_block=negative_block, storage=storage)
         loss += r["loss_sum"]
         pairs += r["pairs"]
     return syn0, syn1neg, loss, pairs
@@ -25,13 +25,14 @@ def run_oracle(orc, corpus, *, dim, window, negatives, seed, epochs=1, table_siz
 def run_gpu(corpus, *, dim, window, negatives, seed, epochs=1, table_size=1 << 16, subsample_t=0.0, window_mode=0,
             lr0=0.025, sentences_in_flight=0, syn0=None, syn1neg=None, first_token_global_pos=0,
             tokens_per_epoch=None, total_epochs=None, start_epoch=0, naive=False, unit_shift=None, negative_block=0,
-            unit_tail=None):
+            unit_tail=None, storage=0):
     from paper_2312_07743_amd import binding
     from paper_2312_07743_amd.trainer import Trainer
     tr = Trainer(vocab=corpus.vocab, dim=dim, window=window, negatives=negatives, counts=corpus.counts,
                  tokens_per_epoch=tokens_per_epoch or corpus.n_tokens, seed=seed, table_size=table_size,
                  subsample_t=subsample_t, total_epochs=total_epochs or epochs, sentences_in_flight=sentences_in_flight,
-                 window_mode=window_mode, lr0=lr0, syn0=syn0, syn1neg=syn1neg, negative_block=negative_block)
+                 window_mode=window_mode, lr0=lr0, syn0=syn0, syn1neg=syn1neg, negative_block=negative_block,
+                 storage=storage)
     tr.set_corpus(corpus.tokens, corpus.sent_off)
     if unit_shift is not None:
         binding.w2v_debug_set_units(tr.ctx, unit_shift)
@@ -139,10 +140,9 @@ def edge_recovery(emb, tokens, sent_off, n_sample=2000, topk=10, seed=0):
     return hits / (len(sample) * topk), on_edges - at_random
 
 
-def bf16_steps_apart(a, b):
-    """How many bfloat16 values lie between the elements of a and b (float32 arrays of bfloat16-representable
-    values), counted on the ordered line of bfloat16 numbers."""
-    def line(x):
-        u = np.ascontiguousarray(x, np.float32).view(np.uint32).astype(np.int64) >> 16
-        return np.where(u & 0x8000, -(u & 0x7FFF), u & 0x7FFF)
-    return np.abs(line(a) - line(b))
+def bf16_agreement(got, ref):
+    """(share of identical elements, mean difference in bfloat16 steps, share of elements more than two steps apart)
+    of two float32 arrays of bfloat16 values.  A step is 2^-7 of max(|ref element|, rms of its row): elements near zero
+    are measured on their row's scale."""
+    steps = scaled_error(got, ref) / 2.0 ** -7
+    return float((got == ref).mean()), float(steps.mean()), float((steps > 2.001).mean())
