@@ -18,9 +18,12 @@ def build(force: bool = False) -> None:
         if (not force and os.path.exists(out)
                 and os.path.getmtime(out) >= os.path.getmtime(SRC)):
             continue
+        # linked under another name and moved into place: a process that has the old library mapped keeps it
+        tmp = f"{out}.{os.getpid()}.tmp"
         cmd = ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-Wall",
-               "-shared", "-fPIC", f"-DREAL={real}", SRC, "-o", out, "-lm"]
+               "-shared", "-fPIC", f"-DREAL={real}", SRC, "-o", tmp, "-lm"]
         subprocess.check_call(cmd)
+        os.replace(tmp, out)
 
 
 if __name__ == "__main__":

@@ -319,21 +319,30 @@ void orc_window_step_pairwise(real_t *syn0, real_t *syn1neg, uint32_t d,
 /*   (distance between the neighbours): unbiased;                      */
 /*   nearest (ties to even): kept only to show why it is not used.     */
 /* The 16 random bits of element e of a row written for token          */
-/* position pos:  S = draw(seed, epoch, pos, 64 + tag), tag = 0 for the */
-/* window's target row, 1+k for its negative k, 32 for the context row */
-/* of the token itself when it leaves the window span;                 */
-/*   c = high word of mix64(0x726F756E64 + e)   (a constant of e),     */
-/*   a = (lo32(S) + c) ^ rotl32(hi32(S) ^ c, 11);  a += rotl32(a, 15); */
-/*   bits = a >> 16.                                                   */
+/* position pos:  S = draw(seed, epoch, pos, 64), one 64-bit draw per   */
+/* position; the row's key K has the halves                            */
+/*   lo32(K) = lo32(S) * (lo32(m) | 1),  hi32(K) = hi32(S) * (hi32(m) | 1) */
+/* (mod 2^32) with m = mix64(0x6B6579 + tag), tag = 0 for the window's  */
+/* target row, 1+k for its negative k, 32 for the context row of the   */
+/* token itself when it leaves the window span;                        */
+/*   c = (high word of mix64(0x726F756E64 + e)) >> 8, made odd: a      */
+/*       24-bit constant of the element;                               */
+/*   a = (lo24(K) * c + hi32(K)) mod 2^32;   bits = a >> 16.           */
+/* Multiplying by an odd number permutes the 32-bit words, so hi32(K)  */
+/* is uniform and independent of lo24(K), and a is uniform for every   */
+/* element; two elements of one write differ by lo24(K) times the      */
+/* difference of their constants.                                      */
+/* Infinities are stored as they are; a NaN is stored as a NaN (its    */
+/* upper half with the quiet bit set).                                 */
 /* ------------------------------------------------------------------ */
-static uint32_t rotl32(uint32_t x, int r) { return (x << r) | (x >> (32 - r)); }
-
 uint32_t orc_round_bits(uint64_t seed, uint32_t epoch, uint64_t pos, uint32_t tag, uint32_t e)
 {
-    uint64_t S = orc_draw(seed, epoch, pos, 64u + tag);
-    uint32_t c = u32_of(orc_mix64(0x726F756E64ull + e));
-    uint32_t a = ((uint32_t)S + c) ^ rotl32((uint32_t)(S >> 32) ^ c, 11);
-    a += rotl32(a, 15);
+    uint64_t S = orc_draw(seed, epoch, pos, 64u);
+    uint64_t m = orc_mix64(0x6B6579ull + tag);
+    uint32_t k_lo = (uint32_t)S * ((uint32_t)m | 1u);
+    uint32_t k_hi = (uint32_t)(S >> 32) * ((uint32_t)(m >> 32) | 1u);
+    uint32_t c = (u32_of(orc_mix64(0x726F756E64ull + e)) >> 8) | 1u;
+    uint32_t a = (k_lo & 0xFFFFFFu) * c + k_hi;
     return a >> 16;
 }
 
@@ -345,6 +354,8 @@ float orc_to_bf16(float x, uint32_t mode, uint32_t bits16)
     if ((b & 0x7F800000u) != 0x7F800000u) {
         if (mode == 1) b += (bits16 & 0xFFFFu);
         else b += 0x7FFFu + ((b >> 16) & 1u);
+    } else if (b & 0x007FFFFFu) {
+        b |= 0x00400000u;                     /* a NaN stays a NaN when its low half is dropped */
     }
     b &= 0xFFFF0000u;
     memcpy(&x, &b, 4);

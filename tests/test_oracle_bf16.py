@@ -57,18 +57,30 @@ def _mix(z):
     return z ^ (z >> 31)
 
 
-def _rotl(x, r):
-    return ((x << r) | (x >> (32 - r))) & 0xFFFFFFFF
-
-
 def test_round_bits_follow_the_written_definition(orc32):
     for seed, ep, pos, tag, e in [(0, 0, 0, 0, 0), (5, 1, 12345, 3, 127), (0xDEADBEEF, 2, (1 << 40) + 7, 32, 511),
                                   (7, 0, (1 << 32) + 1, 20, 64), (M64, 3, 999, 1, 1)]:
-        S = orc32.draw(seed, ep, pos, 64 + tag)                   # the pinned draw function, index 64 + tag
-        c = _mix(0x726F756E64 + e) >> 32
-        a = (((S & 0xFFFFFFFF) + c) & 0xFFFFFFFF) ^ _rotl((S >> 32) ^ c, 11)
-        a = (a + _rotl(a, 15)) & 0xFFFFFFFF
-        assert orc32.round_bits(seed, ep, pos, tag, e) == a >> 16
+        S = orc32.draw(seed, ep, pos, 64)                         # the pinned draw function, index 64
+        m = _mix(0x6B6579 + tag)
+        k_lo = ((S & 0xFFFFFFFF) * ((m & 0xFFFFFFFF) | 1)) & 0xFFFFFFFF   # the row's key: both halves of S times odd
+        k_hi = ((S >> 32) * ((m >> 32) | 1)) & 0xFFFFFFFF                 # constants of the tag
+        c = ((_mix(0x726F756E64 + e) >> 32) >> 8) | 1             # 24 bits, odd
+        a = ((k_lo & 0xFFFFFF) * c + k_hi) & 0xFFFFFFFF
+        assert c < (1 << 24) and orc32.round_bits(seed, ep, pos, tag, e) == a >> 16
+
+
+def test_specials_survive_the_rounding(orc32):
+    """Infinities are stored as they are whatever the random bits; a NaN stays a NaN; the largest finite values may
+    round up to infinity (the upper neighbour of the last bfloat16 is infinity); denormals round like any pattern."""
+    inf = float("inf")
+    for u in (0, 1, 0x8000, 0xFFFF):
+        assert orc32.to_bf16(inf, 1, u) == inf and orc32.to_bf16(-inf, 1, u) == -inf
+        assert math.isnan(orc32.to_bf16(_from_bits(0x7F800001), 1, u)) and math.isnan(orc32.to_bf16(float("nan"), 1, u))
+        assert _f32_bits(orc32.to_bf16(_from_bits(0x7F800001), 1, u)) == 0x7FC00000
+    assert orc32.to_bf16(_from_bits(0x7F7FFFFF), 1, 0) == _from_bits(0x7F7F0000)
+    assert orc32.to_bf16(_from_bits(0x7F7FFFFF), 1, 1) == inf
+    assert _f32_bits(orc32.to_bf16(_from_bits(0x00000001), 1, 0xFFFF)) == 0x00010000
+    assert _f32_bits(orc32.to_bf16(_from_bits(0x00000001), 1, 0xFFFE)) == 0
 
 
 def test_round_bits_are_uniform_and_differ_between_elements_rows_and_positions(orc32):
