@@ -32,7 +32,7 @@ WORKLOADS = {
 
 
 def time_epochs(tokens, sent_off, counts, *, dim, window, negatives, subsample_t, table_size, steps, warmup,
-                update_mode=0):
+                update_mode=0, storage=0):
     """ms per epoch (HIP events on the launch stream) and the figures derived from it for one resident corpus."""
     import numpy as np
     import torch
@@ -41,7 +41,7 @@ def time_epochs(tokens, sent_off, counts, *, dim, window, negatives, subsample_t
     n_tokens = int(tokens.numel()) if isinstance(tokens, torch.Tensor) else len(tokens)
     tr = Trainer(vocab=len(counts), dim=dim, window=window, negatives=negatives, counts=counts, tokens_per_epoch=n_tokens,
                  seed=2024, table_size=table_size, subsample_t=subsample_t, total_epochs=warmup + steps,
-                 update_mode=update_mode)
+                 update_mode=update_mode, storage=storage)
     tr.set_corpus(tokens, sent_off)
     for e in range(warmup):
         tr.train_epoch(e)
@@ -58,11 +58,11 @@ def time_epochs(tokens, sent_off, counts, *, dim, window, negatives, subsample_t
     loss, pairs = tr.loss()
     plan = B.w2v_debug_get_plan(tr.ctx)
     tr.close()
-    algo = (2 * negatives + 4) * 4 * dim * (kept / steps)
+    algo = (2 * negatives + 4) * (2 if storage else 4) * dim * (kept / steps)
     return {"ms_per_epoch": ms, "words_per_s": n_tokens / (ms * 1e-3), "kept_fraction": kept / (steps * n_tokens),
             "algorithmic_GBs": algo / (ms * 1e-3) / 1e9, "frac_of_8TBs": algo / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-            "mean_loss": loss / max(pairs, 1), "update_mode": "summed" if plan["update"] else "overwrite",
-            "wavefronts": plan["wavefronts"], "epochs_timed": steps}
+            "mean_loss": loss / max(pairs, 1), "update_mode": "summed" if plan["update"] == 1 else "overwrite",
+            "wavefronts": plan["wavefronts"], "epochs_timed": steps, "table_storage": "bf16" if storage else "f32"}
 
 
 def other_workloads(mid):
@@ -76,10 +76,17 @@ def other_workloads(mid):
         r = time_epochs(mid.tokens, mid.sent_off, mid.counts, dim=d, window=5, negatives=5, subsample_t=1e-4,
                         table_size=1 << 24, steps=3, warmup=2)
         out.append(dict(workload=f"mid corpus, d={d}, W=5, N=5, t=1e-4", **r))
+    for d in (128, 256):          # extension: tables stored as bfloat16 (half the algorithmic bytes per kept word)
+        r = time_epochs(mid.tokens, mid.sent_off, mid.counts, dim=d, window=5, negatives=5, subsample_t=1e-4,
+                        table_size=1 << 24, steps=3, warmup=2, storage=1)
+        out.append(dict(workload=f"mid corpus, d={d}, W=5, N=5, t=1e-4, bfloat16 tables", **r))
     tok, counts = synth_device.zipf_tokens(550000, 1.1, 44_000_000, seed=1)
     off = torch.arange(44_001, dtype=torch.int64, device="cuda") * 1000
-    r = time_epochs(tok, off, counts, dim=300, window=5, negatives=10, subsample_t=1e-5, table_size=1 << 24, steps=3, warmup=1)
-    out.append(dict(workload="large prefix: vocab 550,000 Zipf(1.1), 44M tokens in 1,000-token sentences, d=300, W=5, N=10, t=1e-5", **r))
+    for storage in (0, 1):
+        r = time_epochs(tok, off, counts, dim=300, window=5, negatives=10, subsample_t=1e-5, table_size=1 << 24, steps=3,
+                        warmup=1, storage=storage)
+        out.append(dict(workload="large prefix: vocab 550,000 Zipf(1.1), 44M tokens in 1,000-token sentences, d=300, W=5, "
+                                 "N=10, t=1e-5" + (", bfloat16 tables" if storage else ""), **r))
     del tok
     tok, counts = synth_device.barabasi_albert_walk_tokens(1_000_000, 5, 1, 80, seed=1)
     off = torch.arange(1_000_001, dtype=torch.int64, device="cuda") * 80
@@ -117,6 +124,8 @@ def main():
                          "updates at once; for walk corpora)")
     ap.add_argument("--update-mode", type=int, default=0, choices=(0, 1, 2),
                     help="cfg.update_mode: 0 the library's choice from the word counts, 1 overwrite, 2 summed lock-free updates")
+    ap.add_argument("--storage", type=int, default=0, choices=(0, 1),
+                    help="cfg.storage: 0 float tables (the paper's precision), 1 bfloat16 tables with stochastic rounding")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="skip the short runs of the other configurations (d sweep, large and graph prefixes) that the "
@@ -165,7 +174,7 @@ def main():
     tr = Trainer(vocab=corpus.vocab, dim=dim, window=window, negatives=negatives, counts=corpus.counts,
                  tokens_per_epoch=corpus.n_tokens, seed=2024, table_size=table_size, subsample_t=t_sub,
                  total_epochs=E, sentences_in_flight=args.in_flight, window_mode=1 if args.fixed_width else 0, negative_block=args.negative_block,
-                 coherent_tables=args.coherent_tables, update_mode=args.update_mode)
+                 coherent_tables=args.coherent_tables, update_mode=args.update_mode, storage=args.storage)
     tr.set_corpus(corpus.tokens, corpus.sent_off)
     if args.from_host:
         t_pin = torch.as_tensor(corpus.tokens).pin_memory()
@@ -199,7 +208,7 @@ def main():
     loss_sum, pairs = tr.loss()
 
     words = corpus.n_tokens * args.steps
-    row_bytes = 4 * dim
+    row_bytes = (2 if args.storage else 4) * dim
     rows_per_kept = 2 * negatives + 4
     if args.negative_block > 1:
         # the negatives' rows move once per stretch that has a kept token (first timed epoch taken as typical)
@@ -214,9 +223,9 @@ def main():
     traffic = traffic_source = None
     # measured L2<->memory bytes per launch: NOT measured in this run, read from the committed rocprofv3 counter
     # summary of this workload (two --pmc runs of this same command, see the file)
-    tpath = os.path.join(ROOT, "profiles", f"window_kernel_{args.workload}_d{dim}_counters.txt")
+    tpath = os.path.join(ROOT, "profiles", f"window_kernel_all_workloads_counters.txt")
     if os.path.exists(tpath) and not (args.naive or args.fixed_width or args.from_host or args.negative_block > 1
-                                      or args.coherent_tables):
+                                      or args.coherent_tables or args.storage or args.update_mode):
         for line in open(tpath):
             if line.startswith("hbm_bytes_per_launch:"):
                 traffic = float(line.split(":")[1])
@@ -240,7 +249,7 @@ def main():
         "metric": "trained words/sec on 1 MI355X; achieved HBM GB/s vs peak",
         "value": words / wall, "unit": "words/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": wall / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "f32" if not args.storage else "f32 arithmetic, bf16 table storage", "data": "synthetic",
         "config": {"workload": f"{args.workload}: vocab {corpus.vocab} {what}, "
                                f"{corpus.n_tokens} tokens in {corpus.n_sent} sentences, d={dim}, W={window}, "
                                f"N={negatives}, subsample t={t_sub}, lr 0.025 linear decay"
@@ -263,7 +272,7 @@ def main():
     }
 
     plain = not (args.naive or args.fixed_width or args.from_host or args.negative_block > 1 or args.coherent_tables
-                 or args.dim or args.in_flight or args.update_mode)
+                 or args.dim or args.in_flight or args.update_mode or args.storage)
     if args.workload == "mid" and plain and not args.no_other_workloads:
         tr.close()
         out["other_workloads"] = other_workloads(corpus)
@@ -276,7 +285,7 @@ def main():
         c0 = time.perf_counter()
         orc.train_epoch(syn0, syn1, corpus.counts, corpus.tokens, corpus.sent_off, window=window, negatives=negatives,
                         seed=2024, epoch=0, total_epochs=E, table_size=table_size, subsample_t=t_sub, s_end=ns,
-                        window_mode=1 if args.fixed_width else 0, negative_block=args.negative_block)
+                        window_mode=1 if args.fixed_width else 0, negative_block=args.negative_block, storage=args.storage)
         cdt = time.perf_counter() - c0
         out["cpu_baseline"] = {"value": int(corpus.sent_off[ns]) / cdt, "unit": "words/s", "cores": 1,
                                "kind": "oracle",

@@ -54,8 +54,10 @@ typedef struct w2v_config {
                                      "traditional"); 1: fixed width ceil(W/2) (Sec. 3.2, the paper's) */
     uint32_t total_epochs;        /* E >= 1, length of the learning-rate decay                          */
     uint32_t sentences_in_flight; /* 0: as many wavefronts at once as the GPU holds, but at most one per
-                                     2,048 * ((N+1)/6)^2 tokens that survive subsampling in an epoch, and at
-                                     least 64 (lock-free sentences, Sec. 2.2 / 2.3);
+                                     2,048 * ((N+1)/6)^2 tokens that survive subsampling in an epoch, with
+                                     summed updates also at most 0.5 / (rows a wavefront holds * sum over
+                                     words of the squared shares of the kept tokens), and at least 64
+                                     (lock-free sentences, Sec. 2.2 / 2.3);
                                      k >= 1: at most k at once; 1 = strict corpus order, deterministic     */
     uint64_t tokens_per_epoch;    /* T >= 1, corpus tokens per epoch before subsampling                 */
     uint64_t seed;                /* keys every random decision and the weight initialisation          */
@@ -178,7 +180,10 @@ int w2v_train_epoch_host(w2v_ctx *ctx, const int32_t *tokens_host, const uint64_
 /* Same arithmetic without any on-chip reuse: every (target, context) pairing re-reads and
  * re-writes its context row, and the window's N+1 output rows go through global memory per
  * context word.  Exists only as the memory-traffic comparator for w2v_train_epoch (the role
- * the pre-existing GPU kernels play in Table 4).  Asynchronous. */
+ * the pre-existing GPU kernels play in Table 4).  A sentence longer than 1,024 tokens is handled in
+ * pieces of 1,024 tokens whose windows do not reach across the cut, so only sentences up to that
+ * length (the corpus preparation rule of Table 3 allows 1,000) train as w2v_train_epoch does.
+ * Asynchronous. */
 int w2v_train_epoch_naive(w2v_ctx *ctx, const int32_t *tokens_dev, const uint64_t *sent_off_dev,
                           uint64_t n_sent, uint64_t first_token_global_pos, uint32_t epoch);
 

@@ -79,7 +79,7 @@ inline int floats_per_lane(RowShape s) { return s.vw * s.r + s.tail; }
 bool pick_row_shape(uint32_t dim, uint32_t ld, RowShape *out);
 
 // LDS bytes one wavefront (= one workgroup) of the window kernel needs.
-uint32_t train_lds_bytes(const KernelArgs &a, RowShape s);
+uint32_t train_lds_bytes(const KernelArgs &a, RowShape s, int update);
 
 // Launchers (all asynchronous on `stream`).  Return hipSuccess or the launch error.
 hipError_t launch_init_weights(void *syn0, void *syn1neg, uint32_t vocab, uint32_t dim, uint32_t ld,

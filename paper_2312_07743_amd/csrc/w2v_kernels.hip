@@ -206,10 +206,11 @@ bool pick_row_shape(uint32_t dim, uint32_t ld, RowShape *out)
     return false;
 }
 
-uint32_t train_lds_bytes(const KernelArgs &a, RowShape s)
+uint32_t train_lds_bytes(const KernelArgs &a, RowShape s, int update)
 {
     const uint32_t rowf = kLanes * floats_per_lane(s);
-    return (2 * a.window + 3) * rowf * 4u + FCAP * 8u + kLanes * 32u + kLanes * a.negatives * 4u;
+    // ring, kept-token FIFO, per-window scalars, negatives; bfloat16 storage: the rounding draws of 64 windows
+    return (2 * a.window + 3) * rowf * 4u + FCAP * 8u + kLanes * 32u + kLanes * a.negatives * 4u + (update == 2 ? kLanes * 16u : 0u);
 }
 
 hipError_t launch_init_weights(void *syn0, void *syn1neg, uint32_t vocab, uint32_t dim, uint32_t ld,
@@ -280,7 +281,7 @@ uint32_t train_resident_waves(const KernelArgs &a, int update, int device)
     TrainFn fn = train_fn(a, s, update);
     if (!fn) return 0;
     int per_cu = 0, cus = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kLanes, train_lds_bytes(a, s)) != hipSuccess) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kLanes, train_lds_bytes(a, s, update)) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) return 0;
     return (uint32_t)(per_cu > 0 ? per_cu : 1) * (uint32_t)(cus > 0 ? cus : 1);
 }
@@ -291,7 +292,7 @@ hipError_t launch_train(const KernelArgs &a, int update, uint32_t waves, hipStre
     if (!pick_row_shape(a.dim, a.ld, &s)) return hipErrorInvalidValue;
     TrainFn fn = train_fn(a, s, update);
     if (!fn) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(fn, dim3(waves), dim3(kLanes), train_lds_bytes(a, s), stream, a);
+    hipLaunchKernelGGL(fn, dim3(waves), dim3(kLanes), train_lds_bytes(a, s, update), stream, a);
     return hipGetLastError();
 }
 

@@ -7,8 +7,10 @@
 //   base  = mix64(key ^ mix64(position))
 //   draw  = mix64(base + G*(index+1));   the high 32 bits are used
 //   index 0: subsampling decision, 1: window width, 2+k: negative k,
-//   64+t: the 64 bits that key the stochastic rounding of a row written for this position (bfloat16 storage):
-//   t = 0 the window's target row, 1+k its negative k, 32 the token's own context row when it leaves the span
+//   64: the 64 bits S that key the stochastic roundings of the rows written for this position (bfloat16 storage).
+//   The key of one row is row_key(S, t): both halves of S times odd constants of the tag t (0 the window's target
+//   row, 1+k its negative k, 32 the token's own context row when it leaves the span); multiplying by an odd number
+//   permutes the 32-bit words, so the halves of a key stay uniform and independent of each other.
 #pragma once
 #include <stdint.h>
 
@@ -22,7 +24,7 @@ namespace w2v {
 
 constexpr uint64_t kGolden = 0x9E3779B97F4A7C15ull;
 
-W2V_HD uint64_t mix64(uint64_t z)
+W2V_HD constexpr uint64_t mix64(uint64_t z)
 {
     z ^= z >> 30;
     z *= 0xBF58476D1CE4E5B9ull;
@@ -36,6 +38,13 @@ W2V_HD uint64_t epoch_key(uint64_t seed, uint32_t epoch) { return mix64(seed + k
 W2V_HD uint64_t position_base(uint64_t key, uint64_t pos) { return mix64(key ^ mix64(pos)); }
 W2V_HD uint32_t draw_u32(uint64_t base, uint32_t index) { return (uint32_t)(mix64(base + kGolden * ((uint64_t)index + 1u)) >> 32); }
 W2V_HD uint64_t draw_u64(uint64_t base, uint32_t index) { return mix64(base + kGolden * ((uint64_t)index + 1u)); }
+W2V_HD constexpr uint64_t row_key(uint64_t draw, uint32_t tag)
+{
+    const uint64_t m = mix64(0x6B6579ull + tag);
+    const uint32_t lo = (uint32_t)draw * ((uint32_t)m | 1u);
+    const uint32_t hi = (uint32_t)(draw >> 32) * ((uint32_t)(m >> 32) | 1u);
+    return ((uint64_t)hi << 32) | lo;
+}
 W2V_HD uint32_t mul_hi_u32(uint32_t a, uint32_t n) { return (uint32_t)(((uint64_t)a * (uint64_t)n) >> 32); }
 
 // subsampling: threshold 0xFFFFFFFF keeps always, otherwise keep iff draw < threshold

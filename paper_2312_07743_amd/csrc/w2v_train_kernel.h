@@ -261,26 +261,28 @@ __device__ __forceinline__ void row_load_bf16(__amdgpu_buffer_rsrc_t rs, int lan
     }
 }
 // Stochastic rounding of a working value to bfloat16: 16 random bits are added to the float's bit pattern and the
-// low half is dropped (infinities and NaNs keep their upper half).  The bits of element e of a row written with the
-// 64-bit draw S:  a = (lo32(S) + c_e) ^ rotl(hi32(S) ^ c_e, 11);  a += rotl(a, 15);  bits = a >> 16, with c_e a
-// constant of the element (the caller keeps it in a register).
-__device__ __forceinline__ uint32_t round_to_bf16(float x, uint32_t s_lo, uint32_t s_hi, uint32_t c)
+// low half is dropped (infinities stay, a NaN stays a NaN).  The bits of element e of a row written with the 64-bit
+// draw S are the upper half of  a = lo24(S) * c_e + hi32(S)  (one v_mad_u32_u24), with c_e an odd 24-bit constant of
+// the element that the caller keeps in a register.  v_cvt_sr_bf16_f32 does the rest in one instruction: it adds the
+// upper half of its second operand to the float and writes the upper half of the sum into one half of its
+// destination, so two calls fill one 32-bit word of the row.
+template <bool HIGH>
+__device__ __forceinline__ void round_to_bf16(uint32_t &word, float x, uint32_t s_lo, uint32_t s_hi, uint32_t c)
 {
-    uint32_t a = (s_lo + c) ^ __builtin_rotateleft32(s_hi ^ c, 11);
-    a += __builtin_rotateleft32(a, 15);
-    uint32_t b = __float_as_uint(x);
-    if ((b & 0x7F800000u) != 0x7F800000u) b += a >> 16;
-    return b >> 16;
+    const uint32_t a = __umul24(s_lo, c) + s_hi;
+    if constexpr (HIGH) asm("v_cvt_sr_bf16_f32 %0, %1, %2 op_sel:[0,0,1]" : "+v"(word) : "v"(x), "v"(a));
+    else asm("v_cvt_sr_bf16_f32 %0, %1, %2" : "+v"(word) : "v"(x), "v"(a));
 }
+// h: the row's chunk as packed words (element x of the chunk in half x & 1 of word x >> 1)
 template <int VW>
 __device__ __forceinline__ void row_store_bf16(__amdgpu_buffer_rsrc_t rs, int lane_bytes, const uint32_t *h)
 {
     if constexpr (VW == 1) {
         __builtin_amdgcn_raw_buffer_store_b16((unsigned short)h[0], rs, lane_bytes, 0, 0);
     } else if constexpr (VW == 2) {
-        __builtin_amdgcn_raw_buffer_store_b32(h[0] | (h[1] << 16), rs, lane_bytes, 0, 0);
+        __builtin_amdgcn_raw_buffer_store_b32(h[0], rs, lane_bytes, 0, 0);
     } else {
-        vec2u t; t.x = h[0] | (h[1] << 16); t.y = h[2] | (h[3] << 16);
+        vec2u t; t.x = h[0]; t.y = h[1];
         __builtin_amdgcn_raw_buffer_store_b64(t, rs, lane_bytes, 0, 0);
     }
 }
@@ -353,6 +355,9 @@ train_kernel(KernelArgs A)
     uint4 *cb_meta = reinterpret_cast<uint4 *>(kp + FCAP);                   // per-window scalars of the chunk
     uint32_t *cb_cm = reinterpret_cast<uint32_t *>(cb_meta + kLanes);        // [64][4] context multiplicities, 4 bits per slot
     uint32_t *cb_pack = cb_cm + 4 * kLanes;                                  // [64][N] negative id | multiplicity<<27
+    // bfloat16 storage: [64] the 64-bit draws that key the roundings of a window: of its centre (output rows) and of
+    // the position that leaves the span after it (that position's context row)
+    uint4 *cb_rnd = reinterpret_cast<uint4 *>(cb_pack + (size_t)kLanes * A.negatives);
 
     // A lane's share of a row: chunk r < R is VW consecutive floats at (r*64 + lane)*VW, chunk R + t is the
     // single float at 64*VW*R + t*64 + lane.  `chunks` calls f(chunk index, its width, its place in a register row).
@@ -381,7 +386,7 @@ train_kernel(KernelArgs A)
         chunks([&](auto r_, auto w_, auto o_) {
             constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
 #pragma unroll
-            for (int x = 0; x < CW; ++x) round_c[RO + x] = (uint32_t)(mix64(0x726F756E64ull + (uint64_t)(eoff[r] + x)) >> 32);
+            for (int x = 0; x < CW; ++x) round_c[RO + x] = ((uint32_t)(mix64(0x726F756E64ull + (uint64_t)(eoff[r] + x)) >> 32) >> 8) | 1u;
         });
     }
     auto load_row = [&](const float *table, uint32_t word, float *dst) {
@@ -416,9 +421,11 @@ train_kernel(KernelArgs A)
             const uint32_t s_lo = (uint32_t)sbits, s_hi = (uint32_t)(sbits >> 32);
             chunks([&](auto r_, auto w_, auto o_) {
                 constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
-                uint32_t h[CW];
-#pragma unroll
-                for (int x = 0; x < CW; ++x) h[x] = round_to_bf16(src[RO + x], s_lo, s_hi, round_c[RO + x]);
+                uint32_t h[(CW + 1) / 2] = {};
+                static_for<CW>([&](auto x_) {
+                    constexpr int x = decltype(x_)::value;
+                    round_to_bf16<(x & 1) != 0>(h[x >> 1], src[RO + x], s_lo, s_hi, round_c[RO + x]);
+                });
                 row_store_bf16<CW>(rs, eoff[r] * 2, h);
             });
             return;
@@ -584,10 +591,11 @@ train_kernel(KernelArgs A)
             return __ballot(meta_word >= 0 && meta_slot == slot) == 0;
         };
         // the row of `slot` goes back: as it is, or (summed) as fresh + (row - snapshot)
-        // the 64-bit draw that keys the rounding of the context row of kept position p (bfloat16 storage)
-        auto leave_bits = [&](uint32_t p) -> uint64_t {
+        // bfloat16 storage: the 64-bit draw of kept position p, which keys the rounding of its context row; inside the
+        // window loop the sampling stage has computed it (lane-parallel), here it is formed by the scalar unit
+        auto leave_draw = [&](uint32_t p) -> uint64_t {
             if constexpr (!BF16) return 0ull;
-            else return draw_u64(position_base(A.key, A.first_pos + t0 + uni(kp[p & (FCAP - 1)])), 64u + 32u);
+            else return draw_u64(position_base(A.key, A.first_pos + t0 + uni(kp[p & (FCAP - 1)])), 64u);
         };
         auto leave_finish = [&](uint32_t slot, uint32_t word, bool summed, const float *fresh, const float *snapv, uint64_t sbits) {
             float t[E];
@@ -599,13 +607,14 @@ train_kernel(KernelArgs A)
             store_row(A.syn0, word, t, sbits);
             give_slot(slot);
         };
-        auto ring_leave = [&](uint32_t p) {
+        // draw: the 64-bit draw of position p (bfloat16 storage)
+        auto ring_leave = [&](uint32_t p, uint64_t draw) {
             uint32_t slot, word;
             if (leave_decide(p, slot, word)) {
                 float fresh[E] = {}, snapv[E] = {};
                 const bool summed = sum_ring;
                 if (summed) { load_row(A.syn0, word, fresh); snap_load(slot, snapv); }
-                leave_finish(slot, word, summed, fresh, snapv, leave_bits(p));
+                leave_finish(slot, word, summed, fresh, snapv, BF16 ? row_key(draw, 32u) : 0ull);
             }
         };
 
@@ -646,6 +655,13 @@ train_kernel(KernelArgs A)
                 const uint32_t my_off = kp[idx];
                 const uint64_t base = position_base(A.key, A.first_pos + t0 + my_off);
                 my_b = (i0 + lane < n_lead) ? 0u : window_width(base, W, A.window_mode);   // lead-in tokens: context only
+                if constexpr (BF16) {
+                    const uint64_t d_own = draw_u64(base, 64u);
+                    uint64_t d_leave = 0ull;
+                    const uint32_t me = i0 + lane;
+                    if (me >= W) d_leave = draw_u64(position_base(A.key, A.first_pos + t0 + kp[(me - W) & (FCAP - 1)]), 64u);
+                    cb_rnd[lane] = make_uint4((uint32_t)d_own, (uint32_t)(d_own >> 32), (uint32_t)d_leave, (uint32_t)(d_leave >> 32));
+                }
                 // negatives: drawn at my own position, or at the first position of my stretch of 2^neg_shift tokens
                 my_stretch = my_off >> A.neg_shift;
                 const bool dump = A.dump.keep != nullptr && i0 + lane >= n_lead;   // test surface: my own decisions
@@ -828,6 +844,12 @@ train_kernel(KernelArgs A)
                 const uint32_t enter_word = uni(mraw.z);
                 const bool has_next = j + 1 < nwin;
 
+                uint64_t win_draw = 0ull, leave_draw_j = 0ull;      // bfloat16 storage: this window's rounding draws
+                if constexpr (BF16) {
+                    const uint4 r = cb_rnd[j];
+                    win_draw = uni64(((uint64_t)r.y << 32) | r.x);
+                    leave_draw_j = uni64(((uint64_t)r.w << 32) | r.z);
+                }
                 // (a) ask LDS for the next window's scalars now, use them after the ring work below
                 uint4 mraw_next = make_uint4(0u, 0u, kNoWord, 0u);
                 uint32_t pack_next = 0;
@@ -930,9 +952,8 @@ train_kernel(KernelArgs A)
                     if constexpr (!LOAD_PER_BLOCK) static_for<NCW>(fetch_slot);
                     // One pass: the KC output rows held in OB (ids in pv, rows kb .. kb+KC-1 of the window) against
                     // all context slots.
-                    // bfloat16 storage: the centre's position keys the rounding of this window's output rows
-                    const uint64_t win_base = BF16 ? position_base(A.key, A.first_pos + t0 + uni(kp[i & (FCAP - 1)])) : 0ull;
-                    auto out_bits = [&](uint32_t tag) -> uint64_t { return BF16 ? draw_u64(win_base, 64u + tag) : 0ull; };
+                    // bfloat16 storage: the centre's draw keys the rounding of this window's output rows
+                    auto out_bits = [&](uint32_t tag) -> uint64_t { return BF16 ? row_key(win_draw, tag) : 0ull; };
                     auto run_pass = [&](uint32_t kb, auto &OB, uint32_t pv) {
                         const uint32_t gk = kb + lane_k;
                         const float mult_lane = (KEXACT || gk <= N) ? (GENERAL ? (float)(pv >> kIdBits) : 1.0f) : 0.0f;
@@ -1205,9 +1226,9 @@ train_kernel(KernelArgs A)
                 }
                 if constexpr (SUMMED) {
                     if (sum_ring) { if (lv) leave_finish(lv_slot, lv_word, lv_summed, lv_fresh, lv_snap, 0ull); }
-                    else if (i >= W) ring_leave(i - W);
+                    else if (i >= W) ring_leave(i - W, 0ull);
                 } else {
-                    if (i >= W) ring_leave(i - W);
+                    if (i >= W) ring_leave(i - W, leave_draw_j);
                 }
 
                 // (i) next window's scalars and rows become current
@@ -1257,7 +1278,7 @@ train_kernel(KernelArgs A)
                     });
                 }
             } else {
-                for (uint32_t p = first; p < n_ins; ++p) ring_leave(p);
+                for (uint32_t p = first; p < n_ins; ++p) ring_leave(p, leave_draw(p));
             }
         }
         __syncthreads();
