@@ -210,7 +210,9 @@ uint32_t train_lds_bytes(const KernelArgs &a, RowShape s, int update)
 {
     const uint32_t rowf = kLanes * floats_per_lane(s);
     // ring, kept-token FIFO, per-window scalars, negatives; bfloat16 storage: the rounding draws of 64 windows
-    return (2 * a.window + 3) * rowf * 4u + FCAP * 8u + kLanes * 32u + kLanes * a.negatives * 4u + (update == 2 ? kLanes * 16u : 0u);
+    const int kmode = a.negatives + 1 > 2u * KC ? 3 : a.negatives + 1 > (uint32_t)KC ? 2 : a.negatives + 1 == (uint32_t)KC ? 1 : 0;
+    return (2 * a.window + 3) * rowf * 4u + FCAP * 8u + kLanes * 32u + kLanes * a.negatives * 4u +
+           (update == 2 && rounding_draws_in_lds(kmode) ? kLanes * 16u : 0u);
 }
 
 hipError_t launch_init_weights(void *syn0, void *syn1neg, uint32_t vocab, uint32_t dim, uint32_t ld,

@@ -323,6 +323,7 @@ constexpr uint32_t kNoWord = 0xFFFFFFFFu;
 // (e: floats of a row per lane, wcap: widest window of the instantiation; measured: rows of one float per lane
 // gain 17 % from 4 per SIMD (128 VGPRs, 16 spilled), 5 spills 56; rows of two floats gain nothing from 4
 // because LDS then limits the CU; 3 for rows of 4 floats per lane spills)
+constexpr bool rounding_draws_in_lds(int kmode) { return kmode <= 1; }
 constexpr int occupancy_goal(int e, int wcap) { return (e == 1 && wcap <= 5) ? 4 : (e <= 2 && wcap <= 10) ? 3 : ((e * wcap <= 25) ? 2 : 1); }
 
 // SUMMED: lock-free updates are added to what memory holds when a row goes back, instead of overwriting it with a copy
@@ -343,6 +344,10 @@ train_kernel(KernelArgs A)
     constexpr bool KFULL = KMODE >= 1;   // the first KC output rows all exist
     constexpr bool KEXACT = KMODE == 1;  // ... and there are no others
     constexpr bool NREG = KMODE <= 1;    // at most KC - 1 negatives: the sampling stage keeps them in registers
+    // bfloat16 storage: the rounding draws of 64 windows are computed lane-parallel in the sampling stage and kept in
+    // LDS, except where that kilobyte would cost the CU a wavefront (the shapes with two passes over the output
+    // rows): there the scalar unit computes the two draws of a window when the window begins
+    constexpr bool DRAWS_IN_LDS = BF16 && rounding_draws_in_lds(KMODE);
 
     extern __shared__ __align__(16) unsigned char lds_raw[];
     const int lane = threadIdx.x;
@@ -655,7 +660,7 @@ train_kernel(KernelArgs A)
                 const uint32_t my_off = kp[idx];
                 const uint64_t base = position_base(A.key, A.first_pos + t0 + my_off);
                 my_b = (i0 + lane < n_lead) ? 0u : window_width(base, W, A.window_mode);   // lead-in tokens: context only
-                if constexpr (BF16) {
+                if constexpr (DRAWS_IN_LDS) {
                     const uint64_t d_own = draw_u64(base, 64u);
                     uint64_t d_leave = 0ull;
                     const uint32_t me = i0 + lane;
@@ -845,10 +850,13 @@ train_kernel(KernelArgs A)
                 const bool has_next = j + 1 < nwin;
 
                 uint64_t win_draw = 0ull, leave_draw_j = 0ull;      // bfloat16 storage: this window's rounding draws
-                if constexpr (BF16) {
+                if constexpr (DRAWS_IN_LDS) {
                     const uint4 r = cb_rnd[j];
                     win_draw = uni64(((uint64_t)r.y << 32) | r.x);
                     leave_draw_j = uni64(((uint64_t)r.w << 32) | r.z);
+                } else if constexpr (BF16) {
+                    win_draw = leave_draw(i);
+                    if (i >= W) leave_draw_j = leave_draw(i - W);
                 }
                 // (a) ask LDS for the next window's scalars now, use them after the ring work below
                 uint4 mraw_next = make_uint4(0u, 0u, kNoWord, 0u);

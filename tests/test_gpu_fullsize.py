@@ -140,7 +140,8 @@ def _lock_free_against(mid, reference, kept_share=(0.45, 0.56)):
         tr = Trainer(vocab=mid.vocab, dim=P["dim"], window=P["window"], negatives=P["negatives"], counts=mid.counts,
                      tokens_per_epoch=mid.n_tokens, seed=run["seed"], table_size=P["table_size"],
                      subsample_t=P["subsample_t"], total_epochs=P["epochs"], sentences_in_flight=0,
-                     negative_block=P.get("negative_block", 0), window_mode=P.get("window_mode", 0))
+                     negative_block=P.get("negative_block", 0), window_mode=P.get("window_mode", 0),
+                     storage=P.get("storage", 0))
         tr.set_corpus(mid.tokens, mid.sent_off)
         losses, kept, invalid = [], 0, 0
         for e in range(P["epochs"]):
@@ -292,3 +293,10 @@ def test_default_concurrency_learns_on_a_small_corpus():
     score = planted_score(tr.embeddings(0), c.labels)
     tr.close()
     assert score >= 0.97 and losses[-1] < 2.60 and losses == sorted(losses, reverse=True), (score, losses)
+
+
+def test_lock_free_run_with_bf16_tables_matches_serial_oracle_statistically(mid):
+    """cfg.storage = 1 (tables stored as bfloat16, stochastic rounding) at the full 'Mid' size, every sentence in
+    flight, against the serial oracle run with the same storage (stored by make_mid_hogwild_reference.py --bf16)."""
+    with open(os.path.join(HERE, "golden", "mid_hogwild_reference_bf16.json")) as f:
+        _lock_free_against(mid, json.load(f))
