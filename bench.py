@@ -32,7 +32,7 @@ WORKLOADS = {
 
 
 def time_epochs(tokens, sent_off, counts, *, dim, window, negatives, subsample_t, table_size, steps, warmup,
-                update_mode=0, storage=0):
+                update_mode=0, storage=0, window_mode=0):
     """ms per epoch (HIP events on the launch stream) and the figures derived from it for one resident corpus."""
     import numpy as np
     import torch
@@ -41,7 +41,7 @@ def time_epochs(tokens, sent_off, counts, *, dim, window, negatives, subsample_t
     n_tokens = int(tokens.numel()) if isinstance(tokens, torch.Tensor) else len(tokens)
     tr = Trainer(vocab=len(counts), dim=dim, window=window, negatives=negatives, counts=counts, tokens_per_epoch=n_tokens,
                  seed=2024, table_size=table_size, subsample_t=subsample_t, total_epochs=warmup + steps,
-                 update_mode=update_mode, storage=storage)
+                 update_mode=update_mode, storage=storage, window_mode=window_mode)
     tr.set_corpus(tokens, sent_off)
     for e in range(warmup):
         tr.train_epoch(e)
@@ -90,9 +90,10 @@ def other_workloads(mid):
     del tok
     tok, counts = synth_device.barabasi_albert_walk_tokens(1_000_000, 5, 1, 80, seed=1)
     off = torch.arange(1_000_001, dtype=torch.int64, device="cuda") * 80
-    for mode, name in ((0, "library default"), (1, "update_mode 1")):
+    for mode, fixed, name in ((0, 0, "library default"), (1, 0, "update_mode 1"),
+                              (1, 1, "update_mode 1, fixed window width ceil(W/2) (the paper's variant)")):
         r = time_epochs(tok, off, counts, dim=128, window=10, negatives=5, subsample_t=0.0, table_size=1 << 24, steps=3,
-                        warmup=1, update_mode=mode)
+                        warmup=1, update_mode=mode, window_mode=fixed)
         out.append(dict(workload=f"graph prefix: Barabasi-Albert 1M nodes (m=5), 80M tokens in walks of 80, d=128, W=10, N=5, "
                                  f"no subsampling, {name}", **r))
     del tok

@@ -324,14 +324,20 @@ constexpr uint32_t kNoWord = 0xFFFFFFFFu;
 // gain 17 % from 4 per SIMD (128 VGPRs, 16 spilled), 5 spills 56; rows of two floats gain nothing from 4
 // because LDS then limits the CU; 3 for rows of 4 floats per lane spills)
 constexpr bool rounding_draws_in_lds(int kmode) { return kmode <= 1; }
-constexpr int occupancy_goal(int e, int wcap) { return (e == 1 && wcap <= 5) ? 4 : (e <= 2 && wcap <= 10) ? 3 : ((e * wcap <= 25) ? 2 : 1); }
+// (the summed width-10 kernel of rows of two floats per lane spilled 72 registers at 3 per SIMD; its ring limits a CU
+// to 9 wavefronts anyway: at 2 per SIMD it spills none and the walk workload runs 5 % faster on 8 per CU)
+constexpr int occupancy_goal(int e, int wcap, bool summed = false)
+{
+    if (summed && wcap > 5 && e == 2) return 2;
+    return (e == 1 && wcap <= 5) ? 4 : (e <= 2 && wcap <= 10) ? 3 : ((e * wcap <= 25) ? 2 : 1);
+}
 
 // SUMMED: lock-free updates are added to what memory holds when a row goes back, instead of overwriting it with a copy
 // that was fetched up to 2W+1 windows earlier (see "summed updates" below); the rows are then stored at system scope.
 // BF16: the tables hold bfloat16 (2 bytes per element, row stride A.ld elements); rows are widened to fp32 when they are
 // fetched into registers / the ring and rounded stochastically when they go back (an extension; the paper stores fp32).
 template <int VW, int R, int TAIL, int WCAP, bool FULL, int KMODE, bool SUMMED, bool BF16>
-__global__ void __launch_bounds__(kLanes) __attribute__((amdgpu_waves_per_eu(occupancy_goal(VW * R + TAIL, WCAP))))
+__global__ void __launch_bounds__(kLanes) __attribute__((amdgpu_waves_per_eu(occupancy_goal(VW * R + TAIL, WCAP, SUMMED))))
 train_kernel(KernelArgs A)
 {
     static_assert(!(BF16 && (FULL || SUMMED)), "bfloat16 rows go through buffer resources and are overwritten");
