@@ -978,16 +978,19 @@ train_kernel(KernelArgs A)
                         for (int kk = 0; kk < KC; ++kk)
 #pragma unroll
                             for (int x = 0; x < E; ++x) dO[kk][x] = 0.0f;
-                        // summed mode: what memory holds of the output rows now is fetched into the registers of the
-                        // window's copies as soon as the last block no longer needs those (its context deltas are
-                        // formed first, its output deltas while the loads travel) and takes the deltas in step (f)
+                        // summed mode: what memory holds of the output rows now is fetched into registers of its own
+                        // when the last block of context slots begins, so that the block's arithmetic covers the trip,
+                        // and takes the deltas in step (f)
                         bool fresh_loaded = false;
+                        float FR[SUMMED ? KC : 1][SUMMED ? E : 1];
                         auto load_fresh = [&]() {
                             if constexpr (SUMMED) {
 #pragma unroll
                                 for (int kk = 0; kk < KC; ++kk) {
                                     const uint32_t pk = lane_value(pv, (uint32_t)kk);
-                                    if ((KEXACT || kb + kk <= N) && (!GENERAL || (pk >> kIdBits))) load_out(pk & kIdMask, OB[kk]);
+#pragma unroll
+                                    for (int x = 0; x < E; ++x) FR[kk][x] = 0.0f;
+                                    if ((KEXACT || kb + kk <= N) && (!GENERAL || (pk >> kIdBits))) load_out(pk & kIdMask, FR[kk]);
                                 }
                             }
                             fresh_loaded = true;
@@ -999,6 +1002,7 @@ train_kernel(KernelArgs A)
                             constexpr int NC = (q < REM) ? BASE + 1 : BASE;
                             constexpr int C0 = q * BASE + (q < REM ? q : REM);
                             if (MASKED && !(amask >> C0)) return;       // no slot from here on takes part
+                            if constexpr (SUMMED && q == NQW - 1) load_fresh();
                             if constexpr (LOAD_PER_BLOCK)
                                 static_for<NC>([&](auto cc_tag) { fetch_slot(std::integral_constant<int, C0 + decltype(cc_tag)::value>{}); });
                             float acc[CC * KC];
@@ -1112,13 +1116,7 @@ train_kernel(KernelArgs A)
                             };
                             using std::true_type;
                             using std::false_type;
-                            if constexpr (SUMMED && q == NQW - 1) {
-                                sweep(true_type{}, false_type{});
-                                load_fresh();
-                                sweep(false_type{}, true_type{});
-                            } else {
-                                sweep(true_type{}, true_type{});
-                            }
+                            sweep(true_type{}, true_type{});
                         });
 
                         // (f) output rows go back (lock-free) once per window
@@ -1141,7 +1139,10 @@ train_kernel(KernelArgs A)
                                 if ((KEXACT || kb + kk <= N) && (!GENERAL || (pk >> kIdBits))) {
                                     float t[E];
 #pragma unroll
-                                    for (int x = 0; x < E; ++x) t[x] = OB[kk][x] + dO[kk][x];
+                                    for (int x = 0; x < E; ++x) {
+                                        if constexpr (SUMMED) t[x] = FR[kk][x] + dO[kk][x];
+                                        else t[x] = OB[kk][x] + dO[kk][x];
+                                    }
                                     store_out(pk & kIdMask, t, out_bits(kb + (uint32_t)kk));
                                 }
                             }

@@ -53,6 +53,35 @@ def test_strict_order_equals_resident_training_bit_for_bit(orc32, pinned):
     host.close()
 
 
+@pytest.mark.parametrize("variant", ["bf16", "summed"])
+def test_strict_order_equals_resident_training_for_the_other_kernels(variant):
+    """The host-fed path launches whatever kernel the context uses: tables stored as bfloat16, and summed updates
+    (forced on in strict order through the test surface): bit-equal to training on a resident copy."""
+    rng = np.random.default_rng(2)
+    lens = [300, 0, 900, 1, 640, 77, 1000, 2, 512]
+    tok = rng.integers(0, 300, size=sum(lens)).astype(np.int32)
+    off = np.cumsum([0] + lens).astype(np.uint64)
+    c = synth.Corpus(tok, off, np.bincount(tok, minlength=300).astype(np.uint64))
+    kw = dict(sentences_in_flight=1, storage=1) if variant == "bf16" else dict(sentences_in_flight=1, update_mode=2)
+    res, host = _trainer(c, **kw), _trainer(c, **kw)
+    if variant == "summed":
+        B.w2v_debug_set_update(res.ctx, 1)
+        B.w2v_debug_set_update(host.ctx, 1)
+    res.set_corpus(c.tokens, c.sent_off)
+    for e in range(2):
+        res.train_epoch(e)
+        B.w2v_train_epoch_host(host.ctx, c.tokens, c.sent_off, len(lens), 0, e, host_staging(host, 2 * 8192), 2 * 8192)
+    torch.cuda.synchronize()
+    if variant == "summed":
+        assert B.w2v_debug_get_plan(host.ctx)["update"] == 1
+    (l0, p0), (l1, p1) = res.loss(), host.loss()
+    assert p0 == p1 and abs(l0 - l1) <= 1e-9 * abs(l0) and res.counters() == host.counters()
+    for which in (0, 1):
+        assert np.array_equal(res.embeddings(which), host.embeddings(which))
+    res.close()
+    host.close()
+
+
 def host_staging(tr, nbytes):
     if getattr(tr, "staging", None) is None or tr.staging.numel() != nbytes:
         tr.staging = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
