@@ -385,7 +385,7 @@ train_kernel(KernelArgs A)
 #pragma unroll
     for (int r = 0; r < NCH; ++r)
         eoff[r] = r < R ? (r * kLanes + lane) * VW : kLanes * VW * R + (r - R) * kLanes + lane;
-    const int lane_c = lane / KC, lane_k = lane % KC;   // pairing handled by this lane after the reduction
+    const int lane_c0 = lane / KC, lane_k0 = lane % KC;   // pairing handled by this lane after the reduction
 
     const uint32_t row_bytes = A.dim * 4u;
     // row `word` of a table -> registers (zeros beyond dim) / registers -> the row (nothing beyond dim)
@@ -833,8 +833,8 @@ train_kernel(KernelArgs A)
             // scalars and output rows of the first window; later windows get theirs one window ahead
             uint4 mraw = cb_meta[0];
             uint32_t packv = 0;
-            if (lane_k >= 1 && (KFULL || (uint32_t)lane_k <= N)) packv = cb_pack[lane_k - 1];
-            if (lane_k == 0) packv = mraw.y | (1u << kIdBits);
+            if (lane_k0 >= 1 && (KFULL || (uint32_t)lane_k0 <= N)) packv = cb_pack[lane_k0 - 1];
+            if (lane_k0 == 0) packv = mraw.y | (1u << kIdBits);
             float O[KC][E];
             const bool first_idle = (uni(mraw.x) >> 19) & 1u;
 #pragma unroll
@@ -844,6 +844,11 @@ train_kernel(KernelArgs A)
                 for (int x = 0; x < E; ++x) O[kk][x] = 0.0f;
                 if (!first_idle && (KFULL || (uint32_t)kk <= N)) load_out(pk & kIdMask, O[kk]);
             }
+            // The rows of the chunk's first window are waited for here, once per 64 windows.  Without this wait the
+            // registers of O carry loads in flight into the window loop on one of its two entry paths, the compiler's
+            // wait-count bookkeeping merges the paths conservatively, and every window gets a full vmcnt(0) in front of
+            // its first multiply-add: right behind the prefetch of the next window's rows, which then hides nothing.
+            __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0), the other counters left alone
 
             for (uint32_t j = 0; j < nwin; ++j) {
                 const uint32_t i = i0 + j;
@@ -855,6 +860,16 @@ train_kernel(KernelArgs A)
                 const uint32_t enter_word = uni(mraw.z);
                 const bool has_next = j + 1 < nwin;
 
+                // The pairing a lane handles after the reduction.  In the shapes under register pressure (windows wider
+                // than 5, two passes over the output rows, five floats per lane) it is taken through an empty asm
+                // statement once per window: the compiler then forms what follows from it (labels, weights, addresses
+                // and shifts of the slot weights, one set per block of every width) where it is used, two or three
+                // instructions each, instead of computing all of it once at kernel entry, where it filled some twenty
+                // registers that were spilled; a reload from scratch waits behind every row prefetch in flight
+                // (vector memory operations complete in order), which cost those shapes 2 to 5 % of their time.  The
+                // other shapes spill nothing on the window path and are 1 to 2 % faster with the values hoisted.
+                uint32_t lane_c = (uint32_t)lane_c0, lane_k = (uint32_t)lane_k0;
+                if constexpr (WCAP > 5 || MULTI || E > 4) asm volatile("" : "+v"(lane_c), "+v"(lane_k));
                 uint64_t win_draw = 0ull, leave_draw_j = 0ull;      // bfloat16 storage: this window's rounding draws
                 if constexpr (DRAWS_IN_LDS) {
                     const uint4 r = cb_rnd[j];
@@ -930,6 +945,24 @@ train_kernel(KernelArgs A)
                 if constexpr (!TWO) fetch_next_window(On);
                 else if (nact == 0) fetch_next_window(O);
 
+                // Called when the window's last pass is about to store its output rows.  Everything fetched so far (the
+                // entering context row, the next window's rows; summed mode: the fresh row and the snapshot of the
+                // position that leaves) has had the window's arithmetic to arrive and is waited for HERE, before this
+                // window's stores are issued: vector memory operations complete in order and the compiler's waits are
+                // all-or-nothing where paths merge, so a wait placed after the stores also waits for their
+                // acknowledgements.  After this point the loop waits for nothing that has a store in front of it.
+                auto arrivals_before_stores = [&](bool window_done) {
+                    __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0), the other counters left alone
+                    if (pend) {
+                        regs_to_ring(ring + (size_t)pend_slot * ROWF, pend_row);
+                        if (sum_ring) snap_store(pend_slot, pend_row);
+                        pend = false;
+                    }
+                    if constexpr (SUMMED) {      // (the leaving row has received all of the window's deltas only then)
+                        if (window_done && sum_ring && lv) { leave_finish(lv_slot, lv_word, lv_summed, lv_fresh, lv_snap, 0ull); lv = false; }
+                    }
+                };
+
                 // (e) the window's arithmetic over context slots 0..NCW-1.
                 //     GENERAL = false: straight-line code for the common window: all NCW slots exist, no two
                 //     of them share a ring row, every negative is distinct and differs from the target.
@@ -968,7 +1001,7 @@ train_kernel(KernelArgs A)
                     // all context slots.
                     // bfloat16 storage: the centre's draw keys the rounding of this window's output rows
                     auto out_bits = [&](uint32_t tag) -> uint64_t { return BF16 ? row_key(win_draw, tag) : 0ull; };
-                    auto run_pass = [&](uint32_t kb, auto &OB, uint32_t pv) {
+                    auto run_pass = [&](uint32_t kb, auto &OB, uint32_t pv, bool early_wait, bool last) {
                         const uint32_t gk = kb + lane_k;
                         const float mult_lane = (KEXACT || gk <= N) ? (GENERAL ? (float)(pv >> kIdBits) : 1.0f) : 0.0f;
                         const float label = (gk == 0) ? 1.0f : 0.0f;
@@ -1120,6 +1153,7 @@ train_kernel(KernelArgs A)
                         });
 
                         // (f) output rows go back (lock-free) once per window
+                        if (early_wait) arrivals_before_stores(last);
                         if (hand_over) {
                             // the negatives' rows stay in registers for the next window (every row exists and
                             // counts once in a window that hands over)
@@ -1149,7 +1183,7 @@ train_kernel(KernelArgs A)
                         }
                     };
                     if constexpr (!MULTI) {
-                        run_pass(0u, O, packv);
+                        run_pass(0u, O, packv, true, true);
                     } else if constexpr (TWO) {
                         // two passes: the second batch of rows travels into On while the first batch is worked on,
                         // and the next window's first batch travels into O while the second is worked on
@@ -1162,9 +1196,13 @@ train_kernel(KernelArgs A)
                             for (int x = 0; x < E; ++x) On[kk][x] = 0.0f;
                             if ((uint32_t)KC + kk <= N) load_out(pk & kIdMask, On[kk]);
                         }
-                        run_pass(0u, O, packv);
+                        // (the early wait sits before the first pass's stores: the second batch is needed right after
+                        // it anyway; before the second pass's stores it would wait for the next window's first batch,
+                        // which has only had the second pass to arrive: measured 2 % slower than letting the next
+                        // window wait for it)
+                        run_pass(0u, O, packv, true, false);
                         fetch_next_window(O);
-                        run_pass((uint32_t)KC, On, pv2);
+                        run_pass((uint32_t)KC, On, pv2, false, true);
                     } else {
                         for (uint32_t kb = 0; kb <= N; kb += KC) {
                             uint32_t pv = packv;
@@ -1179,7 +1217,7 @@ train_kernel(KernelArgs A)
                                     if (kb + kk <= N) load_out(pk & kIdMask, O[kk]);
                                 }
                             }
-                            run_pass(kb, O, pv);
+                            run_pass(kb, O, pv, kb + (uint32_t)KC > N, kb + (uint32_t)KC > N);
                         }
                     }
                 };
@@ -1217,6 +1255,10 @@ train_kernel(KernelArgs A)
                     }
 #undef W2V_WIN
                     if (!done) do_window(integral_constant<int, NCTX>{}, T{});   // anything else
+                } else {
+                    // a position without context (a lead-in token, a sentence of one kept word): nothing to compute,
+                    // but the same wait, so that every path through the window has made it before the paths join
+                    arrivals_before_stores(true);
                 }
 
                 // (g) rows of the next window that this window has just rewritten are fetched again
@@ -1230,6 +1272,9 @@ train_kernel(KernelArgs A)
                                 const uint32_t pk = lane_value(packv_next, (uint32_t)kk);
                                 load_out(pk & kIdMask, TWO ? O[kk] : On[kk]);
                             }
+                        // (rare; waited for at once, so that where this path joins the other no register of the next
+                        // window's rows has a load in flight: the compiler would wait for the stores above as well)
+                        __builtin_amdgcn_s_waitcnt(0x0F70);
                     }
                 }
 

@@ -254,6 +254,24 @@ def test_degenerate_sentences(orc32):
     _parity(orc32, c, dim=128, window=5, negatives=5, seed=5, table_size=4099, subsample_t=2e-2)
 
 
+def test_corpus_passed_as_one_long_sentence(orc32):
+    """Ignoring sentence delimiters (the other half of the paper's own window variant, Section 3.2) means passing the
+    corpus as one sentence: 12,000 tokens, far more than the kept-token FIFO or one sampling chunk holds, with random
+    and with fixed window widths, subsampled, as one unit of work and cut into 8 and into 64 stretches (each stretch
+    reads the W kept tokens on either side as context only, so the windows are those of the whole sentence)."""
+    c0 = synth.zipf_corpus(800, 1.05, 12, 1000, seed=21)
+    one = synth.Corpus(c0.tokens, np.array([0, c0.n_tokens], np.uint64), c0.counts)
+    for window_mode in (0, 1):
+        kw = dict(dim=128, window=5, negatives=5, seed=9, table_size=1 << 16, subsample_t=5e-3, window_mode=window_mode)
+        _parity(orc32, one, unit_shift=0, **kw)
+        _parity(orc32, one, unit_shift=3, **kw)
+        _parity(orc32, one, unit_shift=6, **kw)
+    # the same tokens with delimiters train other windows: the delimiters matter
+    r_one = run_oracle(orc32, one, dim=128, window=5, negatives=5, seed=9, table_size=1 << 16, subsample_t=5e-3)
+    r_cut = run_oracle(orc32, c0, dim=128, window=5, negatives=5, seed=9, table_size=1 << 16, subsample_t=5e-3)
+    assert r_one[3] > r_cut[3]
+
+
 def test_repeated_context_words(orc32):
     # walks that step back and stay: most windows hold a word at several context positions (one ring row,
     # counted with its multiplicity); a run of one word fills more than 15 slots of a wide window

@@ -23,7 +23,8 @@ def _static_epoch(tr, epoch, first=0):
     return float(out_loss.item()), int(out_pairs.item())
 
 
-@pytest.mark.parametrize("shape", [dict(dim=128, window=5, negatives=5), dict(dim=300, window=4, negatives=10)])
+@pytest.mark.parametrize("shape", [dict(dim=128, window=5, negatives=5), dict(dim=300, window=4, negatives=10),
+                                   dict(dim=128, window=5, negatives=5, storage=1)])
 def test_strict_order_equals_the_allocating_entry_point_bit_for_bit(shape):
     big = synth.zipf_corpus(600, 1.05, 9, 500, seed=3)
     small = synth.Corpus(big.tokens[:700].copy(), np.array([0, 300, 300, 700], np.uint64), big.counts)
