@@ -245,19 +245,35 @@ __device__ __forceinline__ void row_store_vec(__amdgpu_buffer_rsrc_t rs, int lan
 }
 
 // bfloat16 storage: a row of dim elements of 2 bytes.  A chunk of VW elements is one 2-, 4- or 8-byte access; a
-// stored value is the upper half of the float's bit pattern.
+// stored value is the upper half of the float's bit pattern.  A load leaves the chunk's words as they are in the
+// first registers of the chunk (a row that has been requested but not yet arrived must not be touched: widening it at
+// once would put a wait for the data right behind every load and no prefetch would hide anything); widen_chunk
+// turns them into floats where the row is first needed.
 template <int VW>
 __device__ __forceinline__ void row_load_bf16(__amdgpu_buffer_rsrc_t rs, int lane_bytes, float *dst)
 {
     if constexpr (VW == 1) {
-        dst[0] = __uint_as_float((uint32_t)__builtin_amdgcn_raw_buffer_load_b16(rs, lane_bytes, 0, 0) << 16);
+        dst[0] = __uint_as_float((uint32_t)__builtin_amdgcn_raw_buffer_load_b16(rs, lane_bytes, 0, 0));
     } else if constexpr (VW == 2) {
-        const uint32_t t = __builtin_amdgcn_raw_buffer_load_b32(rs, lane_bytes, 0, 0);
-        dst[0] = __uint_as_float(t << 16); dst[1] = __uint_as_float(t & 0xFFFF0000u);
+        dst[0] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, lane_bytes, 0, 0));
     } else {
         const vec2u t = __builtin_amdgcn_raw_buffer_load_b64(rs, lane_bytes, 0, 0);
-        dst[0] = __uint_as_float(t.x << 16); dst[1] = __uint_as_float(t.x & 0xFFFF0000u);
-        dst[2] = __uint_as_float(t.y << 16); dst[3] = __uint_as_float(t.y & 0xFFFF0000u);
+        dst[0] = __uint_as_float(t.x); dst[1] = __uint_as_float(t.y);
+    }
+}
+// dst[0 .. VW) = the floats of the chunk whose words lie in src[0 .. (VW+1)/2); dst may be src
+template <int VW>
+__device__ __forceinline__ void widen_chunk(float *dst, const float *src)
+{
+    if constexpr (VW == 1) {
+        dst[0] = __uint_as_float(__float_as_uint(src[0]) << 16);
+    } else if constexpr (VW == 2) {
+        const uint32_t w = __float_as_uint(src[0]);
+        dst[1] = __uint_as_float(w & 0xFFFF0000u); dst[0] = __uint_as_float(w << 16);
+    } else {
+        const uint32_t w0 = __float_as_uint(src[0]), w1 = __float_as_uint(src[1]);
+        dst[3] = __uint_as_float(w1 & 0xFFFF0000u); dst[2] = __uint_as_float(w1 << 16);
+        dst[1] = __uint_as_float(w0 & 0xFFFF0000u); dst[0] = __uint_as_float(w0 << 16);
     }
 }
 // Stochastic rounding of a working value to bfloat16: 16 random bits are added to the float's bit pattern and the
@@ -482,6 +498,16 @@ train_kernel(KernelArgs A)
     auto load_ctx = [&](uint32_t word, float *dst) { load_row(A.syn0, word, dst); };
     auto load_out = [&](uint32_t word, float *dst) { load_row(A.syn1neg, word, dst); };
     auto store_out = [&](uint32_t word, const float *src, uint64_t sbits) { store_row(A.syn1neg, word, src, sbits); };
+    // bfloat16 storage: a fetched row (words as loaded) becomes floats, in place or on its way into another row
+    auto widen_into = [&](float *dst, const float *src) {
+        if constexpr (BF16) {
+            chunks([&](auto r_, auto w_, auto o_) {
+                constexpr int CW = decltype(w_)::value, RO = decltype(o_)::value;
+                widen_chunk<CW>(dst + RO, src + RO);
+            });
+        }
+    };
+    auto widen_row = [&](float *row) { widen_into(row, row); };
     auto ring_to_regs = [&](const float *lrow, float *dst) {      // LDS ring row -> registers
         chunks([&](auto r_, auto w_, auto o_) {
             constexpr int r = decltype(r_)::value, CW = decltype(w_)::value, RO = decltype(o_)::value;
@@ -822,6 +848,7 @@ train_kernel(KernelArgs A)
                     if (ring_enter(n_ins, word, slot)) {
                         float t[E];
                         load_ctx((uint32_t)word, t);
+                        widen_row(t);
                         regs_to_ring(ring + (size_t)slot * ROWF, t);
                         if (sum_ring) snap_store(slot, t);
                     }
@@ -849,6 +876,10 @@ train_kernel(KernelArgs A)
             // wait-count bookkeeping merges the paths conservatively, and every window gets a full vmcnt(0) in front of
             // its first multiply-add: right behind the prefetch of the next window's rows, which then hides nothing.
             __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0), the other counters left alone
+            if constexpr (BF16 && !TWO) {
+#pragma unroll
+                for (int kk = 0; kk < KC; ++kk) widen_row(O[kk]);
+            }
 
             for (uint32_t j = 0; j < nwin; ++j) {
                 const uint32_t i = i0 + j;
@@ -878,6 +909,12 @@ train_kernel(KernelArgs A)
                 } else if constexpr (BF16) {
                     win_draw = leave_draw(i);
                     if (i >= W) leave_draw_j = leave_draw(i - W);
+                }
+                // bfloat16 storage, two passes: the window's first batch of rows was fetched into O as words (between the
+                // passes of the window before, or at the chunk start) and becomes floats here
+                if constexpr (BF16 && TWO) {
+#pragma unroll
+                    for (int kk = 0; kk < KC; ++kk) widen_row(O[kk]);
                 }
                 // (a) ask LDS for the next window's scalars now, use them after the ring work below
                 uint4 mraw_next = make_uint4(0u, 0u, kNoWord, 0u);
@@ -954,6 +991,7 @@ train_kernel(KernelArgs A)
                 auto arrivals_before_stores = [&](bool window_done) {
                     __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0), the other counters left alone
                     if (pend) {
+                        widen_row(pend_row);
                         regs_to_ring(ring + (size_t)pend_slot * ROWF, pend_row);
                         if (sum_ring) snap_store(pend_slot, pend_row);
                         pend = false;
@@ -1202,6 +1240,10 @@ train_kernel(KernelArgs A)
                         // window wait for it)
                         run_pass(0u, O, packv, true, false);
                         fetch_next_window(O);
+                        if constexpr (BF16) {
+#pragma unroll
+                            for (int kk = 0; kk < KC; ++kk) widen_row(On[kk]);
+                        }
                         run_pass((uint32_t)KC, On, pv2, false, true);
                     } else {
                         for (uint32_t kb = 0; kb <= N; kb += KC) {
@@ -1281,6 +1323,7 @@ train_kernel(KernelArgs A)
                 // (h) the fetched context row enters the ring, the oldest position leaves it
                 //     (every lane only touches its own elements of a ring row: no barrier needed)
                 if (pend) {
+                    widen_row(pend_row);
                     regs_to_ring(ring + (size_t)pend_slot * ROWF, pend_row);
                     if (sum_ring) snap_store(pend_slot, pend_row);
                 }
@@ -1301,9 +1344,14 @@ train_kernel(KernelArgs A)
                             for (int x = 0; x < E; ++x) O[0][x] = On[0][x];
                         } else {
 #pragma unroll
-                            for (int kk = 0; kk < KC; ++kk)
+                            for (int kk = 0; kk < KC; ++kk) {
+                                if constexpr (BF16) {
+                                    widen_into(O[kk], On[kk]);        // the rows arrive as words and become floats here
+                                } else {
 #pragma unroll
-                                for (int x = 0; x < E; ++x) O[kk][x] = On[kk][x];
+                                    for (int x = 0; x < E; ++x) O[kk][x] = On[kk][x];
+                                }
+                            }
                         }
                     }
                 }
