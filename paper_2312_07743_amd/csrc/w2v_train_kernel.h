@@ -106,6 +106,21 @@ __device__ __forceinline__ void row_stage(const float *in, float *out, int lane)
     for (int i = 0; i < OUT; ++i) {
         if (i + BIT < IN) {
             const float a = in[i], b = in[i + BIT];
+            if constexpr (BIT == 8 || BIT == 4) {
+                // Lanes whose BIT is clear continue with a (own + partner's), the others with b: two adds that take
+                // the partner's value through the DPP operand and write disjoint banks of four lanes (bank_mask),
+                // instead of two selects and an add.  The s_nop covers the two wait states a DPP read needs after
+                // the write of its register (the compiler does not look into the statement).
+                float o;
+                if constexpr (BIT == 8)
+                    asm volatile("s_nop 1\n\tv_add_f32_dpp %0, %1, %1 row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
+                                 "v_add_f32_dpp %0, %2, %2 row_ror:8 row_mask:0xf bank_mask:0xc" : "=&v"(o) : "v"(a), "v"(b));
+                else
+                    asm volatile("s_nop 1\n\tv_add_f32_dpp %0, %1, %1 row_half_mirror row_mask:0xf bank_mask:0x5\n\t"
+                                 "v_add_f32_dpp %0, %2, %2 row_half_mirror row_mask:0xf bank_mask:0xa" : "=&v"(o) : "v"(a), "v"(b));
+                out[i] = o;
+                continue;
+            }
             const float mine = up ? b : a;
             const float theirs = up ? a : b;
             out[i] = mine + dpp_move<CTRL>(theirs);
