@@ -209,10 +209,12 @@ bool pick_row_shape(uint32_t dim, uint32_t ld, RowShape *out)
 uint32_t train_lds_bytes(const KernelArgs &a, RowShape s, int update)
 {
     const uint32_t rowf = kLanes * floats_per_lane(s);
-    // ring, kept-token FIFO, per-window scalars, negatives; bfloat16 storage: the rounding draws of 64 windows
     const int kmode = a.negatives + 1 > 2u * KC ? 3 : a.negatives + 1 > (uint32_t)KC ? 2 : a.negatives + 1 == (uint32_t)KC ? 1 : 0;
-    return (2 * a.window + 3) * rowf * 4u + FCAP * 8u + kLanes * 32u + kLanes * a.negatives * 4u +
-           (update == 2 && rounding_draws_in_lds(kmode) ? kLanes * 16u : 0u);
+    const uint32_t chunk = (uint32_t)chunk_windows(floats_per_lane(s), wcap_of(a.window), update == 1);
+    const uint32_t fifo = (uint32_t)fifo_entries(floats_per_lane(s), wcap_of(a.window), update == 1);
+    // ring, kept-token FIFO, per-window scalars, negatives; bfloat16 storage: the rounding draws of the chunk's windows
+    return (2 * a.window + 3) * rowf * 4u + fifo * 8u + chunk * 32u + chunk * a.negatives * 4u +
+           (update == 2 && rounding_draws_in_lds(kmode) ? chunk * 16u : 0u);
 }
 
 hipError_t launch_init_weights(void *syn0, void *syn1neg, uint32_t vocab, uint32_t dim, uint32_t ld,

@@ -25,7 +25,17 @@ namespace {
 constexpr int kLanes = 64;
 constexpr int KC = 6;              // output rows held in registers at once
 constexpr int CC = 10;             // most context rows whose pairings are reduced together (CC*KC <= 64)
-constexpr int FCAP = 256;          // kept-token FIFO entries per wavefront (power of two)
+constexpr int FCAP = 256;          // kept-token FIFO entries per wavefront (power of two) of most shapes
+// Windows sampled at a time and FIFO entries by shape (e: floats of a row per lane, wcap: widest window of the
+// instantiation, summed: the summed-update variant).  Two kinds of shape sample 32 windows at a time into a FIFO of 128,
+// because the 2.7 to 3.3 KB of LDS this saves lets a CU hold more wavefronts: rows of five floats per lane (d = 260..320;
+// ring of 16.6 KB at W <= 5: 8 instead of 7 wavefronts per CU), and rows of two floats per lane with windows up to 10
+// (d = 65..128; ring of 11.8 KB: 11 instead of 9; not the summed variant, whose registers limit it to 8 anyway).  The
+// price is a sampling stage that runs half empty.  The FIFO holds the kept positions from W before the chunk's first
+// window to the last one scanned: at most chunk + 2W + 64 entries.
+constexpr int wcap_of(uint32_t window) { return window <= 5 ? 5 : window <= 10 ? 10 : 16; }
+constexpr int chunk_windows(int e, int wcap, bool summed) { return ((e == 5 && wcap <= 10) || (e == 2 && wcap == 10 && !summed)) ? 32 : 64; }
+constexpr int fifo_entries(int e, int wcap, bool summed) { return chunk_windows(e, wcap, summed) == 32 ? 128 : FCAP; }
 constexpr uint32_t kIdBits = 27;
 constexpr uint32_t kIdMask = (1u << kIdBits) - 1u;
 
@@ -375,6 +385,8 @@ train_kernel(KernelArgs A)
     constexpr int E = VW * R + TAIL;     // floats of a row per lane
     constexpr int NCH = R + TAIL;        // chunks of a row per lane: R of VW floats, then TAIL single floats
     constexpr int ROWF = kLanes * E;     // floats of a ring row in LDS
+    constexpr int CHUNK = chunk_windows(E, WCAP, SUMMED);   // windows sampled at a time (one per lane)
+    constexpr int FQ = fifo_entries(E, WCAP, SUMMED);       // kept-token FIFO entries
     constexpr int NCTX = 2 * WCAP;       // context positions a window can have
     constexpr bool MULTI = KMODE >= 2;   // output rows beyond the first KC are handled in further passes
     constexpr bool TWO = KMODE == 2;     // ... in exactly one further pass (KC < N + 1 <= 2 KC)
@@ -393,13 +405,13 @@ train_kernel(KernelArgs A)
     float *ring = reinterpret_cast<float *>(lds_raw);
     // ring row `nslots` is never assigned to a word: it holds zeros and stands in for context slots that do not exist
     int32_t *kw = reinterpret_cast<int32_t *>(ring + (size_t)(nslots + 1) * ROWF);  // kept word ids (FIFO)
-    uint32_t *kp = reinterpret_cast<uint32_t *>(kw + FCAP);                  // their offsets in the sentence
-    uint4 *cb_meta = reinterpret_cast<uint4 *>(kp + FCAP);                   // per-window scalars of the chunk
-    uint32_t *cb_cm = reinterpret_cast<uint32_t *>(cb_meta + kLanes);        // [64][4] context multiplicities, 4 bits per slot
-    uint32_t *cb_pack = cb_cm + 4 * kLanes;                                  // [64][N] negative id | multiplicity<<27
+    uint32_t *kp = reinterpret_cast<uint32_t *>(kw + FQ);                  // their offsets in the sentence
+    uint4 *cb_meta = reinterpret_cast<uint4 *>(kp + FQ);                   // per-window scalars of the chunk
+    uint32_t *cb_cm = reinterpret_cast<uint32_t *>(cb_meta + CHUNK);        // [64][4] context multiplicities, 4 bits per slot
+    uint32_t *cb_pack = cb_cm + 4 * CHUNK;                                  // [64][N] negative id | multiplicity<<27
     // bfloat16 storage: [64] the 64-bit draws that key the roundings of a window: of its centre (output rows) and of
     // the position that leaves the span after it (that position's context row)
-    uint4 *cb_rnd = reinterpret_cast<uint4 *>(cb_pack + (size_t)kLanes * A.negatives);
+    uint4 *cb_rnd = reinterpret_cast<uint4 *>(cb_pack + (size_t)CHUNK * A.negatives);
 
     // A lane's share of a row: chunk r < R is VW consecutive floats at (r*64 + lane)*VW, chunk R + t is the
     // single float at 64*VW*R + t*64 + lane.  `chunks` calls f(chunk index, its width, its place in a register row).
@@ -647,7 +659,7 @@ train_kernel(KernelArgs A)
         // window loop the sampling stage has computed it (lane-parallel), here it is formed by the scalar unit
         auto leave_draw = [&](uint32_t p) -> uint64_t {
             if constexpr (!BF16) return 0ull;
-            else return draw_u64(position_base(A.key, A.first_pos + t0 + uni(kp[p & (FCAP - 1)])), 64u);
+            else return draw_u64(position_base(A.key, A.first_pos + t0 + uni(kp[p & (FQ - 1)])), 64u);
         };
         auto leave_finish = [&](uint32_t slot, uint32_t word, bool summed, const float *fresh, const float *snapv, uint64_t sbits) {
             float t[E];
@@ -672,7 +684,7 @@ train_kernel(KernelArgs A)
 
         for (;;) {
             // ---- look at more tokens until this chunk's windows know all their context ----------
-            while (n_prod < i0 + kLanes + W + 1 && raw_next < len) {
+            while (n_prod < i0 + CHUNK + W + 1 && raw_next < len) {
                 const uint32_t off = raw_next + lane;
                 bool k = false, bad = false;
                 int32_t w = -1;
@@ -681,8 +693,8 @@ train_kernel(KernelArgs A)
                 const uint64_t km = __ballot(k);
                 if (k) {
                     const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(km >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)km, 0u));
-                    kw[(n_prod + rank) & (FCAP - 1)] = w;
-                    kp[(n_prod + rank) & (FCAP - 1)] = off;
+                    kw[(n_prod + rank) & (FQ - 1)] = w;
+                    kp[(n_prod + rank) & (FQ - 1)] = off;
                 }
                 n_own += (uint32_t)__popcll(__ballot(k && off < u1));
                 n_prod += (uint32_t)__popcll(km);
@@ -690,7 +702,7 @@ train_kernel(KernelArgs A)
             }
             __syncthreads();
             if (i0 >= n_own) break;
-            const uint32_t nwin = (n_own - i0 < (uint32_t)kLanes) ? n_own - i0 : (uint32_t)kLanes;
+            const uint32_t nwin = (n_own - i0 < (uint32_t)CHUNK) ? n_own - i0 : (uint32_t)CHUNK;
 
             // ---- width and negatives of the chunk's windows, one window per lane ----------------
             // Negative k of a window carries a multiplicity: 0 if it equals the target or an earlier negative,
@@ -702,7 +714,7 @@ train_kernel(KernelArgs A)
             uint32_t nid[NREG ? KC - 1 : 1] = {}, nmult[NREG ? KC - 1 : 1] = {};
             const bool have = (uint32_t)lane < nwin;
             if (have) {
-                const uint32_t idx = (i0 + lane) & (FCAP - 1);
+                const uint32_t idx = (i0 + lane) & (FQ - 1);
                 my_w = kw[idx];
                 const uint32_t my_off = kp[idx];
                 const uint64_t base = position_base(A.key, A.first_pos + t0 + my_off);
@@ -711,7 +723,7 @@ train_kernel(KernelArgs A)
                     const uint64_t d_own = draw_u64(base, 64u);
                     uint64_t d_leave = 0ull;
                     const uint32_t me = i0 + lane;
-                    if (me >= W) d_leave = draw_u64(position_base(A.key, A.first_pos + t0 + kp[(me - W) & (FCAP - 1)]), 64u);
+                    if (me >= W) d_leave = draw_u64(position_base(A.key, A.first_pos + t0 + kp[(me - W) & (FQ - 1)]), 64u);
                     cb_rnd[lane] = make_uint4((uint32_t)d_own, (uint32_t)(d_own >> 32), (uint32_t)d_leave, (uint32_t)(d_leave >> 32));
                 }
                 // negatives: drawn at my own position, or at the first position of my stretch of 2^neg_shift tokens
@@ -720,7 +732,7 @@ train_kernel(KernelArgs A)
                 if (dump) { A.dump.keep[t0 + my_off] = 1; A.dump.width[t0 + my_off] = (uint8_t)my_b; }
                 const uint64_t nbase = A.neg_shift ? position_base(A.key, A.first_pos + t0 + (my_stretch << A.neg_shift)) : base;
                 const uint32_t pe = i0 + lane + W + 1;
-                if (pe < n_prod) my_enter = (uint32_t)kw[pe & (FCAP - 1)];
+                if (pe < n_prod) my_enter = (uint32_t)kw[pe & (FQ - 1)];
                 uint32_t *pk = cb_pack + (size_t)lane * N;
                 my_plain = 1u;
                 if constexpr (NREG) {
@@ -762,7 +774,7 @@ train_kernel(KernelArgs A)
             if (have) {
                 // which of my first KC output rows does the previous window also write?
                 if (lane > 0) {
-                    const uint32_t pw = (uint32_t)kw[(i0 + lane - 1) & (FCAP - 1)];
+                    const uint32_t pw = (uint32_t)kw[(i0 + lane - 1) & (FQ - 1)];
                     const uint32_t *prev = cb_pack + (size_t)(lane - 1) * N;
                     if constexpr (NREG) {
                         uint32_t pid[KC];           // rows the previous window writes (others: an id no word has)
@@ -809,7 +821,7 @@ train_kernel(KernelArgs A)
                     const uint32_t p = (c & 1) ? me + a : me - a;
                     const bool ok = a <= my_b && ((c & 1) ? p < n_prod : me >= a);
                     sw[c] = -2 - c;
-                    if (ok) { sw[c] = kw[p & (FCAP - 1)]; exist |= 1u << c; }
+                    if (ok) { sw[c] = kw[p & (FQ - 1)]; exist |= 1u << c; }
                 }
                 uint32_t cm[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
@@ -858,7 +870,7 @@ train_kernel(KernelArgs A)
             if (i0 == 0) {
                 const uint32_t want = (W + 1 < n_prod) ? W + 1 : n_prod;
                 while (n_ins < want) {
-                    const int32_t word = (int32_t)uni((uint32_t)kw[n_ins & (FCAP - 1)]);
+                    const int32_t word = (int32_t)uni((uint32_t)kw[n_ins & (FQ - 1)]);
                     uint32_t slot;
                     if (ring_enter(n_ins, word, slot)) {
                         float t[E];
