@@ -30,11 +30,16 @@ constexpr int FCAP = 256;          // kept-token FIFO entries per wavefront (pow
 // instantiation, summed: the summed-update variant).  Two kinds of shape sample 32 windows at a time into a FIFO of 128,
 // because the 2.7 to 3.3 KB of LDS this saves lets a CU hold more wavefronts: rows of five floats per lane (d = 260..320;
 // ring of 16.6 KB at W <= 5: 8 instead of 7 wavefronts per CU), and rows of two floats per lane with windows up to 10
-// (d = 65..128; ring of 11.8 KB: 11 instead of 9; not the summed variant, whose registers limit it to 8 anyway).  The
+// (d = 65..128; ring of 11.8 KB: 11 instead of 9).  The
 // price is a sampling stage that runs half empty.  The FIFO holds the kept positions from W before the chunk's first
 // window to the last one scanned: at most chunk + 2W + 64 entries.
+// Context rows whose pairings are reduced together.  The summed width-10 kernel of rows of two floats per lane takes 5
+// at a time (a second or third reduction for windows wider than 2, but 40 registers fewer): it then fits 3 wavefronts
+// per SIMD without a spill on the window path, and 11 per CU instead of 8 hide its waits better (walk workload 172 ->
+// 164 ms per epoch).
+constexpr int block_slots(int e, int wcap, bool summed) { return (summed && wcap == 10 && e == 2) ? 5 : CC; }
 constexpr int wcap_of(uint32_t window) { return window <= 5 ? 5 : window <= 10 ? 10 : 16; }
-constexpr int chunk_windows(int e, int wcap, bool summed) { return ((e == 5 && wcap <= 10) || (e == 2 && wcap == 10 && !summed)) ? 32 : 64; }
+constexpr int chunk_windows(int e, int wcap, bool summed) { (void)summed; return ((e == 5 && wcap <= 10) || (e == 2 && wcap == 10)) ? 32 : 64; }
 constexpr int fifo_entries(int e, int wcap, bool summed) { return chunk_windows(e, wcap, summed) == 32 ? 128 : FCAP; }
 constexpr uint32_t kIdBits = 27;
 constexpr uint32_t kIdMask = (1u << kIdBits) - 1u;
@@ -365,11 +370,9 @@ constexpr uint32_t kNoWord = 0xFFFFFFFFu;
 // gain 17 % from 4 per SIMD (128 VGPRs, 16 spilled), 5 spills 56; rows of two floats gain nothing from 4
 // because LDS then limits the CU; 3 for rows of 4 floats per lane spills)
 constexpr bool rounding_draws_in_lds(int kmode) { return kmode <= 1; }
-// (the summed width-10 kernel of rows of two floats per lane spilled 72 registers at 3 per SIMD; its ring limits a CU
-// to 9 wavefronts anyway: at 2 per SIMD it spills none and the walk workload runs 5 % faster on 8 per CU)
 constexpr int occupancy_goal(int e, int wcap, bool summed = false)
 {
-    if (summed && wcap > 5 && e == 2) return 2;
+    (void)summed;
     return (e == 1 && wcap <= 5) ? 4 : (e <= 2 && wcap <= 10) ? 3 : ((e * wcap <= 25) ? 2 : 1);
 }
 
@@ -385,6 +388,7 @@ train_kernel(KernelArgs A)
     constexpr int E = VW * R + TAIL;     // floats of a row per lane
     constexpr int NCH = R + TAIL;        // chunks of a row per lane: R of VW floats, then TAIL single floats
     constexpr int ROWF = kLanes * E;     // floats of a ring row in LDS
+    constexpr int CCK = block_slots(E, WCAP, SUMMED);   // most context rows reduced together
     constexpr int CHUNK = chunk_windows(E, WCAP, SUMMED);   // windows sampled at a time (one per lane)
     constexpr int FQ = fifo_entries(E, WCAP, SUMMED);       // kept-token FIFO entries
     constexpr int NCTX = 2 * WCAP;       // context positions a window can have
@@ -1038,7 +1042,7 @@ train_kernel(KernelArgs A)
                     constexpr bool MASKED = decltype(general_tag)::value;
                     constexpr bool GENERAL = MASKED;
                     // the NCW slots are handled in NQW blocks of nearly equal size (BASE or BASE+1 slots)
-                    constexpr int NQW = (NCW + CC - 1) / CC;
+                    constexpr int NQW = (NCW + CCK - 1) / CCK;
                     constexpr int BASE = NCW / NQW, REM = NCW % NQW;
                     // Straight-line windows whose output rows are handled in one pass take the context rows out of
                     // the ring block by block (fewer rows live at a time): no two slots that take part share a row,
@@ -1103,9 +1107,9 @@ train_kernel(KernelArgs A)
                             if constexpr (SUMMED && q == NQW - 1) load_fresh();
                             if constexpr (LOAD_PER_BLOCK)
                                 static_for<NC>([&](auto cc_tag) { fetch_slot(std::integral_constant<int, C0 + decltype(cc_tag)::value>{}); });
-                            float acc[CC * KC];
+                            float acc[CCK * KC];
 #pragma unroll
-                            for (int cc = 0; cc < CC; ++cc) {
+                            for (int cc = 0; cc < CCK; ++cc) {
                                 const int c = C0 + cc;
 #pragma unroll
                                 for (int kk = 0; kk < KC; ++kk) {
@@ -1147,7 +1151,7 @@ train_kernel(KernelArgs A)
                             // sweep over the block forms (one sweep for both, except the summed mode's last block)
                             auto sweep = [&](auto do_i_tag, auto do_o_tag) {
                             constexpr bool DO_I = decltype(do_i_tag)::value, DO_O = decltype(do_o_tag)::value;
-                            static_for<CC>([&](auto cc_tag) {
+                            static_for<CCK>([&](auto cc_tag) {
                                 constexpr int cc = decltype(cc_tag)::value;
                                 constexpr int c = C0 + cc;
                                 if constexpr (cc < NC) if (!MASKED || ((amask >> c) & 1u)) {
