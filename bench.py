@@ -133,7 +133,7 @@ def main():
                          "default run of the mid workload adds as `other_workloads`")
     ap.add_argument("--naive", action="store_true",
                     help="time the no-reuse comparator kernel instead of the window kernel (traffic comparison only)")
-    ap.add_argument("--cpu-sentences", type=int, default=2500)
+    ap.add_argument("--cpu-sentences", type=int, default=5000)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy three times (scale for the rocprofv3 byte counters)")
     args = ap.parse_args()
