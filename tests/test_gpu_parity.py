@@ -272,6 +272,26 @@ def test_corpus_passed_as_one_long_sentence(orc32):
     assert r_one[3] > r_cut[3]
 
 
+@pytest.mark.parametrize("shape", [dict(dim=128, window=10, negatives=5), dict(dim=300, window=5, negatives=10),
+                                   dict(dim=300, window=9, negatives=5), dict(dim=100, window=10, negatives=7)])
+def test_shapes_that_sample_32_windows_at_a_time(orc32, shape):
+    """Rows of five floats per lane, and rows of two floats per lane with windows up to 10, sample 32 instead of 64
+    windows at a time into a kept-token FIFO of 128 entries (their ring leaves less LDS): one sentence of 6,000 tokens
+    (the FIFO wraps about fifty times), subsampled, as one unit and cut into 16 stretches, and ragged short sentences
+    around the chunk size."""
+    c0 = synth.zipf_corpus(600, 1.05, 6, 1000, seed=33)
+    one = synth.Corpus(c0.tokens, np.array([0, c0.n_tokens], np.uint64), c0.counts)
+    kw = dict(seed=19, table_size=1 << 16, subsample_t=5e-3, **shape)
+    _parity(orc32, one, unit_shift=0, **kw)
+    _parity(orc32, one, unit_shift=4, **kw)
+    rng = np.random.default_rng(5)
+    lens = [31, 32, 33, 63, 64, 65, 95, 96, 97, 127, 128, 129, 1, 0, 2, 160, 400]
+    tok = rng.integers(0, 200, size=sum(lens)).astype(np.int32)
+    off = np.cumsum([0] + lens).astype(np.uint64)
+    ragged = synth.Corpus(tok, off, np.bincount(tok, minlength=200).astype(np.uint64))
+    _parity(orc32, ragged, seed=23, table_size=4099, **shape)
+
+
 def test_repeated_context_words(orc32):
     # walks that step back and stay: most windows hold a word at several context positions (one ring row,
     # counted with its multiplicity); a run of one word fills more than 15 slots of a wide window
