@@ -206,7 +206,7 @@ def test_bf16_initial_weights_are_the_nearest_bf16_of_the_float_ones(orc32):
     tr.close()
 
 
-@pytest.mark.parametrize("shape", ["d128", "d64_w10", "d256_n10", "d300_n10_subsampled", "d100_fixed_shared"])
+@pytest.mark.parametrize("shape", ["d128", "d64_w10", "d128_w10", "d256_n10", "d300_n10_subsampled", "d100_fixed_shared"])
 def test_bf16_storage_in_strict_order_matches_the_oracle(orc32, orc64, shape):
     if shape == "d128":
         c = synth.zipf_corpus(500, 1.0, 8, 400, seed=3)
@@ -214,6 +214,9 @@ def test_bf16_storage_in_strict_order_matches_the_oracle(orc32, orc64, shape):
     elif shape == "d64_w10":
         c = synth.barabasi_albert_walks(n_nodes=40, m=5, walks_per_node=1, walk_len=80, seed=4)     # a short run: see above
         kw = dict(dim=64, window=10, negatives=5, seed=23, table_size=1 << 18)
+    elif shape == "d128_w10":                      # 32 windows sampled at a time, their rounding draws kept in LDS
+        c = synth.barabasi_albert_walks(n_nodes=60, m=5, walks_per_node=1, walk_len=80, seed=9)
+        kw = dict(dim=128, window=10, negatives=5, seed=29, table_size=1 << 18)
     elif shape == "d256_n10":
         c = synth.zipf_corpus(800, 1.1, 6, 400, seed=13)
         kw = dict(dim=256, window=7, negatives=10, seed=5, table_size=1 << 16)
